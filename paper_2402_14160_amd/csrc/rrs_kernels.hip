@@ -1,0 +1,657 @@
+// Recursive rejection sampling over the draft tree (Sec. 3.1; Sec. 3.2.2; Alg. 6).
+//
+// A sibling group (the children x_1..x_K of one node) is verified by one
+// workgroup.  The residual distributions q^(k) of Eq. (2) are never stored:
+// with e_t(x) = 2^(zt(x) - max zt), e_d(x) = 2^(zd(x) - max zd) (log2 domain),
+//   q^(1)(x)   = e_t(x) / s_t
+//   p^(k)(x)   = e_d(x) / s_k          for x not in {x_1..x_{k-1}}, else 0
+//   q^(k+1)(x) = max(q^(k)(x) - p^(k)(x), 0) / S_k,   S_k = sum_x max(q^(k) - p^(k), 0)
+// so every stage is one read-only pass over the two logit rows that evaluates a
+// short per-entry chain from the scalars (s_t, s_1.., S_1..) found so far.
+// s_k sums the draft row without the removed tokens directly (no 1 - p
+// cancellation).  Sums are accumulated per lane in fp32, across lanes in fp64
+// in a fixed order, so results do not depend on scheduling.
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <math.h>
+
+#include "../../include/rsd.h"
+#include "rsd_device.hpp"
+
+namespace rsd {
+
+constexpr int kGroupThreads = 512;
+constexpr int kGroupWaves = kGroupThreads / kWave;
+constexpr int kFinalThreads = 512;
+constexpr int kFinalSplits = 8;
+
+// Per (sequence, node) record produced by the group pass, kept in workspace.
+struct GroupRec {
+    float mt2;      // max of target row, log2 domain
+    float md2;      // max of draft row, log2 domain
+    float inv_st;   // 1 / sum_x 2^(zt2 - mt2)
+    int K;          // number of verified children (<= RSD_K_MAX); 0 for a leaf
+    uint32_t flags;
+    int pad[3];
+    int kid[RSD_K_MAX];      // child node ids in stored order
+    int tok[RSD_K_MAX];      // their tokens
+    float inv_s[RSD_K_MAX];  // 1 / s_k (draft mass left at stage k); 0 marks a skipped stage
+    float inv_S[RSD_K_MAX];  // 1 / S_k (1 for a skipped stage)
+    float theta[RSD_K_MAX];
+};
+
+struct RrsArgs {
+    const float *zd;
+    const float *zt;
+    int B, N, V;
+    float inv_t;   // 1/T
+    float c2;      // log2(e)/T
+    const int *tokens;
+    const int *parent;
+    const int *n_nodes;
+    const int *seq_id;
+    uint64_t seed;
+    uint32_t step;
+    int *accepted_nodes;
+    int *accepted_tokens;
+    int depth_max;
+    int *n_accepted;
+    int *last_token;
+    int *final_node;
+    float *theta;
+    float *uniforms;
+    uint32_t *flags;
+    // workspace
+    GroupRec *rec;              // [B, N]
+    unsigned long long *fkey;   // [B, 2] packed (score, token) maxima: residual / fallback
+    int *fdone;                 // [B]
+    int *fnode;                 // [B]
+    uint32_t *fflags;           // [B]
+};
+
+__device__ __forceinline__ int removal_stage(int x, const int *tok, int K) {
+    int rs = K;
+    for (int i = K - 1; i >= 0; --i)
+        if (tok[i] == x) rs = i;
+    return rs;
+}
+
+__device__ __forceinline__ float uniform_f(float v) {
+    return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
+}
+
+// The group's scalars pulled into (scalar) registers once per pass so that the
+// per-entry chain indexes them statically.
+struct ChainRegs {
+    float mt2, md2, inv_st;
+    float is[RSD_K_MAX];
+    float iS[RSD_K_MAX];
+};
+
+__device__ __forceinline__ ChainRegs load_chain(const GroupRec &g) {
+    ChainRegs r;
+    r.mt2 = uniform_f(g.mt2);
+    r.md2 = uniform_f(g.md2);
+    r.inv_st = uniform_f(g.inv_st);
+#pragma unroll
+    for (int j = 0; j < RSD_K_MAX; ++j) {
+        r.is[j] = uniform_f(g.inv_s[j]);
+        r.iS[j] = uniform_f(g.inv_S[j]);
+    }
+    return r;
+}
+
+// q^(nst+1) for four entries none of which is a child token.
+__device__ __forceinline__ void chain4(const float et[4], const float ed[4], const ChainRegs &r,
+                                       int nst, float q[4]) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i) q[i] = et[i] * r.inv_st;
+#pragma unroll
+    for (int j = 0; j < RSD_K_MAX - 1; ++j) {
+        if (j >= nst) break;
+#pragma unroll
+        for (int i = 0; i < 4; ++i) q[i] = fmaxf(q[i] - ed[i] * r.is[j], 0.f) * r.iS[j];
+    }
+}
+
+// q^(nst+1)(x) when x may be the child token removed at stage rs (rs = K: never).
+__device__ __forceinline__ float chain1_masked(float et, float ed, int rs, const ChainRegs &r,
+                                               int nst) {
+    float q = et * r.inv_st;
+#pragma unroll
+    for (int j = 0; j < RSD_K_MAX - 1; ++j) {
+        if (j >= nst) break;
+        const float p = (rs < j) ? 0.f : ed * r.is[j];
+        q = fmaxf(q - p, 0.f) * r.iS[j];
+    }
+    return q;
+}
+
+// Bit i set: this thread's i-th chunk (c = c_lo + tid + i*THREADS) holds a child token.
+template <int THREADS>
+__device__ __forceinline__ uint64_t child_chunk_mask(const GroupRec &g, int c_lo, int c_hi) {
+    uint64_t m = 0;
+    for (int i = 0; i < g.K; ++i) {
+        const int cc = g.tok[i] >> 2;
+        if (cc >= c_lo && cc < c_hi) {
+            const int rel = cc - c_lo;
+            if (rel % THREADS == (int)threadIdx.x) m |= 1ull << (rel / THREADS);
+        }
+    }
+    return m;
+}
+
+struct GroupShared {
+    GroupRec g;
+    MaxSum ms[kGroupWaves];
+    double red[kGroupWaves];
+    int cur;
+    int done;
+};
+
+// Pass 0: maxima and sums of both rows.  The draft sum leaves out every child token.
+template <int THREADS>
+__device__ void group_lse_pass(const float *zt, const float *zd, int V, float c2, GroupShared &sh) {
+    const int nchunk = V >> 2;
+    const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
+    const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
+    const uint64_t hits = child_chunk_mask<THREADS>(sh.g, 0, nchunk);
+    MaxSum at{-INFINITY, 0.f}, ad{-INFINITY, 0.f};
+    int it = 0;
+#pragma unroll 2
+    for (int c = threadIdx.x; c < nchunk; c += THREADS, ++it) {
+        const float4 t = zt4[c];
+        const float4 d = zd4[c];
+        const float a[4] = {t.x * c2, t.y * c2, t.z * c2, t.w * c2};
+        const float e[4] = {d.x * c2, d.y * c2, d.z * c2, d.w * c2};
+        const float mt = fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3]));
+        const float md = fmaxf(fmaxf(e[0], e[1]), fmaxf(e[2], e[3]));
+        if (mt > at.m) { at.s *= exp2f(at.m - mt); at.m = mt; }
+        if (md > ad.m) { ad.s *= exp2f(ad.m - md); ad.m = md; }
+        if (at.m > -INFINITY)
+            at.s += (exp2f(a[0] - at.m) + exp2f(a[1] - at.m)) + (exp2f(a[2] - at.m) + exp2f(a[3] - at.m));
+        if (ad.m > -INFINITY) {
+            if (!((hits >> it) & 1ull)) {
+                ad.s += (exp2f(e[0] - ad.m) + exp2f(e[1] - ad.m)) + (exp2f(e[2] - ad.m) + exp2f(e[3] - ad.m));
+            } else {
+                for (int i = 0; i < 4; ++i)
+                    if (removal_stage((c << 2) + i, sh.g.tok, sh.g.K) == sh.g.K) ad.s += exp2f(e[i] - ad.m);
+            }
+        }
+    }
+    at = block_merge<THREADS>(at, sh.ms);
+    ad = block_merge<THREADS>(ad, sh.ms);
+    if (threadIdx.x == 0) {
+        sh.g.mt2 = at.m;
+        sh.g.md2 = ad.m;
+        sh.g.inv_st = 1.f / at.s;
+        // draft mass still available at stage k: the rest plus the children not yet removed
+        double e[RSD_K_MAX];
+        for (int i = 0; i < sh.g.K; ++i) e[i] = exp2((double)zd[sh.g.tok[i]] * (double)c2 - (double)ad.m);
+        double s = (double)ad.s;
+        for (int k = RSD_K_MAX - 1; k >= 0; --k) {
+            if (k < sh.g.K) {
+                s += e[k];
+                sh.g.inv_s[k] = (float)(1.0 / s);
+            } else {
+                sh.g.inv_s[k] = 0.f;
+            }
+            sh.g.inv_S[k] = 1.f;
+        }
+        if (!(at.s > 0.f) || !isfinite(at.s) || !(s > 0.0) || !isfinite(s)) sh.g.flags |= RSD_FLAG_NONFINITE;
+    }
+    __syncthreads();
+}
+
+// Stage pass: S = sum_x max(q^(nst+1)(x) - p^(nst+1)(x), 0).
+template <int THREADS>
+__device__ double group_residual_mass(const float *zt, const float *zd, int V, float c2, int nst,
+                                      GroupShared &sh) {
+    const int nchunk = V >> 2;
+    const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
+    const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
+    const GroupRec &g = sh.g;
+    const ChainRegs cr = load_chain(g);
+    const float inv_s = uniform_f(g.inv_s[nst]);
+    const uint64_t hits = child_chunk_mask<THREADS>(g, 0, nchunk);
+    float part = 0.f;
+    int it = 0;
+#pragma unroll 2
+    for (int c = threadIdx.x; c < nchunk; c += THREADS, ++it) {
+        const float4 t = zt4[c];
+        const float4 d = zd4[c];
+        const float et[4] = {exp2f(fmaf(t.x, c2, -cr.mt2)), exp2f(fmaf(t.y, c2, -cr.mt2)),
+                             exp2f(fmaf(t.z, c2, -cr.mt2)), exp2f(fmaf(t.w, c2, -cr.mt2))};
+        const float ed[4] = {exp2f(fmaf(d.x, c2, -cr.md2)), exp2f(fmaf(d.y, c2, -cr.md2)),
+                             exp2f(fmaf(d.z, c2, -cr.md2)), exp2f(fmaf(d.w, c2, -cr.md2))};
+        float r[4];
+        if (!((hits >> it) & 1ull)) {
+            float q[4];
+            chain4(et, ed, cr, nst, q);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = fmaxf(q[i] - ed[i] * inv_s, 0.f);
+        } else {
+            for (int i = 0; i < 4; ++i) {
+                const int rs = removal_stage((c << 2) + i, g.tok, g.K);
+                const float p = (rs < nst) ? 0.f : ed[i] * inv_s;
+                r[i] = fmaxf(chain1_masked(et[i], ed[i], rs, cr, nst) - p, 0.f);
+            }
+        }
+        part += (r[0] + r[1]) + (r[2] + r[3]);
+    }
+    return block_sum<THREADS>((double)part, sh.red);
+}
+
+// Threshold of child k (Eq. (3)) from the scalars found so far, in fp64.
+__device__ double child_theta(const float *zt, const float *zd, float c2, int k, const GroupRec &g) {
+    const int x = g.tok[k];
+    const double et = exp2((double)zt[x] * (double)c2 - (double)g.mt2);
+    const double ed = exp2((double)zd[x] * (double)c2 - (double)g.md2);
+    double q = et * (double)g.inv_st;
+    for (int j = 0; j < k; ++j)  // x_k is not removed before stage k
+        q = fmax(q - ed * (double)g.inv_s[j], 0.0) * (double)g.inv_S[j];
+    const double p = ed * (double)g.inv_s[k];
+    if (!(p > 0.0)) return 1.0;
+    return fmin(1.0, q / p);
+}
+
+// Verify one sibling group: fills sh.g (children, scalars, thresholds).
+// All threads of the workgroup must call this.  Returns with sh.g visible to all.
+template <int THREADS>
+__device__ void process_group(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
+    const int *par = a.parent + (int64_t)b * a.N;
+    const int *tok = a.tokens + (int64_t)b * a.N;
+    if (threadIdx.x == 0) {
+        int K = 0;
+        for (int j = node + 1; j < n && K < RSD_K_MAX; ++j) {
+            if (par[j] == node) {
+                sh.g.kid[K] = j;
+                sh.g.tok[K] = min(max(tok[j], 0), a.V - 1);   // never index outside the row
+                ++K;
+            }
+        }
+        sh.g.K = K;
+        sh.g.flags = 0;
+    }
+    __syncthreads();
+    const int K = sh.g.K;
+    if (K == 0) return;
+    const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
+    const float *zd = a.zd + ((int64_t)b * a.N + node) * a.V;
+    group_lse_pass<THREADS>(zt, zd, a.V, a.c2, sh);
+    for (int k = 0; k < K; ++k) {
+        if (threadIdx.x == 0) sh.g.theta[k] = (float)child_theta(zt, zd, a.c2, k, sh.g);
+        if (k == K - 1) break;
+        __syncthreads();
+        const double S = group_residual_mass<THREADS>(zt, zd, a.V, a.c2, k, sh);
+        if (threadIdx.x == 0) {
+            if (S > 0.0 && isfinite(S)) {
+                sh.g.inv_S[k] = (float)(1.0 / S);
+            } else {  // keep q^(k): no subtraction, no rescale
+                sh.g.inv_s[k] = 0.f;
+                sh.g.inv_S[k] = 1.f;
+                sh.g.flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
+            }
+        }
+        __syncthreads();
+    }
+    __syncthreads();
+}
+
+// ---------------------------------------------------------------------------
+// Last-token sampling (Alg. 6, last lines): arg-max over x of log r(x) + G(x)
+// for entries [x_lo, x_hi) of one node.  r = q^(K+1) (unnormalised) when the
+// node's K children were all rejected, or the target row itself for a leaf.
+// Tracks a second arg-max over q^(K) used when the last residual is empty.
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ unsigned long long pack_key(float v, int idx) {
+    uint32_t bits = __float_as_uint(v);
+    bits = (bits & 0x80000000u) ? ~bits : (bits | 0x80000000u);
+    return ((unsigned long long)bits << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)idx);
+}
+
+template <int THREADS>
+__device__ void final_sample_range(const RrsArgs &a, int b, int node, const GroupRec &g, int c_lo,
+                                   int c_hi, float &best_v, int &best_i, float &alt_v, int &alt_i) {
+    const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
+    const float *zd = a.zd + ((int64_t)b * a.N + node) * a.V;
+    const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
+    const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
+    const uint32_t seq = a.seq_id ? (uint32_t)a.seq_id[b] : (uint32_t)b;
+    const PhiloxKey key = make_key(a.seed);
+    const uint32_t c3 = counter_word3(kTagLastGumbel, a.step);
+    const int K = g.K;
+    best_v = -INFINITY; best_i = INT_MAX; alt_v = -INFINITY; alt_i = INT_MAX;
+    if (K == 0) {
+        for (int c = c_lo + (int)threadIdx.x; c < c_hi; c += THREADS) {
+            const float4 t = zt4[c];
+            const uint4 rnd = philox4x32_10((uint32_t)c, (uint32_t)node, seq, c3, key);
+            const uint32_t wd[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
+            const float tz[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float s = tz[i] * a.inv_t + gumbel_from_word(wd[i]);
+                if (better(s, (c << 2) + i, best_v, best_i)) { best_v = s; best_i = (c << 2) + i; }
+            }
+        }
+        return;
+    }
+    const ChainRegs cr = load_chain(g);
+    const float inv_s_last = uniform_f(g.inv_s[K - 1]);
+    const uint64_t hits = child_chunk_mask<THREADS>(g, c_lo, c_hi);
+    int it = 0;
+    for (int c = c_lo + (int)threadIdx.x; c < c_hi; c += THREADS, ++it) {
+        const float4 t = zt4[c];
+        const float4 d = zd4[c];
+        const uint4 rnd = philox4x32_10((uint32_t)c, (uint32_t)node, seq, c3, key);
+        const uint32_t wd[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
+        const float et[4] = {exp2f(fmaf(t.x, a.c2, -cr.mt2)), exp2f(fmaf(t.y, a.c2, -cr.mt2)),
+                             exp2f(fmaf(t.z, a.c2, -cr.mt2)), exp2f(fmaf(t.w, a.c2, -cr.mt2))};
+        const float ed[4] = {exp2f(fmaf(d.x, a.c2, -cr.md2)), exp2f(fmaf(d.y, a.c2, -cr.md2)),
+                             exp2f(fmaf(d.z, a.c2, -cr.md2)), exp2f(fmaf(d.w, a.c2, -cr.md2))};
+        float q[4], r[4];
+        if (!((hits >> it) & 1ull)) {
+            chain4(et, ed, cr, K - 1, q);                                      // q^(K)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) r[i] = fmaxf(q[i] - ed[i] * inv_s_last, 0.f);  // ~ q^(K+1)
+        } else {
+            for (int i = 0; i < 4; ++i) {
+                const int rs = removal_stage((c << 2) + i, g.tok, K);
+                q[i] = chain1_masked(et[i], ed[i], rs, cr, K - 1);
+                r[i] = fmaxf(q[i] - ((rs < K - 1) ? 0.f : ed[i] * inv_s_last), 0.f);
+            }
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const float gum = gumbel_from_word(wd[i]);
+            const float s = logf(r[i]) + gum;
+            const float s2 = logf(q[i]) + gum;
+            if (better(s, (c << 2) + i, best_v, best_i)) { best_v = s; best_i = (c << 2) + i; }
+            if (better(s2, (c << 2) + i, alt_v, alt_i)) { alt_v = s2; alt_i = (c << 2) + i; }
+        }
+    }
+}
+
+// ---------------------------------------------------------------------------
+// ALL_GROUPS, kernel 1: one workgroup per (node, sequence).
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kGroupThreads) void rrs_group_kernel(RrsArgs a) {
+    __shared__ GroupShared sh;
+    const int node = blockIdx.x;
+    const int b = blockIdx.y;
+    const int n = min(max(a.n_nodes[b], 1), a.N);
+    if (node >= n) return;
+    process_group<kGroupThreads>(a, b, node, n, sh);
+    GroupRec *out = a.rec + (int64_t)b * a.N + node;
+    // copy the record (a few hundred bytes) to workspace
+    const int words = sizeof(GroupRec) / 4;
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(&sh.g);
+    uint32_t *dst = reinterpret_cast<uint32_t *>(out);
+    for (int i = threadIdx.x; i < words; i += kGroupThreads) dst[i] = src[i];
+    if (a.theta) {
+        // children beyond the supported group size are not verified: mark them
+        const int *par = a.parent + (int64_t)b * a.N;
+        const int last = sh.g.K > 0 ? sh.g.kid[sh.g.K - 1] : node;
+        for (int j = last + 1 + (int)threadIdx.x; j < n; j += kGroupThreads)
+            if (par[j] == node) a.theta[(int64_t)b * a.N + j] = NAN;
+        if ((int)threadIdx.x < sh.g.K)
+            a.theta[(int64_t)b * a.N + sh.g.kid[threadIdx.x]] = sh.g.theta[threadIdx.x];
+    }
+}
+
+// The walk itself (one lane), shared by both modes.  `rec_of(node)` must return the
+// verified record of `node`.
+__device__ __forceinline__ float accept_uniform(const RrsArgs &a, int b, int node) {
+    const uint32_t seq = a.seq_id ? (uint32_t)a.seq_id[b] : (uint32_t)b;
+    const uint4 r = philox4x32_10(0u, (uint32_t)node, seq, counter_word3(kTagAcceptUniform, a.step),
+                                  make_key(a.seed));
+    return uniform_from_word(r.x);
+}
+
+// ALL_GROUPS, kernel 2: one wave per sequence walks the tree.
+__global__ __launch_bounds__(kWave) void rrs_walk_kernel(RrsArgs a) {
+    const int b = blockIdx.x;
+    const int lane = threadIdx.x;
+    const int n = min(max(a.n_nodes[b], 1), a.N);
+    for (int j = lane; j < a.N; j += kWave) {
+        if (a.uniforms) a.uniforms[(int64_t)b * a.N + j] = (j < n) ? accept_uniform(a, b, j) : 0.f;
+        if (a.theta && (j == 0 || j >= n)) a.theta[(int64_t)b * a.N + j] = NAN;
+    }
+    for (int j = lane; j < a.depth_max; j += kWave) {
+        a.accepted_nodes[(int64_t)b * a.depth_max + j] = -1;
+        if (a.accepted_tokens) a.accepted_tokens[(int64_t)b * a.depth_max + j] = -1;
+    }
+    __syncthreads();
+    if (lane != 0) return;
+    int cur = 0, nacc = 0;
+    uint32_t flags = 0;
+    for (int guard = 0; guard < a.N; ++guard) {
+        const GroupRec &g = a.rec[(int64_t)b * a.N + cur];
+        const int K = g.K;
+        if (K == 0) break;
+        flags |= g.flags & RSD_FLAG_NONFINITE;
+        int took = -1;
+        for (int k = 0; k < K; ++k) {
+            const float u = accept_uniform(a, b, g.kid[k]);
+            if (u < g.theta[k]) {
+                took = k;
+                break;
+            }
+        }
+        // degenerate stages matter only if their residual was used
+        if (g.flags & RSD_FLAG_DEGENERATE_RESIDUAL) {
+            const int used = took < 0 ? K - 1 : took;
+            for (int j = 0; j < used; ++j)
+                if (g.inv_s[j] == 0.f) flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
+        }
+        if (took < 0) break;
+        if (nacc < a.depth_max) {
+            a.accepted_nodes[(int64_t)b * a.depth_max + nacc] = g.kid[took];
+            if (a.accepted_tokens) a.accepted_tokens[(int64_t)b * a.depth_max + nacc] = g.tok[took];
+        }
+        ++nacc;
+        cur = g.kid[took];
+    }
+    a.n_accepted[b] = nacc;
+    if (a.final_node) a.final_node[b] = cur;
+    a.fnode[b] = cur;
+    a.fflags[b] = flags;
+    a.fkey[2 * b] = 0ull;
+    a.fkey[2 * b + 1] = 0ull;
+    a.fdone[b] = 0;
+}
+
+// ALL_GROUPS, kernel 3: last token; the vocabulary is split over kFinalSplits workgroups.
+__global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
+    __shared__ GroupRec g;
+    __shared__ float s_v[kFinalThreads / kWave];
+    __shared__ int s_i[kFinalThreads / kWave];
+    __shared__ int s_last;
+    const int b = blockIdx.y;
+    const int split = blockIdx.x;
+    const int node = a.fnode[b];
+    {
+        const int words = sizeof(GroupRec) / 4;
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(a.rec + (int64_t)b * a.N + node);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(&g);
+        for (int i = threadIdx.x; i < words; i += kFinalThreads) dst[i] = src[i];
+    }
+    __syncthreads();
+    const int nchunk = a.V >> 2;
+    const int per = (nchunk + kFinalSplits - 1) / kFinalSplits;
+    const int c_lo = min(split * per, nchunk), c_hi = min(c_lo + per, nchunk);
+    float bv, av;
+    int bi, ai;
+    final_sample_range<kFinalThreads>(a, b, node, g, c_lo, c_hi, bv, bi, av, ai);
+    block_argmax<kFinalThreads>(bv, bi, s_v, s_i);
+    block_argmax<kFinalThreads>(av, ai, s_v, s_i);
+    if (threadIdx.x == 0) {
+        if (bi != INT_MAX) atomicMax(&a.fkey[2 * b], pack_key(bv, bi));
+        if (ai != INT_MAX) atomicMax(&a.fkey[2 * b + 1], pack_key(av, ai));
+        __threadfence();
+        s_last = (atomicAdd(&a.fdone[b], 1) == kFinalSplits - 1);
+    }
+    __syncthreads();
+    if (s_last && threadIdx.x == 0) {
+        __threadfence();
+        const unsigned long long k0 = atomicMax(&a.fkey[2 * b], 0ull);
+        const unsigned long long k1 = atomicMax(&a.fkey[2 * b + 1], 0ull);
+        uint32_t flags = a.fflags[b];
+        const unsigned long long ninf = pack_key(-INFINITY, 0) >> 32;
+        unsigned long long use = k0;
+        if ((k0 >> 32) <= ninf) {  // empty last residual: fall back to q^(K)
+            if (g.K > 0) flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
+            use = (g.K > 0) ? k1 : k0;
+        }
+        a.last_token[b] = (use == 0ull) ? 0 : (int)(0xFFFFFFFFu - (uint32_t)(use & 0xFFFFFFFFull));
+        if (a.flags) a.flags[b] = flags;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// PATH mode: one persistent workgroup per sequence verifies only the groups on
+// the accepted path, then draws the last token.
+// ---------------------------------------------------------------------------
+__global__ __launch_bounds__(kGroupThreads) void rrs_path_kernel(RrsArgs a) {
+    __shared__ GroupShared sh;
+    __shared__ float s_v[kGroupWaves];
+    __shared__ int s_i[kGroupWaves];
+    __shared__ int s_nacc;
+    __shared__ uint32_t s_flags;
+    const int b = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int n = min(max(a.n_nodes[b], 1), a.N);
+    for (int j = tid; j < a.N; j += kGroupThreads) {
+        if (a.uniforms) a.uniforms[(int64_t)b * a.N + j] = (j < n) ? accept_uniform(a, b, j) : 0.f;
+        if (a.theta) a.theta[(int64_t)b * a.N + j] = NAN;
+    }
+    for (int j = tid; j < a.depth_max; j += kGroupThreads) {
+        a.accepted_nodes[(int64_t)b * a.depth_max + j] = -1;
+        if (a.accepted_tokens) a.accepted_tokens[(int64_t)b * a.depth_max + j] = -1;
+    }
+    if (tid == 0) {
+        sh.cur = 0;
+        sh.done = 0;
+        s_nacc = 0;
+        s_flags = 0;
+    }
+    __syncthreads();
+    for (int guard = 0; guard < a.N; ++guard) {
+        const int cur = sh.cur;
+        process_group<kGroupThreads>(a, b, cur, n, sh);
+        const int K = sh.g.K;
+        if (K == 0) break;
+        if (tid == 0) {
+            uint32_t flags = s_flags | (sh.g.flags & RSD_FLAG_NONFINITE);
+            int took = -1;
+            for (int k = 0; k < K; ++k) {
+                if (a.theta) a.theta[(int64_t)b * a.N + sh.g.kid[k]] = sh.g.theta[k];
+                if (accept_uniform(a, b, sh.g.kid[k]) < sh.g.theta[k]) {
+                    took = k;
+                    break;
+                }
+            }
+            if (sh.g.flags & RSD_FLAG_DEGENERATE_RESIDUAL) {
+                const int used = took < 0 ? K - 1 : took;
+                for (int j = 0; j < used; ++j)
+                    if (sh.g.inv_s[j] == 0.f) flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
+            }
+            s_flags = flags;
+            if (took >= 0) {
+                const int nacc = s_nacc;
+                if (nacc < a.depth_max) {
+                    a.accepted_nodes[(int64_t)b * a.depth_max + nacc] = sh.g.kid[took];
+                    if (a.accepted_tokens)
+                        a.accepted_tokens[(int64_t)b * a.depth_max + nacc] = sh.g.tok[took];
+                }
+                s_nacc = nacc + 1;
+                sh.cur = sh.g.kid[took];
+            } else {
+                sh.done = 1;
+            }
+        }
+        __syncthreads();
+        if (sh.done) break;
+    }
+    // last token at sh.cur with record sh.g (K = 0 for a leaf)
+    const int node = sh.cur;
+    float bv, av;
+    int bi, ai;
+    final_sample_range<kGroupThreads>(a, b, node, sh.g, 0, a.V >> 2, bv, bi, av, ai);
+    block_argmax<kGroupThreads>(bv, bi, s_v, s_i);
+    block_argmax<kGroupThreads>(av, ai, s_v, s_i);
+    if (tid == 0) {
+        uint32_t flags = s_flags;
+        int tokn = bi;
+        if (!(bv > -INFINITY)) {
+            if (sh.g.K > 0) {
+                flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
+                tokn = ai;
+            }
+        }
+        if (tokn == INT_MAX) tokn = 0;
+        a.last_token[b] = tokn;
+        a.n_accepted[b] = s_nacc;
+        if (a.final_node) a.final_node[b] = node;
+        if (a.flags) a.flags[b] = flags;
+    }
+}
+
+static size_t align_up(size_t x, size_t al) { return (x + al - 1) / al * al; }
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+}  // namespace rsd
+
+using namespace rsd;
+
+extern "C" size_t rsd_recursive_reject_workspace_bytes(int32_t B, int32_t N_max, int32_t) {
+    if (B <= 0 || N_max <= 0) return 0;
+    return align_up((size_t)B * N_max * sizeof(GroupRec), 256) + align_up((size_t)B * 16, 256) +
+           3 * align_up((size_t)B * 4, 256);
+}
+
+extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *target_logits,
+                                        int32_t B, int32_t N_max, int32_t V, float inv_temperature,
+                                        const int32_t *tokens, const int32_t *parent,
+                                        const int32_t *n_nodes, const int32_t *seq_id, int32_t mode,
+                                        uint64_t seed, uint32_t step, int32_t *accepted_nodes,
+                                        int32_t *accepted_tokens, int32_t depth_max,
+                                        int32_t *n_accepted, int32_t *last_token, int32_t *final_node,
+                                        float *theta, float *uniforms, uint32_t *flags,
+                                        void *workspace, size_t workspace_bytes, void *stream) {
+    if (!draft_logits || !target_logits || !tokens || !parent || !n_nodes || !accepted_nodes ||
+        !n_accepted || !last_token)
+        return RSD_ERR_NULL;
+    if (B < 0 || N_max < 1 || N_max > RSD_NODES_MAX || V < 4 || (V & 3) || V > 131072 || depth_max < 1 ||
+        !(inv_temperature > 0.f) || !aligned16(draft_logits) || !aligned16(target_logits))
+        return RSD_ERR_SHAPE;
+    if (mode != RSD_MODE_PATH && mode != RSD_MODE_ALL_GROUPS) return RSD_ERR_UNSUPPORTED;
+    if (B == 0) return RSD_OK;
+    const size_t need = rsd_recursive_reject_workspace_bytes(B, N_max, V);
+    if (!workspace || workspace_bytes < need) return RSD_ERR_WORKSPACE;
+    char *ws = static_cast<char *>(workspace);
+    RrsArgs a{};
+    a.zd = draft_logits; a.zt = target_logits; a.B = B; a.N = N_max; a.V = V;
+    a.inv_t = inv_temperature;
+    a.c2 = (float)((double)inv_temperature * 1.4426950408889634);
+    a.tokens = tokens; a.parent = parent; a.n_nodes = n_nodes; a.seq_id = seq_id;
+    a.seed = seed; a.step = step; a.accepted_nodes = accepted_nodes;
+    a.accepted_tokens = accepted_tokens; a.depth_max = depth_max; a.n_accepted = n_accepted;
+    a.last_token = last_token; a.final_node = final_node; a.theta = theta; a.uniforms = uniforms;
+    a.flags = flags;
+    size_t off = 0;
+    a.rec = reinterpret_cast<GroupRec *>(ws + off); off += align_up((size_t)B * N_max * sizeof(GroupRec), 256);
+    a.fkey = reinterpret_cast<unsigned long long *>(ws + off); off += align_up((size_t)B * 16, 256);
+    a.fdone = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * 4, 256);
+    a.fnode = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * 4, 256);
+    a.fflags = reinterpret_cast<uint32_t *>(ws + off);
+    hipStream_t st = (hipStream_t)stream;
+    if (mode == RSD_MODE_PATH) {
+        hipLaunchKernelGGL(rrs_path_kernel, dim3(B), dim3(kGroupThreads), 0, st, a);
+    } else {
+        hipLaunchKernelGGL(rrs_group_kernel, dim3(N_max, B), dim3(kGroupThreads), 0, st, a);
+        hipLaunchKernelGGL(rrs_walk_kernel, dim3(B), dim3(kWave), 0, st, a);
+        hipLaunchKernelGGL(rrs_final_kernel, dim3(kFinalSplits, B), dim3(kFinalThreads), 0, st, a);
+    }
+    return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
+}

@@ -1,0 +1,188 @@
+// Device-side helpers shared by the gfx950 kernels: Philox4x32-10, the
+// uniform/Gumbel maps, and wavefront / workgroup reductions for 64-wide waves.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace rsd {
+
+constexpr int kWave = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr uint32_t kTagDraftGumbel = 0;
+constexpr uint32_t kTagAcceptUniform = 1;
+constexpr uint32_t kTagLastGumbel = 2;
+
+// ---------------------------------------------------------------------------
+// Philox4x32 with 10 rounds (Salmon, Moraes, Dror, Shaw, SC'11).  The key is
+// wave-uniform, so its Weyl sequence lives in scalar registers; each round is
+// two 32x32->64 multiplies and two three-way xors on the vector side.
+// ---------------------------------------------------------------------------
+struct PhiloxKey {
+    uint32_t k0, k1;
+};
+
+__device__ __forceinline__ uint4 philox4x32_10(uint32_t c0, uint32_t c1, uint32_t c2, uint32_t c3,
+                                               PhiloxKey key) {
+    uint32_t k0 = key.k0, k1 = key.k1;
+#pragma unroll
+    for (int r = 0; r < 10; ++r) {
+        const uint64_t p0 = (uint64_t)0xD2511F53u * c0;
+        const uint64_t p1 = (uint64_t)0xCD9E8D57u * c2;
+        const uint32_t n0 = (uint32_t)(p1 >> 32) ^ c1 ^ k0;
+        const uint32_t n2 = (uint32_t)(p0 >> 32) ^ c3 ^ k1;
+        c1 = (uint32_t)p1;
+        c3 = (uint32_t)p0;
+        c0 = n0;
+        c2 = n2;
+        k0 += 0x9E3779B9u;
+        k1 += 0xBB67AE85u;
+    }
+    return make_uint4(c0, c1, c2, c3);
+}
+
+__device__ __forceinline__ PhiloxKey make_key(uint64_t seed) {
+    PhiloxKey k;
+    k.k0 = (uint32_t)seed;
+    k.k1 = (uint32_t)(seed >> 32);
+    return k;
+}
+
+__device__ __forceinline__ uint32_t counter_word3(uint32_t tag, uint32_t step) {
+    return (tag & 0xFu) | (step << 4);
+}
+
+// u = (2*(w >> 9) + 1) * 2^-24: odd 24-bit grid, exact in fp32, never 0 or 1.
+__device__ __forceinline__ float uniform_from_word(uint32_t w) {
+    return (float)((w >> 8) | 1u) * 5.9604644775390625e-08f;
+}
+
+// Standard Gumbel variate -log(-log u).
+__device__ __forceinline__ float gumbel_from_word(uint32_t w) {
+    const float u = uniform_from_word(w);
+    return -logf(-logf(u));
+}
+
+// ---------------------------------------------------------------------------
+// Wavefront reductions (all 64 lanes receive the result).
+// ---------------------------------------------------------------------------
+__device__ __forceinline__ float wave_max(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
+    return v;
+}
+
+__device__ __forceinline__ float wave_sum(float v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+__device__ __forceinline__ double wave_sum(double v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
+    return v;
+}
+
+// (value, index) ordering used by every selection: larger value first, on
+// equal values the lower index first.  NaN never beats anything.
+__device__ __forceinline__ bool better(float v, int i, float bv, int bi) {
+    return (v > bv) || (v == bv && i < bi);
+}
+
+__device__ __forceinline__ void wave_argmax(float &v, int &i) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        const float ov = __shfl_xor(v, o, kWave);
+        const int oi = __shfl_xor(i, o, kWave);
+        if (better(ov, oi, v, i)) {
+            v = ov;
+            i = oi;
+        }
+    }
+}
+
+// Online (max, sum of 2^(x - max)) pair and its merge.
+struct MaxSum {
+    float m;  // running maximum (log2 domain), -inf when empty
+    float s;  // sum of 2^(x - m)
+};
+
+__device__ __forceinline__ MaxSum merge(MaxSum a, MaxSum b) {
+    const float m = fmaxf(a.m, b.m);
+    if (m == -INFINITY) return MaxSum{-INFINITY, 0.f};
+    MaxSum r;
+    r.m = m;
+    r.s = a.s * exp2f(a.m - m) + b.s * exp2f(b.m - m);
+    return r;
+}
+
+__device__ __forceinline__ MaxSum wave_merge(MaxSum v) {
+#pragma unroll
+    for (int o = 32; o > 0; o >>= 1) {
+        MaxSum other;
+        other.m = __shfl_xor(v.m, o, kWave);
+        other.s = __shfl_xor(v.s, o, kWave);
+        v = merge(v, other);
+    }
+    return v;
+}
+
+// Workgroup-wide merge of (max,sum) pairs.  `scratch` holds one pair per wave.
+// Every thread returns the merged pair.  Contains two barriers.
+template <int THREADS>
+__device__ __forceinline__ MaxSum block_merge(MaxSum v, MaxSum *scratch) {
+    constexpr int NW = THREADS / kWave;
+    v = wave_merge(v);
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) scratch[wave] = v;
+    __syncthreads();
+    MaxSum r = scratch[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) r = merge(r, scratch[w]);
+    __syncthreads();
+    return r;
+}
+
+// Workgroup-wide sum in double (fixed order: lanes by xor tree, waves in order).
+template <int THREADS>
+__device__ __forceinline__ double block_sum(double v, double *scratch) {
+    constexpr int NW = THREADS / kWave;
+    v = wave_sum(v);
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) scratch[wave] = v;
+    __syncthreads();
+    double r = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) r += scratch[w];
+    __syncthreads();
+    return r;
+}
+
+// Workgroup-wide arg-max with the `better` ordering.  Two barriers.
+template <int THREADS>
+__device__ __forceinline__ void block_argmax(float &v, int &i, float *sv, int *si) {
+    constexpr int NW = THREADS / kWave;
+    wave_argmax(v, i);
+    const int wave = threadIdx.x / kWave;
+    if ((threadIdx.x & (kWave - 1)) == 0) {
+        sv[wave] = v;
+        si[wave] = i;
+    }
+    __syncthreads();
+    float bv = sv[0];
+    int bi = si[0];
+#pragma unroll
+    for (int w = 1; w < NW; ++w) {
+        if (better(sv[w], si[w], bv, bi)) {
+            bv = sv[w];
+            bi = si[w];
+        }
+    }
+    __syncthreads();
+    v = bv;
+    i = bi;
+}
+
+}  // namespace rsd

@@ -1,0 +1,530 @@
+// Tree-masked attention of the draft-tree tokens (Sec. 3.2.2, tree evaluation;
+// mask of Alg. 5): every query row attends the cached prefix plus the tree
+// nodes on its own root path.
+//
+// bf16 path (gfx950 MFMA, fp32 accumulate).  One workgroup = 4 waves owns 64
+// "stacked" query rows of one (sequence, KV head): the N tree rows of the
+// H_q/H_kv query heads that share the KV head are stacked so that K and V are
+// read once per group.  Keys are streamed in tiles of 64 through LDS; each
+// wave owns 16 query rows and computes, with v_mfma_f32_16x16x32_bf16,
+//     S^T = K Q^T      (keys x queries)     then     O^T += V^T P^T.
+// In this orientation a lane holds scores of ONE query, so the running softmax
+// maximum and the rescale factor are per-lane scalars, and the fp32 scores of
+// two 16-key tiles are, after conversion to bf16, already laid out as the B
+// operand of the second product: P never goes through LDS.  V is transposed on
+// its way into LDS (keys permuted so that the eight keys a lane needs are
+// contiguous).  The tree mask is an ancestor bit-set per node (a node's set is
+// its parent's set plus itself), applied only to the tree-key tiles.
+//
+// A long prefix can be split over several workgroups (flash-decoding style);
+// a small second kernel merges the partial (max, sum, output) triples.
+#include <hip/hip_runtime.h>
+#include <math.h>
+
+#include "../../include/rsd.h"
+#include "rsd_device.hpp"
+
+namespace rsd {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+constexpr int kTile = 64;          // keys per LDS tile
+constexpr int kRowsPerBlock = 64;  // stacked query rows per workgroup (4 waves x 16)
+constexpr int kAttnThreads = 256;
+constexpr int kAncWords = RSD_NODES_MAX / 64;
+
+struct AttnArgs {
+    const void *q, *kp, *vp, *kt, *vt;
+    int B, Hq, Hkv, N, D, P_max;
+    int64_t sb, sh, sp;  // prefix strides in elements
+    const int *plen;
+    const int *nn;
+    const int *par;
+    float scale_log2;  // softmax scale * log2(e)
+    int splits;
+    int row_blocks;
+    float *out;
+    float *lse_out;
+    float *ws_o;  // [B,Hq,N,splits,D]
+    float *ws_m;  // [B,Hq,N,splits]  running max (log2 domain)
+    float *ws_l;  // [B,Hq,N,splits]  running sum
+};
+
+// Ancestor-or-self bit-sets of all nodes of one tree into `anc` ([n][kAncWords]).
+// Parent values are clamped into [0, j-1], so the walk always terminates.
+__device__ __forceinline__ void build_ancestors(const int *par, int n, uint64_t *anc, int threads) {
+    for (int i = threadIdx.x; i < n; i += threads) {
+        uint64_t w[kAncWords];
+#pragma unroll
+        for (int k = 0; k < kAncWords; ++k) w[k] = 0;
+        int j = i;
+        for (int guard = 0; guard <= n; ++guard) {
+#pragma unroll
+            for (int k = 0; k < kAncWords; ++k)
+                if ((j >> 6) == k) w[k] |= 1ull << (j & 63);
+            if (j <= 0) break;
+            int p = par[j];
+            p = min(max(p, 0), j - 1);
+            j = p;
+        }
+#pragma unroll
+        for (int k = 0; k < kAncWords; ++k) anc[i * kAncWords + k] = w[k];
+    }
+}
+
+// Column of key `kappa` (0..63) in the transposed V tile: the eight keys that one
+// lane group feeds to one MFMA (two runs of four, 16 apart) become contiguous.
+__device__ __forceinline__ int vt_col(int kappa) {
+    const int j = kappa >> 5, a = (kappa >> 4) & 1, g = (kappa >> 2) & 3, r = kappa & 3;
+    return (j << 5) | (g << 3) | (a << 2) | r;
+}
+
+template <int D>
+__global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArgs a) {
+    constexpr int KPAD = D + 8;       // K tile row stride (elements)
+    constexpr int VPAD = kTile + 8;   // V^T tile row stride (elements)
+    constexpr int DCH = D / 8;        // 16-byte chunks per row
+    constexpr int LPT = kTile * DCH / kAttnThreads;  // chunks per thread per tile
+    constexpr int KS = D / 32;        // k-steps of the first product
+    constexpr int DT = D / 16;        // output tiles of the second product
+    extern __shared__ __align__(16) unsigned char smem[];
+    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);          // [2][kTile][KPAD]
+    __bf16 *Vt = Ks + 2 * kTile * KPAD;                     // [2][D][VPAD]
+    uint64_t *anc = reinterpret_cast<uint64_t *>(Vt + 2 * D * VPAD);  // [N][kAncWords]
+
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int rb = blockIdx.x / a.splits, sp = blockIdx.x - rb * a.splits;
+    const int n = min(max(a.nn[b], 0), a.N);
+    const int plen = min(max(a.plen[b], 0), a.P_max);
+    const int G = a.Hq / a.Hkv;
+    const int rows = G * n;
+    if (rb * kRowsPerBlock >= rows) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int c16 = lane & 15, g = lane >> 4;
+    const bool do_tree = (sp == a.splits - 1);
+    if (do_tree) build_ancestors(a.par + (int64_t)b * a.N, n, anc, kAttnThreads);
+
+    // ---- this lane's query ------------------------------------------------
+    const int R = rb * kRowsPerBlock + wave * 16 + c16;
+    const bool qvalid = R < rows;
+    const int hq = kvh * G + (qvalid ? R / n : 0);
+    const int qi = qvalid ? R % n : 0;
+    const __bf16 *qptr = reinterpret_cast<const __bf16 *>(a.q) + (((int64_t)b * a.Hq + hq) * a.N + qi) * D;
+    bf16x8 qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        if (qvalid) {
+            qf[ks] = *reinterpret_cast<const bf16x8 *>(qptr + ks * 32 + g * 8);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[ks][e] = (__bf16)0.f;
+        }
+    }
+
+    // ---- tile schedule ------------------------------------------------------
+    const int Tp = (plen + kTile - 1) / kTile, Tt = (n + kTile - 1) / kTile;
+    const int t0 = (int)((int64_t)Tp * sp / a.splits), t1 = (int)((int64_t)Tp * (sp + 1) / a.splits);
+    const int npre = t1 - t0;
+    const int ntiles = npre + (do_tree ? Tt : 0);
+
+    const __bf16 *kp = reinterpret_cast<const __bf16 *>(a.kp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
+    const __bf16 *vp = reinterpret_cast<const __bf16 *>(a.vp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
+    const __bf16 *kt = reinterpret_cast<const __bf16 *>(a.kt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
+    const __bf16 *vt = reinterpret_cast<const __bf16 *>(a.vt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
+
+    uint4 kr[LPT], vr[LPT];
+    auto issue_loads = [&](int u) {
+        const __bf16 *ksrc, *vsrc;
+        int64_t stride;
+        int row0, limit;
+        if (u < npre) {
+            row0 = (t0 + u) * kTile; limit = plen; ksrc = kp; vsrc = vp; stride = a.sp;
+        } else {
+            row0 = (u - npre) * kTile; limit = n; ksrc = kt; vsrc = vt; stride = D;
+        }
+#pragma unroll
+        for (int it = 0; it < LPT; ++it) {
+            const int c = it * kAttnThreads + tid;
+            const int row = c / DCH, part = c - row * DCH;
+            if (row0 + row < limit) {
+                const int64_t off = (int64_t)(row0 + row) * stride + part * 8;
+                kr[it] = *reinterpret_cast<const uint4 *>(ksrc + off);
+                vr[it] = *reinterpret_cast<const uint4 *>(vsrc + off);
+            } else {
+                kr[it] = make_uint4(0, 0, 0, 0);
+                vr[it] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+        __bf16 *kdst = Ks + buf * kTile * KPAD;
+        unsigned short *vdst = reinterpret_cast<unsigned short *>(Vt + buf * D * VPAD);
+#pragma unroll
+        for (int it = 0; it < LPT; ++it) {
+            const int c = it * kAttnThreads + tid;
+            const int row = c / DCH, part = c - row * DCH;
+            *reinterpret_cast<uint4 *>(kdst + row * KPAD + part * 8) = kr[it];
+            const int col = vt_col(row);
+            const uint32_t wv[4] = {vr[it].x, vr[it].y, vr[it].z, vr[it].w};
+#pragma unroll
+            for (int e = 0; e < 8; ++e) {
+                const unsigned short hv = (unsigned short)(wv[e >> 1] >> ((e & 1) * 16));
+                vdst[(part * 8 + e) * VPAD + col] = hv;
+            }
+        }
+    };
+
+    floatx4 o[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) o[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
+    float m = -INFINITY, l = 0.f;
+
+    if (ntiles > 0) {
+        issue_loads(0);
+        store_tile(0);
+    }
+    __syncthreads();
+
+    for (int u = 0; u < ntiles; ++u) {
+        const int buf = u & 1;
+        if (u + 1 < ntiles) issue_loads(u + 1);
+
+        // ---- S^T = K Q^T for the 64 keys of this tile ----------------------
+        const __bf16 *kb = Ks + buf * kTile * KPAD;
+        floatx4 s[4];
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+            s[t] = floatx4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kb + (t * 16 + c16) * KPAD + ks * 32 + g * 8);
+                s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s[t], 0, 0, 0);
+            }
+        }
+
+        // ---- scale, mask, online softmax ------------------------------------
+        const bool is_tree = u >= npre;
+        const int row0 = is_tree ? (u - npre) * kTile : (t0 + u) * kTile;
+        const int limit = is_tree ? n : plen;
+        uint64_t vis = ~0ull;
+        if (is_tree) vis = anc[qi * kAncWords + (u - npre)];
+        if (row0 + kTile > limit) {
+            const int nv = limit - row0;  // 1..63
+            vis &= (nv >= 64) ? ~0ull : ((1ull << nv) - 1ull);
+        }
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const int kk = t * 16 + g * 4 + r;
+                float v = s[t][r] * a.scale_log2;
+                v = ((vis >> kk) & 1ull) ? v : -INFINITY;
+                s[t][r] = v;
+                mx = fmaxf(mx, v);
+            }
+        }
+        mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
+        mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
+        const float m_new = fmaxf(m, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = exp2f(m - m_use);
+        float psum = 0.f;
+#pragma unroll
+        for (int t = 0; t < 4; ++t) {
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+                const float p = exp2f(s[t][r] - m_use);
+                s[t][r] = p;
+                psum += p;
+            }
+        }
+        l = l * alpha + psum;
+        m = m_new;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+
+        // ---- O^T += V^T P^T ---------------------------------------------------
+        bf16x8 pf[2];
+#pragma unroll
+        for (int j = 0; j < 2; ++j) {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) pf[j][e] = (__bf16)s[2 * j + (e >> 2)][e & 3];
+        }
+        const __bf16 *vb = Vt + buf * D * VPAD;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+#pragma unroll
+            for (int j = 0; j < 2; ++j) {
+                const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vb + (dt * 16 + c16) * VPAD + j * 32 + g * 8);
+                o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[j], o[dt], 0, 0, 0);
+            }
+        }
+
+        if (u + 1 < ntiles) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue -----------------------------------------------------------
+    float lt = l + __shfl_xor(l, 16, kWave);
+    lt += __shfl_xor(lt, 32, kWave);
+    if (!qvalid) return;
+    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + qi;
+    if (a.splits == 1) {
+        const float inv = lt > 0.f ? 1.f / lt : 0.f;
+        float *dst = a.out + orow * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            float4 v = make_float4(o[dt][0] * inv, o[dt][1] * inv, o[dt][2] * inv, o[dt][3] * inv);
+            *reinterpret_cast<float4 *>(dst + dt * 16 + g * 4) = v;
+        }
+        if (a.lse_out && g == 0) a.lse_out[orow] = (m + log2f(lt)) * kLn2;
+    } else {
+        float *dst = a.ws_o + (orow * a.splits + sp) * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt) {
+            float4 v = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
+            *reinterpret_cast<float4 *>(dst + dt * 16 + g * 4) = v;
+        }
+        if (g == 0) {
+            a.ws_m[orow * a.splits + sp] = m;
+            a.ws_l[orow * a.splits + sp] = lt;
+        }
+    }
+}
+
+// Merge the per-split partial results of one query row: one wave per row.
+__global__ __launch_bounds__(kWave) void tree_attn_merge_kernel(AttnArgs a) {
+    const int i = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+    const int n = min(max(a.nn[b], 0), a.N);
+    if (i >= n) return;
+    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + i;
+    const int lane = threadIdx.x;
+    float m = -INFINITY;
+    for (int s = 0; s < a.splits; ++s) m = fmaxf(m, a.ws_m[orow * a.splits + s]);
+    float lsum = 0.f;
+    for (int d = lane; d < a.D; d += kWave) {
+        float acc = 0.f, lacc = 0.f;
+        for (int s = 0; s < a.splits; ++s) {
+            const float ms = a.ws_m[orow * a.splits + s];
+            const float w = (ms == -INFINITY) ? 0.f : exp2f(ms - m);
+            acc += w * a.ws_o[(orow * a.splits + s) * a.D + d];
+            lacc += w * a.ws_l[orow * a.splits + s];
+        }
+        a.out[orow * a.D + d] = lacc > 0.f ? acc / lacc : 0.f;
+        lsum = lacc;
+    }
+    if (a.lse_out && lane == 0) a.lse_out[orow] = (m + log2f(lsum)) * kLn2;
+}
+
+// fp32 inputs (small configurations): one wave per query row, plain ALUs.
+__global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnArgs a) {
+    __shared__ uint64_t s_anc[kAncWords];
+    __shared__ float s_p[kWave];
+    __shared__ float s_q[256];
+    const int i = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+    const int n = min(max(a.nn[b], 0), a.N);
+    if (i >= n) return;
+    const int plen = min(max(a.plen[b], 0), a.P_max);
+    const int lane = threadIdx.x;
+    const int D = a.D;
+    const int kvh = hq / (a.Hq / a.Hkv);
+    if (lane == 0) {
+        uint64_t w[kAncWords];
+        for (int k = 0; k < kAncWords; ++k) w[k] = 0;
+        int j = i;
+        const int *par = a.par + (int64_t)b * a.N;
+        for (int guard = 0; guard <= n; ++guard) {
+            w[j >> 6] |= 1ull << (j & 63);
+            if (j <= 0) break;
+            j = min(max(par[j], 0), j - 1);
+        }
+        for (int k = 0; k < kAncWords; ++k) s_anc[k] = w[k];
+    }
+    const float *q = reinterpret_cast<const float *>(a.q) + (((int64_t)b * a.Hq + hq) * a.N + i) * D;
+    for (int d = lane; d < D; d += kWave) s_q[d] = q[d];
+    __syncthreads();
+    const float *kp = reinterpret_cast<const float *>(a.kp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
+    const float *vp = reinterpret_cast<const float *>(a.vp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
+    const float *kt = reinterpret_cast<const float *>(a.kt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
+    const float *vt = reinterpret_cast<const float *>(a.vt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
+    float m = -INFINITY, l = 0.f;
+    float acc[4] = {0.f, 0.f, 0.f, 0.f};  // output dims lane, lane+64, lane+128, lane+192
+    const int total = plen + n;
+    for (int base = 0; base < total; base += kWave) {
+        const int j = base + lane;
+        float sc = -INFINITY;
+        const float *krow = nullptr;
+        if (j < plen) {
+            krow = kp + (int64_t)j * a.sp;
+        } else if (j < total) {
+            const int node = j - plen;
+            if ((s_anc[node >> 6] >> (node & 63)) & 1ull) krow = kt + (int64_t)node * D;
+        }
+        if (krow) {
+            float dot = 0.f;
+            for (int d = 0; d < D; ++d) dot = fmaf(s_q[d], krow[d], dot);
+            sc = dot * a.scale_log2;
+        }
+        const float mx = wave_max(sc);
+        const float m_new = fmaxf(m, mx);
+        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+        const float alpha = exp2f(m - m_use);
+        const float p = exp2f(sc - m_use);
+        l = l * alpha + wave_sum(p);
+        m = m_new;
+        __syncthreads();
+        s_p[lane] = p;
+        __syncthreads();
+        const int cnt = min(kWave, total - base);
+#pragma unroll
+        for (int k = 0; k < 4; ++k) acc[k] *= alpha;
+        for (int jj = 0; jj < cnt; ++jj) {
+            const float pj = s_p[jj];
+            if (pj == 0.f) continue;
+            const int key = base + jj;
+            const float *vrow = key < plen ? vp + (int64_t)key * a.sp : vt + (int64_t)(key - plen) * D;
+#pragma unroll
+            for (int k = 0; k < 4; ++k) {
+                const int d = lane + k * kWave;
+                if (d < D) acc[k] = fmaf(pj, vrow[d], acc[k]);
+            }
+        }
+    }
+    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + i;
+    const float inv = l > 0.f ? 1.f / l : 0.f;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+        const int d = lane + k * kWave;
+        if (d < D) a.out[orow * D + d] = acc[k] * inv;
+    }
+    if (a.lse_out && lane == 0) a.lse_out[orow] = (m + log2f(l)) * kLn2;
+}
+
+static size_t align_up(size_t x, size_t al) { return (x + al - 1) / al * al; }
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int choose_splits(int dtype, int B, int Hq, int Hkv, int N, int P_max, int requested) {
+    if (dtype != RSD_DTYPE_BF16) return 1;
+    const int tiles = (P_max + kTile - 1) / kTile;
+    int s = requested;
+    if (s <= 0) {
+        const int G = Hq / Hkv;
+        const long blocks = (long)((G * N + kRowsPerBlock - 1) / kRowsPerBlock) * Hkv * B;
+        s = (int)((1024 + blocks - 1) / (blocks > 0 ? blocks : 1));
+        if (s > 32) s = 32;
+    }
+    if (s > tiles) s = tiles;
+    if (s < 1) s = 1;
+    return s;
+}
+
+template <int D>
+static size_t attn_smem_bytes(int N) {
+    return (size_t)2 * kTile * (D + 8) * 2 + (size_t)2 * D * (kTile + 8) * 2 + (size_t)N * kAncWords * 8;
+}
+
+}  // namespace rsd
+
+using namespace rsd;
+
+extern "C" size_t rsd_tree_attention_workspace_bytes(int32_t dtype, int32_t B, int32_t H_q,
+                                                     int32_t H_kv, int32_t N_max, int32_t D,
+                                                     int32_t P_max, int32_t num_splits) {
+    if (B <= 0 || H_q <= 0 || H_kv <= 0 || N_max <= 0 || D <= 0 || P_max < 0 || H_q % H_kv) return 0;
+    const int s = choose_splits(dtype, B, H_q, H_kv, N_max, P_max, num_splits);
+    if (s <= 1) return 0;
+    const size_t rows = (size_t)B * H_q * N_max;
+    return align_up(rows * s * D * 4, 256) + 2 * align_up(rows * s * 4, 256);
+}
+
+extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const void *v_prefix,
+                                      const void *k_tree, const void *v_tree, int32_t dtype,
+                                      int32_t B, int32_t H_q, int32_t H_kv, int32_t N_max, int32_t D,
+                                      int32_t P_max, int64_t prefix_stride_b,
+                                      int64_t prefix_stride_h, int64_t prefix_stride_p,
+                                      const int32_t *prefix_len, const int32_t *n_nodes,
+                                      const int32_t *parent, float scale, int32_t num_splits,
+                                      float *out, float *lse_out, void *workspace,
+                                      size_t workspace_bytes, void *stream) {
+    if (!q || !k_tree || !v_tree || !prefix_len || !n_nodes || !parent || !out) return RSD_ERR_NULL;
+    if (P_max > 0 && (!k_prefix || !v_prefix)) return RSD_ERR_NULL;
+    if (B < 0 || H_q < 1 || H_kv < 1 || H_q % H_kv || N_max < 1 || N_max > RSD_NODES_MAX ||
+        P_max < 0 || num_splits < 0)
+        return RSD_ERR_SHAPE;
+    if (dtype != RSD_DTYPE_BF16 && dtype != RSD_DTYPE_F32) return RSD_ERR_UNSUPPORTED;
+    const int esz = dtype == RSD_DTYPE_BF16 ? 2 : 4;
+    const int vec = 16 / esz;
+    if (dtype == RSD_DTYPE_BF16 && D != 64 && D != 128) return RSD_ERR_UNSUPPORTED;
+    if (dtype == RSD_DTYPE_F32 && (D < 1 || D > 256)) return RSD_ERR_UNSUPPORTED;
+    if (!aligned16(q) || !aligned16(k_tree) || !aligned16(v_tree) || !aligned16(out) ||
+        (P_max > 0 && (!aligned16(k_prefix) || !aligned16(v_prefix))))
+        return RSD_ERR_SHAPE;
+    if (P_max > 0 && dtype == RSD_DTYPE_BF16 &&
+        (prefix_stride_b % vec || prefix_stride_h % vec || prefix_stride_p % vec || prefix_stride_p < D))
+        return RSD_ERR_SHAPE;
+    if (P_max > 0 && dtype == RSD_DTYPE_F32 && prefix_stride_p < D) return RSD_ERR_SHAPE;
+    if (B == 0) return RSD_OK;
+
+    AttnArgs a{};
+    a.q = q; a.kp = k_prefix; a.vp = v_prefix; a.kt = k_tree; a.vt = v_tree;
+    a.B = B; a.Hq = H_q; a.Hkv = H_kv; a.N = N_max; a.D = D; a.P_max = P_max;
+    a.sb = prefix_stride_b; a.sh = prefix_stride_h; a.sp = prefix_stride_p;
+    a.plen = prefix_len; a.nn = n_nodes; a.par = parent;
+    a.scale_log2 = (float)((double)scale * 1.4426950408889634);
+    a.out = out; a.lse_out = lse_out;
+    hipStream_t st = (hipStream_t)stream;
+
+    if (dtype == RSD_DTYPE_F32) {
+        a.splits = 1;
+        hipLaunchKernelGGL(tree_attn_f32_kernel, dim3(N_max, H_q, B), dim3(kWave), 0, st, a);
+        return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
+    }
+
+    const int G = H_q / H_kv;
+    a.splits = choose_splits(dtype, B, H_q, H_kv, N_max, P_max, num_splits);
+    a.row_blocks = (G * N_max + kRowsPerBlock - 1) / kRowsPerBlock;
+    if (a.splits > 1) {
+        const size_t need = rsd_tree_attention_workspace_bytes(dtype, B, H_q, H_kv, N_max, D, P_max, num_splits);
+        if (!workspace || workspace_bytes < need) return RSD_ERR_WORKSPACE;
+        const size_t rows = (size_t)B * H_q * N_max;
+        char *ws = static_cast<char *>(workspace);
+        a.ws_o = reinterpret_cast<float *>(ws);
+        a.ws_m = reinterpret_cast<float *>(ws + align_up(rows * a.splits * D * 4, 256));
+        a.ws_l = reinterpret_cast<float *>(ws + align_up(rows * a.splits * D * 4, 256) +
+                                           align_up(rows * a.splits * 4, 256));
+    }
+    const dim3 grid(a.row_blocks * a.splits, H_kv, B);
+    hipError_t err;
+    if (D == 128) {
+        const size_t smem = attn_smem_bytes<128>(N_max);
+        static bool attr_set = false;  // the limit covers the largest N_max, set once
+        if (!attr_set) {
+            err = hipFuncSetAttribute(reinterpret_cast<const void *>(tree_attn_bf16_kernel<128>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)attn_smem_bytes<128>(RSD_NODES_MAX));
+            if (err != hipSuccess) return RSD_ERR_LAUNCH;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(tree_attn_bf16_kernel<128>, grid, dim3(kAttnThreads), smem, st, a);
+    } else {
+        const size_t smem = attn_smem_bytes<64>(N_max);
+        static bool attr_set = false;
+        if (!attr_set) {
+            err = hipFuncSetAttribute(reinterpret_cast<const void *>(tree_attn_bf16_kernel<64>),
+                                      hipFuncAttributeMaxDynamicSharedMemorySize,
+                                      (int)attn_smem_bytes<64>(RSD_NODES_MAX));
+            if (err != hipSuccess) return RSD_ERR_LAUNCH;
+            attr_set = true;
+        }
+        hipLaunchKernelGGL(tree_attn_bf16_kernel<64>, grid, dim3(kAttnThreads), smem, st, a);
+    }
+    if (hipGetLastError() != hipSuccess) return RSD_ERR_LAUNCH;
+    if (a.splits > 1) {
+        hipLaunchKernelGGL(tree_attn_merge_kernel, dim3(N_max, H_q, B), dim3(kWave), 0, st, a);
+        if (hipGetLastError() != hipSuccess) return RSD_ERR_LAUNCH;
+    }
+    return RSD_OK;
+}

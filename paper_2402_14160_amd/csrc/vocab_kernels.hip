@@ -1,0 +1,473 @@
+// Vocabulary-wide passes of the drafting side: log-softmax normaliser,
+// Gumbel-Top-k (Alg. 4) and the Stochastic Beam Search step (Alg. 9).
+//
+// One workgroup owns one logit row.  The row is read once from HBM with
+// 16-byte coalesced loads; each lane's four consecutive entries share one
+// Philox block.  The perturbed scores stay in registers, so selecting the k
+// winners needs no second pass over memory.
+#include <hip/hip_runtime.h>
+#include <limits.h>
+#include <math.h>
+
+#include "../../include/rsd.h"
+#include "rsd_device.hpp"
+
+namespace rsd {
+
+// ---------------------------------------------------------------------------
+// lse[r] = log sum_x exp(z[r,x] / T)      (Eq. (5): phi = z/T - lse)
+// ---------------------------------------------------------------------------
+template <int THREADS>
+__global__ __launch_bounds__(THREADS) void lse_kernel(const float *__restrict__ logits, int64_t ld,
+                                                      int V, float c2, float *__restrict__ lse) {
+    __shared__ MaxSum s_ms[THREADS / kWave];
+    const int row = blockIdx.x;
+    const float *zrow = logits + (int64_t)row * ld;
+    const float4 *z4 = reinterpret_cast<const float4 *>(zrow);
+    const int nchunk = V >> 2;
+    MaxSum acc{-INFINITY, 0.f};
+#pragma unroll 4
+    for (int c = threadIdx.x; c < nchunk; c += THREADS) {
+        const float4 z = z4[c];
+        const float a0 = z.x * c2, a1 = z.y * c2, a2 = z.z * c2, a3 = z.w * c2;
+        const float mx = fmaxf(fmaxf(a0, a1), fmaxf(a2, a3));
+        if (mx > acc.m) {
+            acc.s *= exp2f(acc.m - mx);
+            acc.m = mx;
+        }
+        if (acc.m > -INFINITY)
+            acc.s += (exp2f(a0 - acc.m) + exp2f(a1 - acc.m)) + (exp2f(a2 - acc.m) + exp2f(a3 - acc.m));
+    }
+    const int tail = (nchunk << 2) + threadIdx.x;
+    if (tail < V) {
+        const float a = zrow[tail] * c2;
+        if (a > acc.m) {
+            acc.s *= exp2f(acc.m - a);
+            acc.m = a;
+        }
+        if (acc.m > -INFINITY) acc.s += exp2f(a - acc.m);
+    }
+    acc = block_merge<THREADS>(acc, s_ms);
+    if (threadIdx.x == 0) lse[row] = (acc.m + log2f(acc.s)) * kLn2;
+}
+
+// ---------------------------------------------------------------------------
+// Gumbel-Top-k row kernel.
+// ---------------------------------------------------------------------------
+struct TopkArgs {
+    const float *logits;
+    int64_t ld;
+    int V;
+    int k_max;
+    const int *k_per_row;  // [R] or null
+    const int *seq_id;     // indexed by row / rows_per_seq, or null
+    const int *node_id;    // [R] or null
+    const int *n_live;     // [R / rows_per_seq] or null: rows w >= n_live[b] are dead (SBS)
+    int rows_per_seq;      // 1 for Gumbel-Top-k; W_in for SBS
+    int seq_default_is_b;  // null seq_id means: 0 (Gumbel-Top-k) or b (SBS)
+    int node_default_is_w; // null node_id means: row (Gumbel-Top-k) or w (SBS)
+    float inv_t;
+    uint64_t seed;
+    uint32_t step;
+    int *tokens;       // [R, k_max]
+    float *perturbed;  // [R, k_max] or null
+    float *logprob;    // [R, k_max] or null
+    float *lse;        // [R] or null
+    int *count;        // [R] or null
+};
+
+constexpr int kTopkThreads = 1024;
+constexpr int kTopkWaves = kTopkThreads / kWave;
+constexpr int kCandMax = 1024;
+
+template <int CH>
+__global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
+    __shared__ MaxSum s_ms[kTopkWaves];
+    __shared__ float s_wmax[kTopkWaves];
+    __shared__ float s_tau;
+    __shared__ int s_cnt;
+    __shared__ float s_cval[kCandMax];
+    __shared__ int s_cidx[kCandMax];
+    __shared__ float s_av[kTopkWaves];
+    __shared__ int s_ai[kTopkWaves];
+    __shared__ float s_outv[RSD_K_MAX];
+    __shared__ int s_outi[RSD_K_MAX];
+    __shared__ int s_nout;
+
+    const int row = blockIdx.x;
+    const int tid = threadIdx.x;
+    const int lane = tid & (kWave - 1);
+    const int wave = tid / kWave;
+    const int b = row / a.rows_per_seq;
+    const int w = row - b * a.rows_per_seq;
+    const bool dead = a.n_live != nullptr && w >= a.n_live[b];
+
+    int k = a.k_per_row ? a.k_per_row[row] : a.k_max;
+    k = min(max(k, 0), a.k_max);
+    if (dead) k = 0;
+    const uint32_t seq = a.seq_id ? (uint32_t)a.seq_id[a.rows_per_seq > 1 ? b : row]
+                                  : (a.seq_default_is_b ? (uint32_t)b : 0u);
+    const uint32_t node = a.node_id ? (uint32_t)a.node_id[row]
+                                    : (a.node_default_is_w ? (uint32_t)w : (uint32_t)row);
+    const PhiloxKey key = make_key(a.seed);
+    const uint32_t c3 = counter_word3(kTagDraftGumbel, a.step);
+
+    const float *zrow = a.logits + (int64_t)row * a.ld;
+    const int V = a.V;
+
+    float val[CH * 4];
+    MaxSum acc{-INFINITY, 0.f};
+    if (!dead) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+            const int c = j * kTopkThreads + tid;
+            const int x = c << 2;
+            float z[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
+            if (x + 3 < V) {
+                const float4 t = *reinterpret_cast<const float4 *>(zrow + x);
+                z[0] = t.x; z[1] = t.y; z[2] = t.z; z[3] = t.w;
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if (x + e < V) z[e] = zrow[x + e];
+            }
+            if (x < V) {
+                const uint4 r = philox4x32_10((uint32_t)c, node, seq, c3, key);
+                const uint32_t wd[4] = {r.x, r.y, r.z, r.w};
+                float mx = -INFINITY;
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const float s = z[e] * a.inv_t;
+                    z[e] = s;
+                    mx = fmaxf(mx, s);
+                    // out-of-range entries hold -inf and stay -inf
+                    val[j * 4 + e] = s + gumbel_from_word(wd[e]);
+                }
+                const float mx2 = mx * kLog2e;
+                if (mx2 > acc.m) {
+                    acc.s *= exp2f(acc.m - mx2);
+                    acc.m = mx2;
+                }
+                if (acc.m > -INFINITY) {
+#pragma unroll
+                    for (int e = 0; e < 4; ++e) acc.s += exp2f(fmaf(z[e], kLog2e, -acc.m));
+                }
+            } else {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) val[j * 4 + e] = -INFINITY;
+            }
+        }
+    } else {
+#pragma unroll
+        for (int e = 0; e < CH * 4; ++e) val[e] = -INFINITY;
+    }
+
+    // ---- row normaliser -------------------------------------------------
+    acc = block_merge<kTopkThreads>(acc, s_ms);
+    const float lse_nat = (acc.m + log2f(acc.s)) * kLn2;
+
+    // ---- threshold: k-th largest wave maximum ----------------------------
+    float tmax = -INFINITY;
+#pragma unroll
+    for (int e = 0; e < CH * 4; ++e) tmax = fmaxf(tmax, val[e]);
+    const float wmax = wave_max(tmax);
+    if (lane == 0) s_wmax[wave] = wmax;
+    if (tid == 0) {
+        s_cnt = 0;
+        s_nout = 0;
+    }
+    __syncthreads();
+    if (tid < kTopkWaves) {
+        // rank of this wave's maximum among the 16 (ties by wave index)
+        const float mine = s_wmax[tid];
+        int rank = 0;
+        for (int o = 0; o < kTopkWaves; ++o) {
+            const float ov = s_wmax[o];
+            rank += (ov > mine) || (ov == mine && o < tid);
+        }
+        if (rank == max(k, 1) - 1) s_tau = mine;
+    }
+    __syncthreads();
+    const float tau = s_tau;
+
+    // ---- gather everything at or above the threshold ---------------------
+    if (k > 0) {
+#pragma unroll
+        for (int j = 0; j < CH; ++j) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const float v = val[j * 4 + e];
+                if (v >= tau && v > -INFINITY) {
+                    const int slot = atomicAdd(&s_cnt, 1);
+                    if (slot < kCandMax) {
+                        s_cval[slot] = v;
+                        s_cidx[slot] = ((j * kTopkThreads + tid) << 2) + e;
+                    }
+                }
+            }
+        }
+    }
+    __syncthreads();
+    const int ncand = s_cnt;
+
+    if (ncand <= kCandMax) {
+        // ---- wave 0 picks the k best candidates in order -----------------
+        if (wave == 0) {
+            for (int r = 0; r < k; ++r) {
+                float bv = -INFINITY;
+                int bi = INT_MAX, bslot = -1;
+                for (int s = lane; s < ncand; s += kWave) {
+                    const float v = s_cval[s];
+                    const int i = s_cidx[s];
+                    if (better(v, i, bv, bi)) {
+                        bv = v;
+                        bi = i;
+                        bslot = s;
+                    }
+                }
+                float wv = bv;
+                int wi = bi;
+                wave_argmax(wv, wi);
+                if (!(wv > -INFINITY)) break;
+                if (bslot >= 0 && bi == wi) s_cval[bslot] = -INFINITY;
+                if (lane == 0) {
+                    s_outv[r] = wv;
+                    s_outi[r] = wi;
+                    s_nout = r + 1;
+                }
+                __threadfence_block();
+            }
+        }
+        __syncthreads();
+    } else {
+        // ---- rare: too many candidates (many equal or -inf scores); k rounds of
+        // workgroup-wide arg-max over the register-resident scores ---------
+        for (int r = 0; r < k; ++r) {
+            float bv = -INFINITY;
+            int bi = INT_MAX;
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e) {
+                    const int i = ((j * kTopkThreads + tid) << 2) + e;
+                    if (better(val[j * 4 + e], i, bv, bi)) {
+                        bv = val[j * 4 + e];
+                        bi = i;
+                    }
+                }
+            }
+            block_argmax<kTopkThreads>(bv, bi, s_av, s_ai);
+            if (!(bv > -INFINITY)) break;
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+#pragma unroll
+                for (int e = 0; e < 4; ++e)
+                    if ((((j * kTopkThreads + tid) << 2) + e) == bi) val[j * 4 + e] = -INFINITY;
+            }
+            if (tid == 0) {
+                s_outv[r] = bv;
+                s_outi[r] = bi;
+                s_nout = r + 1;
+            }
+        }
+        __syncthreads();
+    }
+
+    // ---- outputs ----------------------------------------------------------
+    const int nout = s_nout;
+    if (tid < a.k_max) {
+        const int64_t o = (int64_t)row * a.k_max + tid;
+        if (tid < nout) {
+            const int t = s_outi[tid];
+            a.tokens[o] = t;
+            if (a.perturbed) a.perturbed[o] = s_outv[tid] - lse_nat;
+            if (a.logprob) a.logprob[o] = zrow[t] * a.inv_t - lse_nat;
+        } else {
+            a.tokens[o] = -1;
+            if (a.perturbed) a.perturbed[o] = -INFINITY;
+            if (a.logprob) a.logprob[o] = -INFINITY;
+        }
+    }
+    if (tid == 0) {
+        if (a.count) a.count[row] = nout;
+        if (a.lse) a.lse[row] = dead ? 0.f : lse_nat;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// SBS: combine the per-row top-W lists of one sequence (Alg. 9, last steps).
+// Only each row's W best perturbed scores can be among the global top-W since
+// T(u, .) is increasing within a row (Theorem 3.2's argument).
+// ---------------------------------------------------------------------------
+struct SbsSelectArgs {
+    const int *row_tok;      // [B*W_in, W]
+    const float *row_pert;   // [B*W_in, W]  z/T - lse + G
+    const float *row_logp;   // [B*W_in, W]  z/T - lse
+    const int *row_cnt;      // [B*W_in]
+    const float *sum_logprob;   // [B, W_in]
+    const float *trunc_gumbel;  // [B, W_in]
+    const int *n_in;
+    int W_in, W, V;
+    int *tokens;
+    int *parent;
+    float *sum_out;
+    float *gum_out;
+    int *n_out;
+};
+
+__global__ __launch_bounds__(256) void sbs_select_kernel(SbsSelectArgs a) {
+    __shared__ double s_psi[256];
+    __shared__ int s_key[256];
+    const int b = blockIdx.x;
+    const int t = threadIdx.x;
+    const int w = t / a.W;
+    const int j = t - w * a.W;
+    const int n = min(max(a.n_in[b], 0), a.W_in);
+    double psi = -INFINITY, phi = -INFINITY;
+    int tok = -1;
+    bool live = false;
+    if (w < n && w < a.W_in) {
+        const int row = b * a.W_in + w;
+        if (j < a.row_cnt[row]) {
+            live = true;
+            tok = a.row_tok[row * a.W + j];
+            const double sigma = (double)a.sum_logprob[row];
+            const double gamma = (double)a.trunc_gumbel[row];
+            const double pj = (double)a.row_pert[row * a.W + j];
+            const double p0 = (double)a.row_pert[row * a.W];
+            phi = (double)a.row_logp[row * a.W + j] + sigma;
+            const double d = pj - p0;  // Phi~ - Z <= 0 (the row's sigma cancels)
+            if (j == 0 || !(d < 0.0)) {
+                psi = gamma;
+            } else {
+                const double log1m = d > -0.6931471805599453 ? log(-expm1(d)) : log1p(-exp(d));
+                const double v = gamma - (pj + sigma) + log1m;
+                psi = gamma - (fmax(v, 0.0) + log1p(exp(-fabs(v))));
+            }
+        }
+    }
+    s_psi[t] = live ? psi : -INFINITY;
+    s_key[t] = live ? (w * a.V + tok) : INT_MAX;
+    __syncthreads();
+    int total = 0, rank = 0;
+    for (int o = 0; o < 256; ++o) {
+        const double op = s_psi[o];
+        const int ok = s_key[o];
+        const bool olive = ok != INT_MAX;
+        total += olive;
+        if (live && olive && ((op > psi) || (op == psi && ok < s_key[t]))) ++rank;
+    }
+    if (live && rank < a.W) {
+        const int o = b * a.W + rank;
+        a.tokens[o] = tok;
+        a.parent[o] = w;
+        a.sum_out[o] = (float)phi;
+        a.gum_out[o] = (float)psi;
+    }
+    const int nout = min(total, a.W);
+    if (t >= nout && t < a.W) {
+        const int o = b * a.W + t;
+        a.tokens[o] = -1;
+        a.parent[o] = -1;
+        a.sum_out[o] = -INFINITY;
+        a.gum_out[o] = -INFINITY;
+    }
+    if (t == 0) a.n_out[b] = nout;
+}
+
+static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+static int32_t launch_topk(const TopkArgs &a, int R, hipStream_t st) {
+    if (R == 0) return RSD_OK;
+    if (a.V <= kTopkThreads * 4 * 8)
+        hipLaunchKernelGGL(gumbel_topk_kernel<8>, dim3(R), dim3(kTopkThreads), 0, st, a);
+    else
+        hipLaunchKernelGGL(gumbel_topk_kernel<16>, dim3(R), dim3(kTopkThreads), 0, st, a);
+    return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
+}
+
+}  // namespace rsd
+
+using namespace rsd;
+
+extern "C" int32_t rsd_log_softmax_lse(const float *logits, int64_t ld, int32_t R, int32_t V,
+                                       float inv_temperature, float *lse, void *stream) {
+    if (!logits || !lse) return RSD_ERR_NULL;
+    if (R < 0 || V < 1 || ld < V || (ld & 3) || !aligned16(logits) || !(inv_temperature > 0.f))
+        return RSD_ERR_SHAPE;
+    if (R == 0) return RSD_OK;
+    const float c2 = (float)((double)inv_temperature * 1.4426950408889634);
+    hipLaunchKernelGGL(lse_kernel<256>, dim3(R), dim3(256), 0, (hipStream_t)stream, logits, ld, V, c2,
+                       lse);
+    return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
+}
+
+extern "C" size_t rsd_gumbel_topk_workspace_bytes(int32_t, int32_t, int32_t) { return 0; }
+
+extern "C" int32_t rsd_gumbel_topk(const float *logits, int64_t ld, int32_t R, int32_t V,
+                                   int32_t k_max, const int32_t *k_per_row, float inv_temperature,
+                                   const int32_t *seq_id, const int32_t *node_id, uint64_t seed,
+                                   uint32_t step, int32_t *tokens, float *perturbed, float *logprob,
+                                   float *lse, int32_t *count, void *, size_t, void *stream) {
+    if (!logits || !tokens) return RSD_ERR_NULL;
+    if (R < 0 || V < 1 || V > RSD_VOCAB_MAX || k_max < 1 || k_max > RSD_K_MAX || k_max > V ||
+        ld < V || (ld & 3) || !aligned16(logits) || !(inv_temperature > 0.f))
+        return RSD_ERR_SHAPE;
+    TopkArgs a{};
+    a.logits = logits; a.ld = ld; a.V = V; a.k_max = k_max; a.k_per_row = k_per_row;
+    a.seq_id = seq_id; a.node_id = node_id; a.n_live = nullptr; a.rows_per_seq = 1;
+    a.seq_default_is_b = 0; a.node_default_is_w = 0; a.inv_t = inv_temperature;
+    a.seed = seed; a.step = step; a.tokens = tokens; a.perturbed = perturbed;
+    a.logprob = logprob; a.lse = lse; a.count = count;
+    return launch_topk(a, R, (hipStream_t)stream);
+}
+
+static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
+
+extern "C" size_t rsd_sbs_step_workspace_bytes(int32_t B, int32_t W_in, int32_t, int32_t W) {
+    if (B < 0 || W_in < 0 || W < 0) return 0;
+    const size_t rows = (size_t)B * W_in;
+    return 3 * align_up(rows * W * 4, 256) + align_up(rows * 4, 256);
+}
+
+extern "C" int32_t rsd_sbs_step(const float *logits, const float *sum_logprob,
+                                const float *trunc_gumbel, const int32_t *n_in,
+                                const int32_t *seq_id, const int32_t *node_id, int32_t B,
+                                int32_t W_in, int32_t V, int32_t W, float inv_temperature,
+                                uint64_t seed, uint32_t step, int32_t *tokens, int32_t *parent,
+                                float *sum_logprob_out, float *trunc_gumbel_out, int32_t *n_out,
+                                float *lse, void *workspace, size_t workspace_bytes, void *stream) {
+    if (!logits || !sum_logprob || !trunc_gumbel || !n_in || !tokens || !parent ||
+        !sum_logprob_out || !trunc_gumbel_out || !n_out)
+        return RSD_ERR_NULL;
+    if (B < 0 || W_in < 1 || W_in > RSD_K_MAX || W < 1 || W > RSD_K_MAX || V < 1 ||
+        V > RSD_VOCAB_MAX || W > V || !aligned16(logits) || !(inv_temperature > 0.f) || ((V & 3) && (int64_t)B * W_in > 1))
+        return RSD_ERR_SHAPE;
+    if (B == 0) return RSD_OK;
+    const size_t need = rsd_sbs_step_workspace_bytes(B, W_in, V, W);
+    if (!workspace || workspace_bytes < need) return RSD_ERR_WORKSPACE;
+    const size_t rows = (size_t)B * W_in;
+    char *ws = static_cast<char *>(workspace);
+    const size_t seg = align_up(rows * W * 4, 256);
+    int *row_tok = reinterpret_cast<int *>(ws);
+    float *row_pert = reinterpret_cast<float *>(ws + seg);
+    float *row_logp = reinterpret_cast<float *>(ws + 2 * seg);
+    int *row_cnt = reinterpret_cast<int *>(ws + 3 * seg);
+
+    TopkArgs a{};
+    a.logits = logits; a.ld = V; a.V = V; a.k_max = W; a.k_per_row = nullptr;
+    a.seq_id = seq_id; a.node_id = node_id; a.n_live = n_in; a.rows_per_seq = W_in;
+    a.seq_default_is_b = 1; a.node_default_is_w = 1; a.inv_t = inv_temperature;
+    a.seed = seed; a.step = step; a.tokens = row_tok; a.perturbed = row_pert;
+    a.logprob = row_logp; a.lse = lse; a.count = row_cnt;
+    const int32_t rc = launch_topk(a, (int)rows, (hipStream_t)stream);
+    if (rc != RSD_OK) return rc;
+
+    SbsSelectArgs s{};
+    s.row_tok = row_tok; s.row_pert = row_pert; s.row_logp = row_logp; s.row_cnt = row_cnt;
+    s.sum_logprob = sum_logprob; s.trunc_gumbel = trunc_gumbel; s.n_in = n_in;
+    s.W_in = W_in; s.W = W; s.V = V; s.tokens = tokens; s.parent = parent;
+    s.sum_out = sum_logprob_out; s.gum_out = trunc_gumbel_out; s.n_out = n_out;
+    hipLaunchKernelGGL(sbs_select_kernel, dim3(B), dim3(256), 0, (hipStream_t)stream, s);
+    return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
+}

@@ -1,0 +1,308 @@
+"""GPU parity: every C-ABI call against the CPU oracle on the same seeded inputs."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import rrs as o_rrs
+from oracle import sbs as o_sbs
+from oracle import tree_attention as o_attn
+from paper_2402_14160_amd import binding, draft_tree, workloads
+from tests.gpu_util import (LOGP_TOL, NEAR_TIE, check_topk_against_oracle, dev, oracle_tree_const,
+                            say, to_np)
+
+pytestmark = pytest.mark.gpu
+
+
+# --------------------------------------------------------------------------- lse
+@pytest.mark.parametrize("R,V,inv_t", [(3, 64, 1.0), (5, 1001, 1.0), (7, 32000, 1.0 / 0.3),
+                                       (4, 50272, 1.0)])
+def test_log_softmax_lse(R, V, inv_t):
+    say(f"lse R={R} V={V}")
+    zt, _ = workloads.make_logits("zipf", 1, R, V, seed=1)
+    ld = (V + 3) // 4 * 4
+    buf = torch.zeros((R, ld), dtype=torch.float32)
+    buf[:, :V] = zt[0]
+    got = to_np(binding.log_softmax_lse(buf.to(dev())[:, :V], inv_t))
+    z = zt[0].numpy().astype(np.float64) * np.float32(inv_t).astype(np.float64)
+    ref = np.log(np.sum(np.exp(z - z.max(1, keepdims=True)), 1)) + z.max(1)
+    assert np.allclose(got, ref, rtol=0, atol=LOGP_TOL)
+
+
+# ------------------------------------------------------------------- gumbel top-k
+@pytest.mark.parametrize("kind,R,V,k_max,inv_t", [
+    ("normal", 3, 64, 2, 1.0),          # config 0 shape
+    ("zipf", 9, 1001, 5, 1.0),          # ragged vocabulary tail
+    ("zipf", 22, 32000, 3, 1.0),        # config 1 rows
+    ("zipf", 12, 32000, 8, 1.0 / 0.3),  # temperature 0.3
+    ("zipf", 6, 50272, 6, 1.0),         # OPT vocabulary, second kernel instance
+    ("zipf", 2, 65536, 16, 1.0),        # limits
+])
+def test_gumbel_topk_matches_oracle(kind, R, V, k_max, inv_t):
+    say(f"gumbel_topk {kind} R={R} V={V} k={k_max}")
+    _, zd = workloads.make_logits(kind, 1, R, V, seed=2)
+    ld = (V + 3) // 4 * 4
+    buf = torch.zeros((R, ld), dtype=torch.float32)
+    buf[:, :V] = zd[0]
+    rng = np.random.default_rng(0)
+    ks = rng.integers(0, k_max + 1, size=R).astype(np.int32)
+    ks[0] = k_max
+    seq = rng.integers(0, 100, size=R).astype(np.int32)
+    node = rng.integers(0, 256, size=R).astype(np.int32)
+    g = binding.gumbel_topk(buf.to(dev())[:, :V], k_max, k_per_row=torch.from_numpy(ks).to(dev()),
+                            inv_temperature=inv_t, seq_id=torch.from_numpy(seq).to(dev()),
+                            node_id=torch.from_numpy(node).to(dev()), seed=0xABCDEF0123, step=3)
+    near = check_topk_against_oracle(zd[0].numpy(), g, ks, np.float32(inv_t), seq, node,
+                                     0xABCDEF0123, 3, k_max)
+    say(f"  near-tie rows: {near} of {R}")
+    assert near <= 1
+    g2 = binding.gumbel_topk(buf.to(dev())[:, :V], k_max, k_per_row=torch.from_numpy(ks).to(dev()),
+                             inv_temperature=inv_t, seq_id=torch.from_numpy(seq).to(dev()),
+                             node_id=torch.from_numpy(node).to(dev()), seed=0xABCDEF0123, step=3)
+    for key in ("tokens", "perturbed", "logprob", "lse", "count"):
+        assert torch.equal(g[key], g2[key]), key     # run-to-run determinism
+
+
+def test_gumbel_topk_defaults_and_filtered_rows():
+    say("gumbel_topk defaults / -inf rows")
+    V, R, k = 5000, 4, 8
+    _, zd = workloads.make_logits("zipf", 1, R, V, seed=3)
+    z = zd[0].clone()
+    z[1, 3:] = -float("inf")                 # 3 finite entries: count < k, slow selection path
+    z[2, :] = -float("inf")                  # nothing to sample
+    z[3, ::2] = -float("inf")
+    g = binding.gumbel_topk(z.to(dev()), k, seed=9)
+    near = check_topk_against_oracle(z.numpy(), g, np.full(R, k), 1.0, np.zeros(R, int),
+                                     np.arange(R), 9, 0, k)
+    assert near == 0
+    assert to_np(g["count"]).tolist() == [8, 3, 0, 8]
+
+
+def test_gumbel_topk_rejects_bad_arguments():
+    z = torch.zeros((2, 64), dtype=torch.float32, device=dev())
+    for kwargs in (dict(k_max=17), dict(k_max=65), dict(k_max=4, inv_temperature=0.0)):
+        with pytest.raises(binding.RsdError) as e:
+            binding.gumbel_topk(z, **kwargs)
+        assert e.value.code == -2
+    with pytest.raises(binding.RsdError):
+        binding.gumbel_topk(torch.zeros((1, 70000), dtype=torch.float32, device=dev()), 2)
+
+
+# -------------------------------------------------------------------------- SBS
+@pytest.mark.parametrize("B,W_in,V,W,inv_t", [(1, 1, 64, 2, 1.0), (3, 6, 32000, 6, 1.0),
+                                               (2, 6, 50272, 6, 1.0), (2, 12, 4000, 12, 1 / 0.3)])
+def test_sbs_step_matches_oracle(B, W_in, V, W, inv_t):
+    say(f"sbs_step B={B} W_in={W_in} V={V} W={W}")
+    _, zd = workloads.make_logits("zipf", B, W_in, V, seed=4)
+    rng = np.random.default_rng(1)
+    sigma = (-rng.exponential(3.0, size=(B, W_in))).astype(np.float32)
+    gamma = (-np.sort(rng.exponential(1.0, size=(B, W_in)), axis=1)).astype(np.float32)
+    n_in = rng.integers(1, W_in + 1, size=B).astype(np.int32)
+    n_in[0] = W_in
+    node = rng.integers(0, 200, size=(B, W_in)).astype(np.int32)
+    seq = rng.integers(0, 50, size=B).astype(np.int32)
+    d = dev()
+    g = binding.sbs_step(zd.to(d), torch.from_numpy(sigma).to(d), torch.from_numpy(gamma).to(d),
+                         torch.from_numpy(n_in).to(d), W, inv_temperature=inv_t,
+                         seq_id=torch.from_numpy(seq).to(d), node_id=torch.from_numpy(node).to(d),
+                         seed=77, step=2)
+    ref = o_sbs.sbs_step(zd.numpy(), sigma, gamma, n_in, W, inv_temperature=np.float32(inv_t),
+                         seq_id=seq, node_id=node, seed=77, step=2)
+    assert np.array_equal(to_np(g["n_out"]), ref["n_out"])
+    near = 0
+    for b in range(B):
+        n = int(ref["n_out"][b])
+        gaps = -np.diff(ref["trunc_gumbel"][b, :n])
+        if np.any(gaps < NEAR_TIE):
+            near += 1
+            continue
+        assert np.array_equal(to_np(g["tokens"])[b, :n], ref["tokens"][b, :n])
+        assert np.array_equal(to_np(g["parent"])[b, :n], ref["parent"][b, :n])
+        assert np.allclose(to_np(g["sum_logprob"])[b, :n], ref["sum_logprob"][b, :n], rtol=1e-6, atol=LOGP_TOL)
+        assert np.allclose(to_np(g["trunc_gumbel"])[b, :n], ref["trunc_gumbel"][b, :n], rtol=1e-6, atol=2e-5)
+        assert np.all(to_np(g["tokens"])[b, n:] == -1)
+        live = int(n_in[b])
+        assert np.allclose(to_np(g["lse"])[b, :live], ref["lse"][b, :live], rtol=0, atol=LOGP_TOL)
+    say(f"  near-tie sequences: {near} of {B}")
+    assert near <= 1
+
+
+# ------------------------------------------------------------------ tree building
+def test_draft_trees_match_oracle_gumbel_and_sbs():
+    say("draft trees (config 0 and a small config-1-like case)")
+    d = dev()
+    for kind, V, branching, n_cap, seed in (("normal", 64, (2, 2), 7, 0), ("zipf", 32000, (3, 2, 2, 1), 34, 5)):
+        _, zd = workloads.make_logits(kind, 2, n_cap, V, seed=seed)
+        counts = [workloads.full_tree_child_counts(branching)] * 2
+        g = draft_tree.create_draft_tree_const(zd.to(d), counts, seed=seed, step=1)
+        for b in range(2):
+            ref = oracle_tree_const(zd[b].numpy(), counts[b], b, seed, 1)
+            n = len(ref["tokens"])
+            assert int(g["n_nodes"][b]) == n
+            assert np.array_equal(to_np(g["tokens"])[b, :n], ref["tokens"])
+            assert np.array_equal(to_np(g["parent"])[b, :n], ref["parent"])
+    _, zd = workloads.make_logits("zipf", 2, 37, 50272, seed=6)
+    g = draft_tree.create_draft_tree_sbs(zd.to(d), 6, 6, seed=6, step=0)
+    from oracle import draft_tree as o_tree
+    for b in range(2):
+        ref = o_tree.create_draft_tree_sbs(zd[b].numpy(), 6, 6, seq=b, seed=6, step=0)
+        n = len(ref["tokens"])
+        assert int(g["n_nodes"][b]) == n == 37
+        assert np.array_equal(to_np(g["tokens"])[b, :n], ref["tokens"])
+        assert np.array_equal(to_np(g["parent"])[b, :n], ref["parent"])
+
+
+# --------------------------------------------------------------- tree attention
+def _random_tree(rng, n, max_children=4):
+    parent = [-1]
+    frontier = [0]
+    while len(parent) < n:
+        nxt = []
+        for p in frontier:
+            for _ in range(int(rng.integers(0, max_children + 1))):
+                if len(parent) < n:
+                    parent.append(p); nxt.append(len(parent) - 1)
+        frontier = nxt or [len(parent) - 1]
+        if not nxt and len(parent) < n:
+            parent.append(frontier[0]); frontier = [len(parent) - 1]
+    return np.array(parent[:n], dtype=np.int32)
+
+
+def _attention_case(B, Hq, Hkv, N, D, P, dtype, seed, n_nodes=None, plens=None, splits=0):
+    rng = np.random.default_rng(seed)
+    q, kp, vp, kt, vt = workloads.make_qkv(B, Hq, Hkv, N, D, max(P, 1), dtype, seed)
+    n_nodes = np.full(B, N, dtype=np.int32) if n_nodes is None else np.asarray(n_nodes, dtype=np.int32)
+    plens = np.full(B, P, dtype=np.int32) if plens is None else np.asarray(plens, dtype=np.int32)
+    parent = np.stack([_random_tree(rng, N) for _ in range(B)])
+    d = dev()
+    scale = workloads.attention_scale(D)
+    out, lse = binding.tree_attention(q.to(d), kp.to(d) if P > 0 else None, vp.to(d) if P > 0 else None,
+                                      kt.to(d), vt.to(d), torch.from_numpy(plens).to(d),
+                                      torch.from_numpy(n_nodes).to(d), torch.from_numpy(parent).to(d),
+                                      scale, num_splits=splits, return_lse=True)
+    f = lambda t: t.to(torch.float32).numpy()
+    ref, ref_lse = o_attn.tree_attention(f(q), f(kp), f(vp), f(kt), f(vt), plens, n_nodes, parent, scale)
+    out, lse = to_np(out), to_np(lse)
+    err = 0.0
+    for b in range(B):
+        n = int(n_nodes[b])
+        if n:
+            err = max(err, np.abs(out[b, :, :n] - ref[b, :, :n]).max())
+            assert np.allclose(lse[b, :, :n], ref_lse[b, :, :n], rtol=0, atol=2e-2 if dtype == "bf16" else 1e-4)
+    return err
+
+
+def test_tree_attention_fp32_config0():
+    say("attention fp32 config 0")
+    err = _attention_case(1, 1, 1, 7, 64, 32, "f32", 0)
+    say(f"  max abs err {err:.2e}")
+    assert err < 1e-4
+    assert _attention_case(2, 4, 2, 9, 48, 70, "f32", 1, n_nodes=[9, 5], plens=[70, 3]) < 1e-4
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,N,D,P,splits,n_nodes,plens", [
+    (1, 2, 2, 34, 128, 1024, 0, None, None),          # config-1 shape, few heads, auto split
+    (2, 4, 2, 37, 128, 200, 1, None, [200, 131]),     # GQA, ragged prefix tail, one split
+    (2, 4, 2, 37, 128, 200, 3, [37, 20], [200, 64]),  # forced splits, per-sequence sizes
+    (1, 8, 1, 65, 128, 300, 2, None, None),           # 65 nodes: two tree tiles, 520 stacked rows
+    (2, 2, 2, 130, 128, 64, 0, [130, 1], None),       # three ancestor words; single-node tree
+    (1, 2, 1, 16, 64, 96, 0, None, None),             # head_dim 64
+    (1, 2, 2, 20, 128, 0, 0, None, None),             # no prefix at all
+    (2, 2, 2, 12, 128, 80, 0, [0, 12], [80, 0]),      # empty tree in one sequence, empty prefix in other
+])
+def test_tree_attention_bf16(B, Hq, Hkv, N, D, P, splits, n_nodes, plens):
+    say(f"attention bf16 B={B} Hq={Hq} Hkv={Hkv} N={N} D={D} P={P} splits={splits}")
+    err = _attention_case(B, Hq, Hkv, N, D, P, "bf16", 3, n_nodes=n_nodes, plens=plens, splits=splits)
+    say(f"  max abs err {err:.2e}")
+    assert err < 1e-2
+
+
+def test_tree_attention_strided_prefix_and_bad_arguments():
+    say("attention strided prefix cache")
+    d = dev()
+    B, H, N, D, P, cap = 1, 2, 10, 128, 100, 160
+    q, kp, vp, kt, vt = workloads.make_qkv(B, H, H, N, D, cap, "bf16", 8)
+    parent = torch.tensor([[-1, 0, 0, 1, 1, 2, 3, 3, 5, 8]], dtype=torch.int32)
+    args = (torch.tensor([P], dtype=torch.int32, device=d), torch.tensor([N], dtype=torch.int32, device=d),
+            parent.to(d), 0.1)
+    full = binding.tree_attention(q.to(d), kp.to(d), vp.to(d), kt.to(d), vt.to(d), *args)
+    sliced = binding.tree_attention(q.to(d), kp.to(d)[:, :, :P], vp.to(d)[:, :, :P], kt.to(d), vt.to(d), *args)
+    assert torch.equal(full, sliced)          # capacity 160, length 100: same result via strides
+    with pytest.raises(binding.RsdError) as e:
+        binding.tree_attention(q.to(d)[..., :96].contiguous(), None, None, kt.to(d)[..., :96].contiguous(),
+                               vt.to(d)[..., :96].contiguous(), *args)
+    assert e.value.code == -6
+
+
+# ------------------------------------------------------- recursive rejection sampling
+def _rrs_case(kind, B, V, counts, n_cap, seed, inv_t, mode, sbs=None):
+    d = dev()
+    zt, zd = workloads.make_logits(kind, B, n_cap, V, seed=seed)
+    if sbs is None:
+        tree = draft_tree.create_draft_tree_const(zd.to(d), counts, seed=seed, step=2, inv_temperature=inv_t)
+    else:
+        tree = draft_tree.create_draft_tree_sbs(zd.to(d), sbs[0], sbs[1], seed=seed, step=2, inv_temperature=inv_t)
+    g = binding.recursive_reject(zd.to(d), zt.to(d), tree["tokens"], tree["parent"], tree["n_nodes"],
+                                 inv_temperature=inv_t, mode=mode, seed=seed, step=2)
+    ref = o_rrs.recursive_reject(zt.numpy(), zd.numpy(), to_np(tree["tokens"]), to_np(tree["parent"]),
+                                 to_np(tree["n_nodes"]), inv_temperature=np.float32(inv_t), mode=mode,
+                                 seed=seed, step=2)
+    assert np.array_equal(to_np(g["uniforms"]).astype(np.float64)[:, 1:] *
+                          (np.arange(1, n_cap)[None] < to_np(tree["n_nodes"])[:, None]),
+                          ref["uniforms"][:, 1:] * (np.arange(1, n_cap)[None] < to_np(tree["n_nodes"])[:, None]))
+    th_g, th_r = to_np(g["theta"]).astype(np.float64), ref["theta"]
+    both = np.isfinite(th_r)
+    assert np.array_equal(np.isfinite(th_g), both)
+    assert np.allclose(th_g[both], th_r[both], rtol=1e-5, atol=1e-6)
+    near = 0
+    for b in range(B):
+        if ref["near_tie"][b] or ref["last_gap"][b] < NEAR_TIE:
+            near += 1
+            continue
+        k = int(ref["n_accepted"][b])
+        assert int(g["n_accepted"][b]) == k
+        assert np.array_equal(to_np(g["accepted_nodes"])[b, :k], ref["accepted_nodes"][b, :k])
+        assert np.array_equal(to_np(g["accepted_tokens"])[b, :k], ref["accepted_tokens"][b, :k])
+        assert np.all(to_np(g["accepted_nodes"])[b, k:] == -1)
+        assert int(g["final_node"][b]) == int(ref["final_node"][b])
+        assert int(g["last_token"][b]) == int(ref["last_token"][b]), (b, k)
+        assert int(g["flags"][b]) == (1 if ref["flags"][b] else 0)
+    return near, ref
+
+
+@pytest.mark.parametrize("mode", [binding.MODE_PATH, binding.MODE_ALL_GROUPS])
+@pytest.mark.parametrize("kind,B,V,branching,inv_t", [
+    ("normal", 4, 64, (2, 2), 1.0),
+    ("zipf", 3, 32000, (3, 2, 2, 1), 1.0),
+    ("zipf", 2, 32000, (8, 4, 2), 1.0 / 0.3),
+    ("zipf", 2, 50272, (4, 3), 1.0),
+])
+def test_recursive_reject_matches_oracle(mode, kind, B, V, branching, inv_t):
+    say(f"rrs mode={mode} {kind} B={B} V={V} b={branching} invT={inv_t:.2f}")
+    counts = [workloads.full_tree_child_counts(branching)] * B
+    n_cap = 1 + sum(int(np.prod(branching[:l + 1])) for l in range(len(branching)))
+    near, ref = _rrs_case(kind, B, V, counts, n_cap, 11, inv_t, mode)
+    say(f"  near-tie sequences: {near} of {B}; accepted lengths {ref['n_accepted'].tolist()}")
+    assert near <= 1
+
+
+def test_recursive_reject_on_sbs_tree_and_ragged_subtrees():
+    say("rrs on an SBS tree (interleaved parents) and random subtrees")
+    near, ref = _rrs_case("zipf", 3, 32000, None, 37, 13, 1.0, binding.MODE_ALL_GROUPS, sbs=(6, 6))
+    assert near <= 1
+    counts = [workloads.random_subtree_child_counts((8, 4, 2), 40, s) for s in range(3)]
+    near, ref = _rrs_case("zipf", 3, 32000, counts, 40, 14, 1.0, binding.MODE_PATH)
+    assert near <= 1
+
+
+def test_recursive_reject_identical_models_and_single_node():
+    say("rrs identical models / root only")
+    d = dev()
+    zt, _ = workloads.make_logits("zipf", 2, 5, 4000, seed=15)
+    tokens = torch.tensor([[-1, 7, 9, 11, 13], [-1, 0, 0, 0, 0]], dtype=torch.int32, device=d)
+    parent = torch.tensor([[-1, 0, 1, 2, 3], [-1, -1, -1, -1, -1]], dtype=torch.int32, device=d)
+    n_nodes = torch.tensor([5, 1], dtype=torch.int32, device=d)
+    g = binding.recursive_reject(zt.to(d), zt.to(d), tokens, parent, n_nodes, seed=1)
+    ref = o_rrs.recursive_reject(zt.numpy(), zt.numpy(), to_np(tokens), to_np(parent), to_np(n_nodes), seed=1)
+    assert to_np(g["n_accepted"]).tolist() == [4, 0] == ref["n_accepted"].tolist()
+    assert to_np(g["last_token"]).tolist() == ref["last_token"].tolist()
+    assert to_np(g["final_node"]).tolist() == [4, 0]
