@@ -1,0 +1,295 @@
+#!/usr/bin/env python3
+"""Benchmark of the RSD draft-tree hot path on one MI355X.
+
+A step is one pass of the whole hot path over one batch of synthetic input that
+is already resident in HBM: drafting (Gumbel-Top-k per tree level, or the
+Stochastic Beam Search steps), one layer of tree-masked attention, and recursive
+rejection sampling.  The headline value is tree nodes per second of the whole
+step; the attention+verification-only figure of the metric's definition
+(B*N / (t_attention_one_layer + t_rrs)) is reported beside it.
+
+Prints ONE JSON line.  Default workload: the largest single-GPU configuration
+("cfg4_stress"); the other configurations are timed briefly and listed under
+"per_config".
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
+MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+N_LAYERS = {"cfg1_llama2_7b": 32, "cfg2_opt_13b_sbs": 40, "cfg3_llama2_70b_gqa": 80, "cfg4_stress": 32}
+
+
+def build_case(cfg, seed, torch, binding, draft_tree, workloads):
+    """Generate inputs on the GPU, grow the trees with the HIP samplers, and return the
+    resident tensors plus the three phase closures."""
+    dev = torch.device("cuda:0")
+    B, N, V = cfg["B"], cfg["N"], cfg["V"]
+    zt, zd = workloads.make_logits(cfg["logits"], B, N, V, seed, device=dev)
+    q, kp, vp, kt, vt = workloads.make_qkv(B, cfg["Hq"], cfg["Hkv"], N, cfg["D"], cfg["P"],
+                                           cfg["dtype"], seed + 1, device=dev)
+    plen = torch.full((B,), cfg["P"], dtype=torch.int32, device=dev)
+    scale = workloads.attention_scale(cfg["D"])
+    case = dict(cfg=cfg, zt=zt, zd=zd, q=q, kp=kp, vp=vp, kt=kt, vt=vt, plen=plen, scale=scale)
+
+    if cfg["sampler"] == "gumbel":
+        counts = workloads.tree_child_counts(cfg, seed)
+        tree = draft_tree.create_draft_tree_const(zd, counts, seed=seed, step=0)
+        # resident per-level row matrices, as a draft model would hand them over
+        levels = []
+        depth = max(len(c) for c in counts)
+        for level in range(depth):
+            rb, rn, ks = [], [], []
+            for b in range(B):
+                lo_hi = tree["level_off"][b]
+                if level >= len(counts[b]) or level + 1 >= len(lo_hi):
+                    continue
+                lo, hi = lo_hi[level], lo_hi[level + 1]
+                for i in range(lo, hi):
+                    if counts[b][level][i - lo] > 0:
+                        rb.append(b); rn.append(i); ks.append(counts[b][level][i - lo])
+            if not ks:
+                continue
+            rows = zd[torch.tensor(rb, device=dev), torch.tensor(rn, device=dev)].contiguous()
+            levels.append(dict(rows=rows, k_max=max(ks),
+                               k=torch.tensor(ks, dtype=torch.int32, device=dev),
+                               seq=torch.tensor(rb, dtype=torch.int32, device=dev),
+                               node=torch.tensor(rn, dtype=torch.int32, device=dev)))
+        case["draft_rows"] = sum(l["rows"].shape[0] for l in levels)
+
+        def draft():
+            for l in levels:
+                binding.gumbel_topk(l["rows"], l["k_max"], k_per_row=l["k"], seq_id=l["seq"],
+                                    node_id=l["node"], seed=seed, step=0)
+    else:
+        W, L = cfg["width"], cfg["depth"]
+        tree = draft_tree.create_draft_tree_sbs(zd, W, L, seed=seed, step=0)
+        levels = []
+        for level in range(L):
+            w_in = 1 if level == 0 else W
+            lo = 0 if level == 0 else 1 + (level - 1) * W
+            rows = zd[:, lo:lo + w_in].contiguous()
+            node = (lo + torch.arange(w_in, device=dev, dtype=torch.int32))[None].expand(B, w_in).contiguous()
+            levels.append(dict(rows=rows, node=node,
+                               sigma=torch.zeros((B, w_in), dtype=torch.float32, device=dev),
+                               gamma=torch.zeros((B, w_in), dtype=torch.float32, device=dev),
+                               n_in=torch.full((B,), w_in, dtype=torch.int32, device=dev)))
+        case["draft_rows"] = sum(l["rows"].shape[0] * l["rows"].shape[1] for l in levels)
+
+        def draft():
+            sigma, gamma = levels[0]["sigma"], levels[0]["gamma"]
+            for l in levels:
+                out = binding.sbs_step(l["rows"], sigma, gamma, l["n_in"], W, node_id=l["node"],
+                                       seed=seed, step=0)
+                sigma, gamma = out["sum_logprob"], out["trunc_gumbel"]
+
+    case["tree"] = tree
+    attn_out = torch.empty((B, cfg["Hq"], N, cfg["D"]), dtype=torch.float32, device=dev)
+    mode = binding.MODE_ALL_GROUPS
+
+    def attn():
+        binding.tree_attention(q, kp, vp, kt, vt, plen, tree["n_nodes"], tree["parent"], scale, out=attn_out)
+
+    def rrs():
+        return binding.recursive_reject(zd, zt, tree["tokens"], tree["parent"], tree["n_nodes"],
+                                        mode=mode, seed=seed, step=0, diagnostics=False)
+
+    case.update(draft=draft, attn=attn, rrs=rrs, attn_out=attn_out)
+    return case
+
+
+def algorithmic_figures(case):
+    """Bytes / flops that one step has to move / do at the least."""
+    cfg, tree = case["cfg"], case["tree"]
+    B, V, D, P = cfg["B"], cfg["V"], cfg["D"], cfg["P"]
+    esz = 2 if cfg["dtype"] == "bf16" else 4
+    n_nodes = tree["n_nodes"].cpu().tolist()
+    parent = tree["parent"].cpu()
+    attn_bytes = attn_flops = 0
+    groups = 0
+    for b in range(B):
+        n = n_nodes[b]
+        attn_bytes += 2 * (P + n) * cfg["Hkv"] * D * esz + cfg["Hq"] * n * D * (esz + 4)
+        attn_flops += 4 * n * (P + n) * D * cfg["Hq"]
+        groups += len(set(parent[b, 1:n].tolist()))
+    # every sibling group reads its draft row and its target row once; the last token reads
+    # one more row pair per sequence
+    rrs_bytes = (groups + B) * 2 * V * 4
+    draft_bytes = case["draft_rows"] * V * 4
+    return dict(attn_bytes=attn_bytes, attn_flops=attn_flops, rrs_bytes=rrs_bytes,
+                draft_bytes=draft_bytes, nodes=sum(n_nodes), groups=groups)
+
+
+def time_case(case, steps, warmup, torch):
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    for _ in range(warmup):
+        case["draft"](); case["attn"](); case["rrs"]()
+    torch.cuda.synchronize()
+    marks = [[ev() for _ in range(4)] for _ in range(steps)]
+    t0 = time.perf_counter()
+    for s in range(steps):
+        marks[s][0].record()
+        case["draft"]()
+        marks[s][1].record()
+        case["attn"]()
+        marks[s][2].record()
+        case["rrs"]()
+        marks[s][3].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    phase = [sum(m[i].elapsed_time(m[i + 1]) for m in marks) / steps for i in range(3)]
+    return dict(ms_per_step=wall * 1000.0 / steps, draft_ms=phase[0], attn_ms=phase[1], rrs_ms=phase[2])
+
+
+def report(case, t):
+    fig = algorithmic_figures(case)
+    cfg = case["cfg"]
+    attn_s, rrs_s, draft_s = t["attn_ms"] / 1e3, t["rrs_ms"] / 1e3, t["draft_ms"] / 1e3
+    intensity = fig["attn_flops"] / fig["attn_bytes"]
+    ridge = MFMA_BF16_PEAK_TFLOPS * 1e12 / (HBM_PEAK_GBS * 1e9)
+    out = dict(
+        workload=cfg["name"], nodes=fig["nodes"], ms_per_step=round(t["ms_per_step"], 4),
+        nodes_per_s_full_step=fig["nodes"] / (t["ms_per_step"] / 1e3),
+        nodes_per_s_attn_rrs=fig["nodes"] / (attn_s + rrs_s),
+        draft_ms=round(t["draft_ms"], 4), attn_ms=round(t["attn_ms"], 4), rrs_ms=round(t["rrs_ms"], 4),
+        attn_GBps=fig["attn_bytes"] / attn_s / 1e9, attn_TFLOPs=fig["attn_flops"] / attn_s / 1e12,
+        attn_frac_hbm=fig["attn_bytes"] / attn_s / 1e9 / HBM_PEAK_GBS,
+        attn_frac_mfma=fig["attn_flops"] / attn_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
+        attn_bound="mfma" if intensity > ridge else "hbm",
+        rrs_GBps=fig["rrs_bytes"] / rrs_s / 1e9, rrs_frac_hbm=fig["rrs_bytes"] / rrs_s / 1e9 / HBM_PEAK_GBS,
+        draft_GBps=fig["draft_bytes"] / draft_s / 1e9 if draft_s > 0 else None,
+        draft_frac_hbm=fig["draft_bytes"] / draft_s / 1e9 / HBM_PEAK_GBS if draft_s > 0 else None,
+        model_equiv_nodes_per_s=(fig["nodes"] / (N_LAYERS[cfg["name"]] * attn_s + rrs_s)
+                                 if cfg["name"] in N_LAYERS else None),
+    )
+    return out, fig
+
+
+def cpu_baseline(case, fig, torch):
+    """The oracle, as it stands, on a bounded sample of the same workload."""
+    import numpy as np
+
+    from oracle import gumbel_topk as o_topk
+    from oracle import rrs as o_rrs
+    from oracle import sbs as o_sbs
+    from oracle import tree_attention as o_attn
+    cfg, tree = case["cfg"], case["tree"]
+    B = cfg["B"]
+    b = 0
+    n = int(tree["n_nodes"][b])
+    heads = min(4, cfg["Hkv"])
+    group = cfg["Hq"] // cfg["Hkv"]
+    f = lambda t: t.to(torch.float32).cpu().numpy()
+    q = f(case["q"][b:b + 1, :heads * group]); kp = f(case["kp"][b:b + 1, :heads]); vp = f(case["vp"][b:b + 1, :heads])
+    kt = f(case["kt"][b:b + 1, :heads]); vt = f(case["vt"][b:b + 1, :heads])
+    parent = tree["parent"][b:b + 1].cpu().numpy(); tokens = tree["tokens"][b:b + 1].cpu().numpy()
+    zt = case["zt"][b:b + 1].cpu().numpy(); zd = case["zd"][b:b + 1].cpu().numpy()
+    t0 = time.perf_counter()
+    o_attn.tree_attention(q, kp, vp, kt, vt, [cfg["P"]], [n], parent, case["scale"])
+    t_attn = (time.perf_counter() - t0) * cfg["Hkv"] / heads
+    t0 = time.perf_counter()
+    o_rrs.recursive_reject(zt, zd, tokens, parent, [n], mode=o_rrs.MODE_ALL_GROUPS, seed=0, step=0)
+    t_rrs = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    nonleaf = sorted(set(parent[0, 1:n].tolist()))
+    if cfg["sampler"] == "gumbel":
+        o_topk.gumbel_topk(zd[0, nonleaf], 2, seq_id=np.zeros(len(nonleaf), int), node_id=np.array(nonleaf), seed=0)
+    else:
+        for lo in range(0, len(nonleaf), cfg["width"]):
+            rows = nonleaf[lo:lo + cfg["width"]]
+            o_sbs.sbs_step(zd[:, rows], np.zeros((1, len(rows))), np.zeros((1, len(rows))), [len(rows)],
+                           cfg["width"], seed=0)
+    t_draft = time.perf_counter() - t0
+    per_seq = t_attn + t_rrs + t_draft
+    try:
+        import threadpoolctl
+        threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
+    except Exception:
+        threads = os.cpu_count()
+    return dict(value=n / per_seq, unit="tree nodes/s", cores=threads, kind="oracle",
+                sample=(f"sequence 0 of {B}: drafting of its {len(nonleaf)} non-leaf rows, tree attention of "
+                        f"{heads} of {cfg['Hkv']} KV heads (time scaled to all heads), and recursive rejection "
+                        f"sampling (all groups); {t_draft + t_attn * heads / cfg['Hkv'] + t_rrs:.1f} s of CPU work"),
+                seconds_per_sequence=per_seq)
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--config", default="cfg4_stress", help="primary workload (name or index)")
+    ap.add_argument("--no-others", action="store_true", help="skip the brief runs of the other configurations")
+    ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
+    ap.add_argument("--seed", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py: this build measures one GPU only (no collectives are part of the hot path); "
+                 "run with --gpus 1")
+
+    import torch
+
+    from paper_2402_14160_amd import binding, draft_tree, workloads
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU")
+    binding.lib()   # fails loudly if the HIP library is missing
+
+    key = int(args.config) if args.config.isdigit() else args.config
+    cfg = workloads.config(key)
+    case = build_case(cfg, args.seed, torch, binding, draft_tree, workloads)
+    torch.cuda.synchronize()
+    t = time_case(case, args.steps, args.warmup, torch)
+    rep, fig = report(case, t)
+
+    # roofline of the dominant kernel: the tree-attention launch
+    bound = rep["attn_bound"]
+    if bound == "hbm":
+        roof = dict(bound="hbm", achieved=rep["attn_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
+                    frac=rep["attn_frac_hbm"], traffic=None, kernel="tree_attn_bf16_kernel")
+    else:
+        roof = dict(bound="mfma", achieved=rep["attn_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
+                    frac=rep["attn_frac_mfma"], traffic=None, kernel="tree_attn_bf16_kernel")
+
+    per_config = {}
+    if not args.no_others:
+        for other in workloads.CONFIGS:
+            if other["name"] == cfg["name"]:
+                continue
+            del case
+            torch.cuda.empty_cache()
+            case = build_case(dict(other), args.seed, torch, binding, draft_tree, workloads)
+            tt = time_case(case, max(5, args.steps), args.warmup, torch)
+            per_config[other["name"]], _ = report(case, tt)
+        del case
+        torch.cuda.empty_cache()
+        case = build_case(cfg, args.seed, torch, binding, draft_tree, workloads)
+
+    cpu = None if args.no_cpu else cpu_baseline(case, fig, torch)
+
+    line = dict(
+        metric="draft-tree nodes verified/sec (attn+RRS) at 1 GPU; % HBM and % MFMA peak",
+        value=rep["nodes_per_s_full_step"], unit="tree nodes/s", n_gpus=1, steps=args.steps,
+        warmup=args.warmup, ms_per_step=rep["ms_per_step"], higher_is_better=True, scaling="weak",
+        vs_baseline=None, dtype="bf16" if cfg["dtype"] == "bf16" else "f32", data="synthetic",
+        config=dict(workload=cfg["name"], batch=cfg["B"], vocab=cfg["V"], nodes_per_seq=cfg["N"],
+                    q_heads=cfg["Hq"], kv_heads=cfg["Hkv"], head_dim=cfg["D"], kv_prefix=cfg["P"],
+                    sampler=cfg["sampler"], rrs_mode="all_groups"),
+        value_attn_rrs_only=rep["nodes_per_s_attn_rrs"],
+        phases=dict(draft_ms=rep["draft_ms"], attn_ms=rep["attn_ms"], rrs_ms=rep["rrs_ms"],
+                    attn_GBps=rep["attn_GBps"], attn_TFLOPs=rep["attn_TFLOPs"],
+                    rrs_GBps=rep["rrs_GBps"], draft_GBps=rep["draft_GBps"],
+                    model_equiv_nodes_per_s=rep["model_equiv_nodes_per_s"]),
+        roofline=roof, cpu_baseline=cpu, per_config=per_config,
+    )
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()
