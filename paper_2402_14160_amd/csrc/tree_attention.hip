@@ -11,10 +11,11 @@
 // In this orientation a lane holds scores of ONE query, so the running softmax
 // maximum and the rescale factor are per-lane scalars, and the fp32 scores of
 // two 16-key tiles are, after conversion to bf16, already laid out as the B
-// operand of the second product: P never goes through LDS.  V is transposed on
-// its way into LDS (keys permuted so that the eight keys a lane needs are
-// contiguous).  The tree mask is an ancestor bit-set per node (a node's set is
-// its parent's set plus itself), applied only to the tree-key tiles.
+// operand of the second product: P never goes through LDS.  K and V tiles are
+// stored row-major in LDS; the V^T operand is fetched with the gfx950
+// transposing LDS read (ds_read_b64_tr_b16), which hands each lane four keys of
+// one head-dim column.  The tree mask is an ancestor bit-set per node (a node's
+// set is its parent's set plus itself), applied only to the tree-key tiles.
 //
 // A long prefix can be split over several workgroups (flash-decoding style);
 // a small second kernel merges the partial (max, sum, output) triples.
@@ -27,7 +28,9 @@
 namespace rsd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
+typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
 constexpr int kTile = 64;          // keys per LDS tile
 constexpr int kRowsPerBlock = 64;  // stacked query rows per workgroup (4 waves x 16)
@@ -73,25 +76,26 @@ __device__ __forceinline__ void build_ancestors(const int *par, int n, uint64_t 
     }
 }
 
-// Column of key `kappa` (0..63) in the transposed V tile: the eight keys that one
-// lane group feeds to one MFMA (two runs of four, 16 apart) become contiguous.
-__device__ __forceinline__ int vt_col(int kappa) {
-    const int j = kappa >> 5, a = (kappa >> 4) & 1, g = (kappa >> 2) & 3, r = kappa & 3;
-    return (j << 5) | (g << 3) | (a << 2) | r;
+// Transposing LDS read: within each block of 16 lanes, lane i supplies the address of four
+// contiguous 16-bit elements and receives element (i % 4) of the loads of lanes
+// i/4, 4 + i/4, 8 + i/4 and 12 + i/4.  Seen as a 4 x 16 tile (row k read by lanes 4k..4k+3,
+// four columns each), lane i ends up with column i of all four rows.
+__device__ __forceinline__ bf16x4 lds_read_tr(const __bf16 *p) {
+    return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p));
 }
 
 template <int D>
 __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArgs a) {
-    constexpr int KPAD = D + 8;       // K tile row stride (elements)
-    constexpr int VPAD = kTile + 8;   // V^T tile row stride (elements)
+    constexpr int KPAD = D + 8;       // K tile row stride (elements): conflict-free 16-byte reads
+    constexpr int VPAD = D + 16;      // V tile row stride (elements): conflict-free transposing reads
     constexpr int DCH = D / 8;        // 16-byte chunks per row
     constexpr int LPT = kTile * DCH / kAttnThreads;  // chunks per thread per tile
     constexpr int KS = D / 32;        // k-steps of the first product
     constexpr int DT = D / 16;        // output tiles of the second product
     extern __shared__ __align__(16) unsigned char smem[];
     __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);          // [2][kTile][KPAD]
-    __bf16 *Vt = Ks + 2 * kTile * KPAD;                     // [2][D][VPAD]
-    uint64_t *anc = reinterpret_cast<uint64_t *>(Vt + 2 * D * VPAD);  // [N][kAncWords]
+    __bf16 *Vs = Ks + 2 * kTile * KPAD;                     // [2][kTile][VPAD]
+    uint64_t *anc = reinterpret_cast<uint64_t *>(Vs + 2 * kTile * VPAD);  // [N][kAncWords]
 
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int rb = blockIdx.x / a.splits, sp = blockIdx.x - rb * a.splits;
@@ -160,19 +164,13 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     };
     auto store_tile = [&](int buf) {
         __bf16 *kdst = Ks + buf * kTile * KPAD;
-        unsigned short *vdst = reinterpret_cast<unsigned short *>(Vt + buf * D * VPAD);
+        __bf16 *vdst = Vs + buf * kTile * VPAD;
 #pragma unroll
         for (int it = 0; it < LPT; ++it) {
             const int c = it * kAttnThreads + tid;
             const int row = c / DCH, part = c - row * DCH;
             *reinterpret_cast<uint4 *>(kdst + row * KPAD + part * 8) = kr[it];
-            const int col = vt_col(row);
-            const uint32_t wv[4] = {vr[it].x, vr[it].y, vr[it].z, vr[it].w};
-#pragma unroll
-            for (int e = 0; e < 8; ++e) {
-                const unsigned short hv = (unsigned short)(wv[e >> 1] >> ((e & 1) * 16));
-                vdst[(part * 8 + e) * VPAD + col] = hv;
-            }
+            *reinterpret_cast<uint4 *>(vdst + row * VPAD + part * 8) = vr[it];
         }
     };
 
@@ -253,12 +251,17 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
 #pragma unroll
             for (int e = 0; e < 8; ++e) pf[j][e] = (__bf16)s[2 * j + (e >> 2)][e & 3];
         }
-        const __bf16 *vb = Vt + buf * D * VPAD;
+        // lane (c16, g) of the A operand needs V[key][16 dt + c16] for the keys
+        // 32 j + 16 a + 4 g + r (a = 0,1; r = 0..3): two transposing reads, in which this
+        // lane loads row 32 j + 16 a + 4 g + c16 / 4, columns 16 dt + 4 (c16 % 4) .. + 3.
+        const __bf16 *vb = Vs + buf * kTile * VPAD + (g * 4 + (c16 >> 2)) * VPAD + (c16 & 3) * 4;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const bf16x8 vf = *reinterpret_cast<const bf16x8 *>(vb + (dt * 16 + c16) * VPAD + j * 32 + g * 8);
+                const bf16x4 lo = lds_read_tr(vb + (j * 32) * VPAD + dt * 16);
+                const bf16x4 hi = lds_read_tr(vb + (j * 32 + 16) * VPAD + dt * 16);
+                const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[j], o[dt], 0, 0, 0);
             }
         }
@@ -423,7 +426,7 @@ static int choose_splits(int dtype, int B, int Hq, int Hkv, int N, int P_max, in
 
 template <int D>
 static size_t attn_smem_bytes(int N) {
-    return (size_t)2 * kTile * (D + 8) * 2 + (size_t)2 * D * (kTile + 8) * 2 + (size_t)N * kAncWords * 8;
+    return (size_t)2 * kTile * (D + 8) * 2 + (size_t)2 * kTile * (D + 16) * 2 + (size_t)N * kAncWords * 8;
 }
 
 }  // namespace rsd
