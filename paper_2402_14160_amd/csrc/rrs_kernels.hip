@@ -20,8 +20,9 @@
 
 namespace rsd {
 
-constexpr int kGroupThreads = 512;
-constexpr int kGroupWaves = kGroupThreads / kWave;
+constexpr int kGroupThreads = 512;   // streaming variant (any vocabulary size)
+constexpr int kRegThreads = 512;     // register-resident variant: 2 waves per SIMD, 256 VGPRs each
+constexpr int kGroupWaves = kRegThreads / kWave;
 constexpr int kFinalThreads = 512;
 constexpr int kFinalSplits = 8;
 
@@ -145,6 +146,11 @@ struct GroupShared {
     GroupRec g;
     MaxSum ms[kGroupWaves];
     double red[kGroupWaves];
+    double cu[RSD_K_MAX];  // children: unnormalised residual value of the child token (fp64)
+    double ce[RSD_K_MAX];  // children: draft exponential of the child token, 0 once removed
+    double alpha;          // q^(k) = alpha * (register value)
+    float gamma;           // stage factor applied to the draft exponentials
+    int ok;
     int cur;
     int done;
 };
@@ -257,8 +263,8 @@ __device__ double child_theta(const float *zt, const float *zd, float c2, int k,
 
 // Verify one sibling group: fills sh.g (children, scalars, thresholds).
 // All threads of the workgroup must call this.  Returns with sh.g visible to all.
-template <int THREADS>
-__device__ void process_group(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
+// Children of `node` in stored order (thread 0), then a barrier.
+__device__ __forceinline__ void scan_children(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
     const int *par = a.parent + (int64_t)b * a.N;
     const int *tok = a.tokens + (int64_t)b * a.N;
     if (threadIdx.x == 0) {
@@ -274,6 +280,11 @@ __device__ void process_group(const RrsArgs &a, int b, int node, int n, GroupSha
         sh.g.flags = 0;
     }
     __syncthreads();
+}
+
+template <int THREADS>
+__device__ void process_group(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
+    scan_children(a, b, node, n, sh);
     const int K = sh.g.K;
     if (K == 0) return;
     const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
@@ -296,6 +307,151 @@ __device__ void process_group(const RrsArgs &a, int b, int node, int n, GroupSha
         __syncthreads();
     }
     __syncthreads();
+}
+
+
+// Register-resident variant for vocabularies up to kRegThreads * 4 * CH entries: both logit
+// rows are read from memory once; each thread keeps its share of the target-side value
+// u(x) (q^(k) = alpha_k * u) and of the draft exponentials in registers, so a stage is
+//     S = sum_x max(u - gamma_k * e_d, 0);   u <- max(u - gamma_k * e_d, 0);   alpha_{k+1} = 1 / S
+// with gamma_k = 1 / (s_k * alpha_k): three to five ALU operations per entry and one
+// workgroup reduction.  The child tokens themselves are followed in fp64 by thread 0.
+template <int CH>
+__device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
+    constexpr int T = kRegThreads;
+    scan_children(a, b, node, n, sh);
+    const int K = sh.g.K;
+    if (K == 0) return;
+    const int tid = threadIdx.x;
+    const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
+    const float *zd = a.zd + ((int64_t)b * a.N + node) * a.V;
+    const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
+    const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
+    const int nchunk = a.V >> 2;
+    const float c2 = a.c2;
+    // bit (4 j + e) set: this thread's register entry (j, e) is a child token
+    uint64_t elmask = 0;
+    for (int i = 0; i < K; ++i) {
+        const int x = sh.g.tok[i], c = x >> 2;
+        if (c % T == tid) elmask |= 1ull << (((c / T) << 2) | (x & 3));
+    }
+
+    float ut[CH * 4], ed[CH * 4];
+    float mt = -INFINITY, md = -INFINITY;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const int c = j * T + tid;
+        if (c < nchunk) {
+            const float4 t = zt4[c];
+            const float4 d = zd4[c];
+            ut[4 * j + 0] = t.x * c2; ut[4 * j + 1] = t.y * c2; ut[4 * j + 2] = t.z * c2; ut[4 * j + 3] = t.w * c2;
+            ed[4 * j + 0] = d.x * c2; ed[4 * j + 1] = d.y * c2; ed[4 * j + 2] = d.z * c2; ed[4 * j + 3] = d.w * c2;
+        } else {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) { ut[4 * j + e] = -INFINITY; ed[4 * j + e] = -INFINITY; }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) { mt = fmaxf(mt, ut[4 * j + e]); md = fmaxf(md, ed[4 * j + e]); }
+    }
+    // row maxima
+    mt = wave_max(mt);
+    md = wave_max(md);
+    if ((tid & (kWave - 1)) == 0) sh.ms[tid / kWave] = MaxSum{mt, md};
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < T / kWave; ++w) { mt = fmaxf(mt, sh.ms[w].m); md = fmaxf(md, sh.ms[w].s); }
+    __syncthreads();
+    const float mt_use = (mt == -INFINITY) ? 0.f : mt, md_use = (md == -INFINITY) ? 0.f : md;
+    // exponentials in place; the draft sum leaves out every child token
+    float st = 0.f, sd = 0.f;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            ut[4 * j + e] = __builtin_amdgcn_exp2f(ut[4 * j + e] - mt_use);
+            ed[4 * j + e] = __builtin_amdgcn_exp2f(ed[4 * j + e] - md_use);
+        }
+        st += (ut[4 * j] + ut[4 * j + 1]) + (ut[4 * j + 2] + ut[4 * j + 3]);
+        float dsum[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) dsum[e] = ((elmask >> (4 * j + e)) & 1ull) ? 0.f : ed[4 * j + e];
+        sd += (dsum[0] + dsum[1]) + (dsum[2] + dsum[3]);
+    }
+    const double St = block_sum<T>((double)st, sh.red);
+    const double Sd = block_sum<T>((double)sd, sh.red);
+    if (tid < K) {
+        const int x = sh.g.tok[tid];
+        sh.cu[tid] = exp2((double)zt[x] * (double)c2 - (double)mt_use);
+        sh.ce[tid] = exp2((double)zd[x] * (double)c2 - (double)md_use);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        sh.g.mt2 = mt_use;
+        sh.g.md2 = md_use;
+        sh.g.inv_st = (float)(1.0 / St);
+        double s = Sd;
+        for (int k = RSD_K_MAX - 1; k >= 0; --k) {
+            if (k < K) {
+                s += sh.ce[k];
+                sh.g.inv_s[k] = (float)(1.0 / s);
+            } else {
+                sh.g.inv_s[k] = 0.f;
+            }
+            sh.g.inv_S[k] = 1.f;
+        }
+        if (!(St > 0.0) || !isfinite(St) || !(s > 0.0) || !isfinite(s)) sh.g.flags |= RSD_FLAG_NONFINITE;
+        sh.alpha = 1.0 / St;
+    }
+    __syncthreads();
+    for (int k = 0; k < K; ++k) {
+        if (tid == 0) {
+            const double p = sh.ce[k] * (double)sh.g.inv_s[k];
+            sh.g.theta[k] = (p > 0.0) ? (float)fmin(1.0, sh.cu[k] * sh.alpha / p) : 1.f;
+            sh.gamma = (float)((double)sh.g.inv_s[k] / sh.alpha);
+        }
+        if (k == K - 1) break;
+        __syncthreads();
+        const float gamma = sh.gamma;
+        float part = 0.f;
+#pragma unroll
+        for (int i = 0; i < CH * 4; ++i) part += fmaxf(fmaf(-gamma, ed[i], ut[i]), 0.f);
+        const double S = block_sum<T>((double)part, sh.red);
+        if (tid == 0) {
+            const bool ok = S > 0.0 && isfinite(S);
+            if (ok) {
+                sh.g.inv_S[k] = (float)(1.0 / (sh.alpha * S));
+                for (int t = 0; t < K; ++t) sh.cu[t] = fmax(sh.cu[t] - (double)gamma * sh.ce[t], 0.0);
+                sh.alpha = 1.0 / S;
+            } else {  // keep q^(k)
+                sh.g.inv_s[k] = 0.f;
+                sh.g.inv_S[k] = 1.f;
+                sh.g.flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
+            }
+            sh.ce[k] = 0.0;  // x_k leaves the draft distribution either way
+            sh.ok = ok;
+        }
+        __syncthreads();
+        if (sh.ok) {
+#pragma unroll
+            for (int i = 0; i < CH * 4; ++i) ut[i] = fmaxf(fmaf(-gamma, ed[i], ut[i]), 0.f);
+        }
+        if (elmask != 0ull) {  // x_k leaves the draft distribution: clear it where it lives
+            const int xk = sh.g.tok[k], ck = xk >> 2;
+            const int target = (ck % T == tid) ? (((ck / T) << 2) | (xk & 3)) : -1;
+#pragma unroll
+            for (int i = 0; i < CH * 4; ++i)
+                if (i == target) ed[i] = 0.f;
+        }
+    }
+    __syncthreads();
+}
+
+template <int THREADS, int CH>
+__device__ __forceinline__ void verify_group(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
+    if constexpr (CH > 0)
+        process_group_reg<CH>(a, b, node, n, sh);
+    else
+        process_group<THREADS>(a, b, node, n, sh);
 }
 
 // ---------------------------------------------------------------------------
@@ -375,24 +531,25 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
 // ---------------------------------------------------------------------------
 // ALL_GROUPS, kernel 1: one workgroup per (node, sequence).
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kGroupThreads) void rrs_group_kernel(RrsArgs a) {
+template <int THREADS, int CH>
+__global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
     const int node = blockIdx.x;
     const int b = blockIdx.y;
     const int n = min(max(a.n_nodes[b], 1), a.N);
     if (node >= n) return;
-    process_group<kGroupThreads>(a, b, node, n, sh);
+    verify_group<THREADS, CH>(a, b, node, n, sh);
     GroupRec *out = a.rec + (int64_t)b * a.N + node;
     // copy the record (a few hundred bytes) to workspace
     const int words = sizeof(GroupRec) / 4;
     const uint32_t *src = reinterpret_cast<const uint32_t *>(&sh.g);
     uint32_t *dst = reinterpret_cast<uint32_t *>(out);
-    for (int i = threadIdx.x; i < words; i += kGroupThreads) dst[i] = src[i];
+    for (int i = threadIdx.x; i < words; i += THREADS) dst[i] = src[i];
     if (a.theta) {
         // children beyond the supported group size are not verified: mark them
         const int *par = a.parent + (int64_t)b * a.N;
         const int last = sh.g.K > 0 ? sh.g.kid[sh.g.K - 1] : node;
-        for (int j = last + 1 + (int)threadIdx.x; j < n; j += kGroupThreads)
+        for (int j = last + 1 + (int)threadIdx.x; j < n; j += THREADS)
             if (par[j] == node) a.theta[(int64_t)b * a.N + j] = NAN;
         if ((int)threadIdx.x < sh.g.K)
             a.theta[(int64_t)b * a.N + sh.g.kid[threadIdx.x]] = sh.g.theta[threadIdx.x];
@@ -512,20 +669,21 @@ __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
 // PATH mode: one persistent workgroup per sequence verifies only the groups on
 // the accepted path, then draws the last token.
 // ---------------------------------------------------------------------------
-__global__ __launch_bounds__(kGroupThreads) void rrs_path_kernel(RrsArgs a) {
+template <int THREADS, int CH>
+__global__ __launch_bounds__(THREADS) void rrs_path_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
-    __shared__ float s_v[kGroupWaves];
-    __shared__ int s_i[kGroupWaves];
+    __shared__ float s_v[THREADS / kWave];
+    __shared__ int s_i[THREADS / kWave];
     __shared__ int s_nacc;
     __shared__ uint32_t s_flags;
     const int b = blockIdx.x;
     const int tid = threadIdx.x;
     const int n = min(max(a.n_nodes[b], 1), a.N);
-    for (int j = tid; j < a.N; j += kGroupThreads) {
+    for (int j = tid; j < a.N; j += THREADS) {
         if (a.uniforms) a.uniforms[(int64_t)b * a.N + j] = (j < n) ? accept_uniform(a, b, j) : 0.f;
         if (a.theta) a.theta[(int64_t)b * a.N + j] = NAN;
     }
-    for (int j = tid; j < a.depth_max; j += kGroupThreads) {
+    for (int j = tid; j < a.depth_max; j += THREADS) {
         a.accepted_nodes[(int64_t)b * a.depth_max + j] = -1;
         if (a.accepted_tokens) a.accepted_tokens[(int64_t)b * a.depth_max + j] = -1;
     }
@@ -538,7 +696,7 @@ __global__ __launch_bounds__(kGroupThreads) void rrs_path_kernel(RrsArgs a) {
     __syncthreads();
     for (int guard = 0; guard < a.N; ++guard) {
         const int cur = sh.cur;
-        process_group<kGroupThreads>(a, b, cur, n, sh);
+        verify_group<THREADS, CH>(a, b, cur, n, sh);
         const int K = sh.g.K;
         if (K == 0) break;
         if (tid == 0) {
@@ -577,9 +735,9 @@ __global__ __launch_bounds__(kGroupThreads) void rrs_path_kernel(RrsArgs a) {
     const int node = sh.cur;
     float bv, av;
     int bi, ai;
-    final_sample_range<kGroupThreads>(a, b, node, sh.g, 0, a.V >> 2, bv, bi, av, ai);
-    block_argmax<kGroupThreads>(bv, bi, s_v, s_i);
-    block_argmax<kGroupThreads>(av, ai, s_v, s_i);
+    final_sample_range<THREADS>(a, b, node, sh.g, 0, a.V >> 2, bv, bi, av, ai);
+    block_argmax<THREADS>(bv, bi, s_v, s_i);
+    block_argmax<THREADS>(av, ai, s_v, s_i);
     if (tid == 0) {
         uint32_t flags = s_flags;
         int tokn = bi;
@@ -646,10 +804,17 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
     a.fnode = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * 4, 256);
     a.fflags = reinterpret_cast<uint32_t *>(ws + off);
     hipStream_t st = (hipStream_t)stream;
+    const bool reg8 = V <= kRegThreads * 4 * 16;
     if (mode == RSD_MODE_PATH) {
-        hipLaunchKernelGGL(rrs_path_kernel, dim3(B), dim3(kGroupThreads), 0, st, a);
+        if (reg8)
+            hipLaunchKernelGGL((rrs_path_kernel<kRegThreads, 16>), dim3(B), dim3(kRegThreads), 0, st, a);
+        else
+            hipLaunchKernelGGL((rrs_path_kernel<kGroupThreads, 0>), dim3(B), dim3(kGroupThreads), 0, st, a);
     } else {
-        hipLaunchKernelGGL(rrs_group_kernel, dim3(N_max, B), dim3(kGroupThreads), 0, st, a);
+        if (reg8)
+            hipLaunchKernelGGL((rrs_group_kernel<kRegThreads, 16>), dim3(N_max, B), dim3(kRegThreads), 0, st, a);
+        else
+            hipLaunchKernelGGL((rrs_group_kernel<kGroupThreads, 0>), dim3(N_max, B), dim3(kGroupThreads), 0, st, a);
         hipLaunchKernelGGL(rrs_walk_kernel, dim3(B), dim3(kWave), 0, st, a);
         hipLaunchKernelGGL(rrs_final_kernel, dim3(kFinalSplits, B), dim3(kFinalThreads), 0, st, a);
     }
