@@ -68,6 +68,9 @@ struct RrsArgs {
     int *fdone;                 // [B]
     int *fnode;                 // [B]
     uint32_t *fflags;           // [B]
+    int *kcount;                // [B, N] number of children of every node
+    int *work;                  // [B, N] non-leaf nodes (b * N + node), most children first
+    int *wq;                    // [0] number of work items, [1] next item to take
 };
 
 __device__ __forceinline__ int removal_stage(int x, const int *tok, int K) {
@@ -146,11 +149,10 @@ struct GroupShared {
     GroupRec g;
     MaxSum ms[kGroupWaves];
     double red[kGroupWaves];
-    double cu[RSD_K_MAX];  // children: unnormalised residual value of the child token (fp64)
-    double ce[RSD_K_MAX];  // children: draft exponential of the child token, 0 once removed
-    double alpha;          // q^(k) = alpha * (register value)
-    float gamma;           // stage factor applied to the draft exponentials
-    int ok;
+    double red2[kGroupWaves];
+    double ce[RSD_K_MAX];   // draft exponentials of the child tokens (fp64)
+    double isk[RSD_K_MAX];  // 1 / s_k in fp64
+    unsigned long long cmask[RSD_NODES_MAX / kWave];  // per-wave ballots of the child scan
     int cur;
     int done;
 };
@@ -245,7 +247,7 @@ __device__ double group_residual_mass(const float *zt, const float *zd, int V, f
         }
         part += (r[0] + r[1]) + (r[2] + r[3]);
     }
-    return block_sum<THREADS>((double)part, sh.red);
+    return block_sum<THREADS>(part, sh.red);
 }
 
 // Threshold of child k (Eq. (3)) from the scalars found so far, in fp64.
@@ -263,20 +265,33 @@ __device__ double child_theta(const float *zt, const float *zd, float c2, int k,
 
 // Verify one sibling group: fills sh.g (children, scalars, thresholds).
 // All threads of the workgroup must call this.  Returns with sh.g visible to all.
-// Children of `node` in stored order (thread 0), then a barrier.
+// Children of `node` in stored order: the first RSD_NODES_MAX threads test one node each,
+// wave ballots give every match its rank.  Ends with a barrier.
 __device__ __forceinline__ void scan_children(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
     const int *par = a.parent + (int64_t)b * a.N;
     const int *tok = a.tokens + (int64_t)b * a.N;
-    if (threadIdx.x == 0) {
-        int K = 0;
-        for (int j = node + 1; j < n && K < RSD_K_MAX; ++j) {
-            if (par[j] == node) {
-                sh.g.kid[K] = j;
-                sh.g.tok[K] = min(max(tok[j], 0), a.V - 1);   // never index outside the row
-                ++K;
-            }
+    const int j = threadIdx.x, lane = j & (kWave - 1), wave = j / kWave;
+    bool match = false;
+    int t = 0;
+    if (j > node && j < n) {
+        match = par[j] == node;
+        t = tok[j];
+    }
+    const unsigned long long mask = __ballot(match);
+    if (wave < RSD_NODES_MAX / kWave && lane == 0) sh.cmask[wave] = mask;
+    __syncthreads();
+    if (match) {
+        int rank = __popcll(mask & ((1ull << lane) - 1ull));
+        for (int w = 0; w < wave; ++w) rank += __popcll(sh.cmask[w]);
+        if (rank < RSD_K_MAX) {
+            sh.g.kid[rank] = j;
+            sh.g.tok[rank] = min(max(t, 0), a.V - 1);  // never index outside the row
         }
-        sh.g.K = K;
+    }
+    if (j == 0) {
+        int total = 0;
+        for (int w = 0; w < RSD_NODES_MAX / kWave; ++w) total += __popcll(sh.cmask[w]);
+        sh.g.K = min(total, RSD_K_MAX);
         sh.g.flags = 0;
     }
     __syncthreads();
@@ -312,17 +327,19 @@ __device__ void process_group(const RrsArgs &a, int b, int node, int n, GroupSha
 
 // Register-resident variant for vocabularies up to kRegThreads * 4 * CH entries: both logit
 // rows are read from memory once; each thread keeps its share of the target-side value
-// u(x) (q^(k) = alpha_k * u) and of the draft exponentials in registers, so a stage is
-//     S = sum_x max(u - gamma_k * e_d, 0);   u <- max(u - gamma_k * e_d, 0);   alpha_{k+1} = 1 / S
-// with gamma_k = 1 / (s_k * alpha_k): three to five ALU operations per entry and one
-// workgroup reduction.  The child tokens themselves are followed in fp64 by thread 0.
+// u(x) (q^(k) = u / A_k) and of the draft exponentials e_d(x) in registers, so a stage is
+//     S = sum_x max(u - gamma_k * e_d, 0);   u <- max(u - gamma_k * e_d, 0);   A_{k+1} = S
+// with gamma_k = A_k / s_k: three to five ALU operations per entry, one wave reduction and a
+// single barrier.  Every thread carries the scalars; lane t < K follows child token t in fp64.
 template <int CH>
 __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
     constexpr int T = kRegThreads;
+    constexpr int NW = T / kWave;
     scan_children(a, b, node, n, sh);
     const int K = sh.g.K;
     if (K == 0) return;
-    const int tid = threadIdx.x;
+    const int tid = threadIdx.x, wave = tid / kWave;
+    const bool lane0 = (tid & (kWave - 1)) == 0;
     const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
     const float *zd = a.zd + ((int64_t)b * a.N + node) * a.V;
     const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
@@ -353,14 +370,19 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
 #pragma unroll
         for (int e = 0; e < 4; ++e) { mt = fmaxf(mt, ut[4 * j + e]); md = fmaxf(md, ed[4 * j + e]); }
     }
+    // children: lane t < K reads its token's two logits (fp64 follow-up of the child tokens)
+    double cu = 0.0, ce = 0.0;
+    if (tid < K) {
+        cu = (double)zt[sh.g.tok[tid]] * (double)c2;
+        ce = (double)zd[sh.g.tok[tid]] * (double)c2;
+    }
     // row maxima
     mt = wave_max(mt);
     md = wave_max(md);
-    if ((tid & (kWave - 1)) == 0) sh.ms[tid / kWave] = MaxSum{mt, md};
+    if (lane0) sh.ms[wave] = MaxSum{mt, md};
     __syncthreads();
 #pragma unroll
-    for (int w = 0; w < T / kWave; ++w) { mt = fmaxf(mt, sh.ms[w].m); md = fmaxf(md, sh.ms[w].s); }
-    __syncthreads();
+    for (int w = 0; w < NW; ++w) { mt = fmaxf(mt, sh.ms[w].m); md = fmaxf(md, sh.ms[w].s); }
     const float mt_use = (mt == -INFINITY) ? 0.f : mt, md_use = (md == -INFINITY) ? 0.f : md;
     // exponentials in place; the draft sum leaves out every child token
     float st = 0.f, sd = 0.f;
@@ -377,65 +399,71 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
         for (int e = 0; e < 4; ++e) dsum[e] = ((elmask >> (4 * j + e)) & 1ull) ? 0.f : ed[4 * j + e];
         sd += (dsum[0] + dsum[1]) + (dsum[2] + dsum[3]);
     }
-    const double St = block_sum<T>((double)st, sh.red);
-    const double Sd = block_sum<T>((double)sd, sh.red);
+    st = wave_sum(st);
+    sd = wave_sum(sd);
     if (tid < K) {
-        const int x = sh.g.tok[tid];
-        sh.cu[tid] = exp2((double)zt[x] * (double)c2 - (double)mt_use);
-        sh.ce[tid] = exp2((double)zd[x] * (double)c2 - (double)md_use);
+        cu = exp2(cu - (double)mt_use);
+        ce = exp2(ce - (double)md_use);
+        sh.ce[tid] = ce;
+    }
+    if (lane0) {
+        sh.red[wave] = (double)st;
+        sh.red2[wave] = (double)sd;
     }
     __syncthreads();
-    if (tid == 0) {
-        sh.g.mt2 = mt_use;
-        sh.g.md2 = md_use;
-        sh.g.inv_st = (float)(1.0 / St);
+    double St = 0.0, Sd = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { St += sh.red[w]; Sd += sh.red2[w]; }
+    // draft mass still available at stage k: the rest plus the children not yet removed
+    if (tid < RSD_K_MAX) {
         double s = Sd;
-        for (int k = RSD_K_MAX - 1; k >= 0; --k) {
-            if (k < K) {
-                s += sh.ce[k];
-                sh.g.inv_s[k] = (float)(1.0 / s);
-            } else {
-                sh.g.inv_s[k] = 0.f;
-            }
-            sh.g.inv_S[k] = 1.f;
+        for (int i = K - 1; i >= tid; --i) s += sh.ce[i];
+        const double inv = (tid < K) ? 1.0 / s : 0.0;
+        sh.isk[tid] = inv;
+        sh.g.inv_s[tid] = (float)inv;
+        sh.g.inv_S[tid] = 1.f;
+        if (tid == 0) {
+            sh.g.mt2 = mt_use;
+            sh.g.md2 = md_use;
+            sh.g.inv_st = (float)(1.0 / St);
+            if (!(St > 0.0) || !isfinite(St) || !(s > 0.0) || !isfinite(s)) sh.g.flags |= RSD_FLAG_NONFINITE;
         }
-        if (!(St > 0.0) || !isfinite(St) || !(s > 0.0) || !isfinite(s)) sh.g.flags |= RSD_FLAG_NONFINITE;
-        sh.alpha = 1.0 / St;
     }
     __syncthreads();
+    double A = St;  // q^(k) = u / A
     for (int k = 0; k < K; ++k) {
-        if (tid == 0) {
-            const double p = sh.ce[k] * (double)sh.g.inv_s[k];
-            sh.g.theta[k] = (p > 0.0) ? (float)fmin(1.0, sh.cu[k] * sh.alpha / p) : 1.f;
-            sh.gamma = (float)((double)sh.g.inv_s[k] / sh.alpha);
+        const double inv_sk = sh.isk[k];
+        if (tid == k) {  // threshold of child k (Eq. (3))
+            const double p = ce * inv_sk;
+            sh.g.theta[k] = (p > 0.0) ? (float)fmin(1.0, cu / (A * p)) : 1.f;
         }
         if (k == K - 1) break;
-        __syncthreads();
-        const float gamma = sh.gamma;
+        const float gamma = (float)(inv_sk * A);
         float part = 0.f;
 #pragma unroll
         for (int i = 0; i < CH * 4; ++i) part += fmaxf(fmaf(-gamma, ed[i], ut[i]), 0.f);
-        const double S = block_sum<T>((double)part, sh.red);
-        if (tid == 0) {
-            const bool ok = S > 0.0 && isfinite(S);
-            if (ok) {
-                sh.g.inv_S[k] = (float)(1.0 / (sh.alpha * S));
-                for (int t = 0; t < K; ++t) sh.cu[t] = fmax(sh.cu[t] - (double)gamma * sh.ce[t], 0.0);
-                sh.alpha = 1.0 / S;
-            } else {  // keep q^(k)
-                sh.g.inv_s[k] = 0.f;
-                sh.g.inv_S[k] = 1.f;
-                sh.g.flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
-            }
-            sh.ce[k] = 0.0;  // x_k leaves the draft distribution either way
-            sh.ok = ok;
-        }
+        part = wave_sum(part);
+        double *red = (k & 1) ? sh.red2 : sh.red;
+        if (lane0) red[wave] = (double)part;
         __syncthreads();
-        if (sh.ok) {
+        double S = 0.0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) S += red[w];
+        const bool ok = S > 0.0 && isfinite(S);
+        if (ok) {
 #pragma unroll
             for (int i = 0; i < CH * 4; ++i) ut[i] = fmaxf(fmaf(-gamma, ed[i], ut[i]), 0.f);
+            if (tid < K) cu = fmax(cu - (double)gamma * ce, 0.0);
+            if (tid == 0) sh.g.inv_S[k] = (float)(A / S);
+            A = S;
+        } else if (tid == 0) {  // keep q^(k): no subtraction, no rescale
+            sh.g.inv_s[k] = 0.f;
+            sh.g.inv_S[k] = 1.f;
+            sh.g.flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
         }
-        if (elmask != 0ull) {  // x_k leaves the draft distribution: clear it where it lives
+        // x_k leaves the draft distribution either way
+        if (tid == k) ce = 0.0;
+        if (elmask != 0ull) {
             const int xk = sh.g.tok[k], ck = xk >> 2;
             const int target = (ck % T == tid) ? (((ck / T) << 2) | (xk & 3)) : -1;
 #pragma unroll
@@ -529,30 +557,86 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
 }
 
 // ---------------------------------------------------------------------------
-// ALL_GROUPS, kernel 1: one workgroup per (node, sequence).
+// ALL_GROUPS, kernel 0 (one workgroup): count the children of every node and list the
+// non-leaf nodes, those with the most children first, as work items for kernel 1.
+// ---------------------------------------------------------------------------
+constexpr int kPlanThreads = 1024;
+
+__global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
+    __shared__ int hist[RSD_K_MAX + 1];
+    __shared__ int offs[RSD_K_MAX + 1];
+    const int tid = threadIdx.x;
+    const int total = a.B * a.N;
+    for (int i = tid; i < total; i += kPlanThreads) a.kcount[i] = 0;
+    if (tid <= RSD_K_MAX) hist[tid] = 0;
+    if (tid == 0) {
+        a.wq[0] = 0;
+        a.wq[1] = 0;
+    }
+    __syncthreads();
+    for (int i = tid; i < total; i += kPlanThreads) {
+        const int b = i / a.N, j = i - b * a.N;
+        const int n = min(max(a.n_nodes[b], 1), a.N);
+        if (j >= 1 && j < n) {
+            const int p = a.parent[i];
+            if (p >= 0 && p < j) atomicAdd(&a.kcount[b * a.N + p], 1);
+        }
+    }
+    __syncthreads();
+    for (int i = tid; i < total; i += kPlanThreads) {
+        const int k = min(a.kcount[i], RSD_K_MAX);
+        if (k > 0) atomicAdd(&hist[k], 1);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        int running = 0;
+        for (int k = RSD_K_MAX; k >= 1; --k) {
+            offs[k] = running;
+            running += hist[k];
+        }
+        a.wq[0] = running;
+    }
+    __syncthreads();
+    for (int i = tid; i < total; i += kPlanThreads) {
+        const int k = min(a.kcount[i], RSD_K_MAX);
+        if (k > 0) a.work[atomicAdd(&offs[k], 1)] = i;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// ALL_GROUPS, kernel 1: persistent workgroups take sibling groups from the work list
+// until it is empty (every workgroup leaves the loop once the shared counter passes the
+// item count).
 // ---------------------------------------------------------------------------
 template <int THREADS, int CH>
 __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
-    const int node = blockIdx.x;
-    const int b = blockIdx.y;
-    const int n = min(max(a.n_nodes[b], 1), a.N);
-    if (node >= n) return;
-    verify_group<THREADS, CH>(a, b, node, n, sh);
-    GroupRec *out = a.rec + (int64_t)b * a.N + node;
-    // copy the record (a few hundred bytes) to workspace
-    const int words = sizeof(GroupRec) / 4;
-    const uint32_t *src = reinterpret_cast<const uint32_t *>(&sh.g);
-    uint32_t *dst = reinterpret_cast<uint32_t *>(out);
-    for (int i = threadIdx.x; i < words; i += THREADS) dst[i] = src[i];
-    if (a.theta) {
-        // children beyond the supported group size are not verified: mark them
-        const int *par = a.parent + (int64_t)b * a.N;
-        const int last = sh.g.K > 0 ? sh.g.kid[sh.g.K - 1] : node;
-        for (int j = last + 1 + (int)threadIdx.x; j < n; j += THREADS)
-            if (par[j] == node) a.theta[(int64_t)b * a.N + j] = NAN;
-        if ((int)threadIdx.x < sh.g.K)
-            a.theta[(int64_t)b * a.N + sh.g.kid[threadIdx.x]] = sh.g.theta[threadIdx.x];
+    __shared__ int s_item;
+    const int count = a.wq[0];
+    for (;;) {
+        if (threadIdx.x == 0) s_item = atomicAdd(&a.wq[1], 1);
+        __syncthreads();
+        const int item = s_item;
+        if (item >= count) break;
+        const int i = a.work[item];
+        const int b = i / a.N, node = i - b * a.N;
+        const int n = min(max(a.n_nodes[b], 1), a.N);
+        verify_group<THREADS, CH>(a, b, node, n, sh);
+        GroupRec *out = a.rec + i;
+        const int words = sizeof(GroupRec) / 4;
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(&sh.g);
+        uint32_t *dst = reinterpret_cast<uint32_t *>(out);
+        for (int w = threadIdx.x; w < words; w += THREADS) dst[w] = src[w];
+        if (a.theta) {
+            // children beyond the supported group size are not verified: mark them
+            const int *par = a.parent + (int64_t)b * a.N;
+            const int last = sh.g.K > 0 ? sh.g.kid[sh.g.K - 1] : node;
+            for (int j = last + 1 + (int)threadIdx.x; j < n; j += THREADS)
+                if (par[j] == node) a.theta[(int64_t)b * a.N + j] = NAN;
+            if ((int)threadIdx.x < sh.g.K)
+                a.theta[(int64_t)b * a.N + sh.g.kid[threadIdx.x]] = sh.g.theta[threadIdx.x];
+        }
+        __syncthreads();  // sh and s_item are reused by the next item
     }
 }
 
@@ -583,6 +667,7 @@ __global__ __launch_bounds__(kWave) void rrs_walk_kernel(RrsArgs a) {
     int cur = 0, nacc = 0;
     uint32_t flags = 0;
     for (int guard = 0; guard < a.N; ++guard) {
+        if (a.kcount[(int64_t)b * a.N + cur] == 0) break;  // leaf: no record was written
         const GroupRec &g = a.rec[(int64_t)b * a.N + cur];
         const int K = g.K;
         if (K == 0) break;
@@ -627,11 +712,13 @@ __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
     const int b = blockIdx.y;
     const int split = blockIdx.x;
     const int node = a.fnode[b];
-    {
+    if (a.kcount[(int64_t)b * a.N + node] > 0) {
         const int words = sizeof(GroupRec) / 4;
         const uint32_t *src = reinterpret_cast<const uint32_t *>(a.rec + (int64_t)b * a.N + node);
         uint32_t *dst = reinterpret_cast<uint32_t *>(&g);
         for (int i = threadIdx.x; i < words; i += kFinalThreads) dst[i] = src[i];
+    } else if (threadIdx.x == 0) {
+        g.K = 0;  // leaf: sample from the target row itself
     }
     __syncthreads();
     const int nchunk = a.V >> 2;
@@ -765,7 +852,7 @@ using namespace rsd;
 extern "C" size_t rsd_recursive_reject_workspace_bytes(int32_t B, int32_t N_max, int32_t) {
     if (B <= 0 || N_max <= 0) return 0;
     return align_up((size_t)B * N_max * sizeof(GroupRec), 256) + align_up((size_t)B * 16, 256) +
-           3 * align_up((size_t)B * 4, 256);
+           3 * align_up((size_t)B * 4, 256) + 2 * align_up((size_t)B * N_max * 4, 256) + 256;
 }
 
 extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *target_logits,
@@ -802,7 +889,10 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
     a.fkey = reinterpret_cast<unsigned long long *>(ws + off); off += align_up((size_t)B * 16, 256);
     a.fdone = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * 4, 256);
     a.fnode = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * 4, 256);
-    a.fflags = reinterpret_cast<uint32_t *>(ws + off);
+    a.fflags = reinterpret_cast<uint32_t *>(ws + off); off += align_up((size_t)B * 4, 256);
+    a.kcount = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * N_max * 4, 256);
+    a.work = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * N_max * 4, 256);
+    a.wq = reinterpret_cast<int *>(ws + off);
     hipStream_t st = (hipStream_t)stream;
     const bool reg8 = V <= kRegThreads * 4 * 16;
     if (mode == RSD_MODE_PATH) {
@@ -811,10 +901,21 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
         else
             hipLaunchKernelGGL((rrs_path_kernel<kGroupThreads, 0>), dim3(B), dim3(kGroupThreads), 0, st, a);
     } else {
+        static int n_cu = 0;
+        if (n_cu == 0) {
+            int dev = 0, cus = 0;
+            if (hipGetDevice(&dev) != hipSuccess ||
+                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
+                cus = 256;
+            n_cu = cus;
+        }
+        const long items_max = (long)B * N_max;
+        const int grid = (int)(items_max < n_cu ? items_max : n_cu);
+        hipLaunchKernelGGL(rrs_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a);
         if (reg8)
-            hipLaunchKernelGGL((rrs_group_kernel<kRegThreads, 16>), dim3(N_max, B), dim3(kRegThreads), 0, st, a);
+            hipLaunchKernelGGL((rrs_group_kernel<kRegThreads, 16>), dim3(grid), dim3(kRegThreads), 0, st, a);
         else
-            hipLaunchKernelGGL((rrs_group_kernel<kGroupThreads, 0>), dim3(N_max, B), dim3(kGroupThreads), 0, st, a);
+            hipLaunchKernelGGL((rrs_group_kernel<kGroupThreads, 0>), dim3(2 * grid), dim3(kGroupThreads), 0, st, a);
         hipLaunchKernelGGL(rrs_walk_kernel, dim3(B), dim3(kWave), 0, st, a);
         hipLaunchKernelGGL(rrs_final_kernel, dim3(kFinalSplits, B), dim3(kFinalThreads), 0, st, a);
     }

@@ -65,24 +65,33 @@ __device__ __forceinline__ float gumbel_from_word(uint32_t w) {
 }
 
 // ---------------------------------------------------------------------------
-// Wavefront reductions (all 64 lanes receive the result).
+// Wavefront reductions (all 64 lanes receive the result).  The fp32 sum and max
+// use DPP lane permutes inside each row of 16 lanes (no LDS traffic), then
+// combine the four rows through scalar lane reads; the order is fixed.
 // ---------------------------------------------------------------------------
+template <int CTRL>
+__device__ __forceinline__ float dpp_move(float v) {
+    return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(v), CTRL, 0xF, 0xF, false));
+}
+
+__device__ __forceinline__ float read_lane(float v, int lane) {
+    return __int_as_float(__builtin_amdgcn_readlane(__float_as_int(v), lane));
+}
+
 __device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, kWave));
-    return v;
+    v = fmaxf(v, dpp_move<0xB1>(v));   // quad_perm [1,0,3,2]
+    v = fmaxf(v, dpp_move<0x4E>(v));   // quad_perm [2,3,0,1]
+    v = fmaxf(v, dpp_move<0x124>(v));  // row_ror 4
+    v = fmaxf(v, dpp_move<0x128>(v));  // row_ror 8
+    return fmaxf(fmaxf(read_lane(v, 0), read_lane(v, 16)), fmaxf(read_lane(v, 32), read_lane(v, 48)));
 }
 
 __device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
-}
-
-__device__ __forceinline__ double wave_sum(double v) {
-#pragma unroll
-    for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, kWave);
-    return v;
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x124>(v);
+    v += dpp_move<0x128>(v);
+    return (read_lane(v, 0) + read_lane(v, 16)) + (read_lane(v, 32) + read_lane(v, 48));
 }
 
 // (value, index) ordering used by every selection: larger value first, on
@@ -145,13 +154,14 @@ __device__ __forceinline__ MaxSum block_merge(MaxSum v, MaxSum *scratch) {
     return r;
 }
 
-// Workgroup-wide sum in double (fixed order: lanes by xor tree, waves in order).
+// Workgroup-wide sum of fp32 partials: fp32 inside a wave (fixed DPP order), fp64 across
+// the waves in wave order.  Two barriers.
 template <int THREADS>
-__device__ __forceinline__ double block_sum(double v, double *scratch) {
+__device__ __forceinline__ double block_sum(float part, double *scratch) {
     constexpr int NW = THREADS / kWave;
-    v = wave_sum(v);
+    const float v = wave_sum(part);
     const int wave = threadIdx.x / kWave;
-    if ((threadIdx.x & (kWave - 1)) == 0) scratch[wave] = v;
+    if ((threadIdx.x & (kWave - 1)) == 0) scratch[wave] = (double)v;
     __syncthreads();
     double r = 0.0;
 #pragma unroll
