@@ -1,0 +1,95 @@
+"""CPU-side checks of the C ABI: the library loads, exports every declared symbol,
+and rejects bad arguments before touching the GPU."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2402_14160_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+HEADER = os.path.join(ROOT, "include", "rsd.h")
+
+if not os.path.exists(binding.LIB_PATH):
+    pytest.skip("librsd.so is not built (run __graft_entry__.build())", allow_module_level=True)
+
+
+def declared_functions():
+    text = open(HEADER).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(rsd_[a-z_0-9]+)\s*\(", text)))
+
+
+def test_every_declared_symbol_is_exported_and_bound():
+    names = declared_functions()
+    assert "rsd_gumbel_topk" in names and "rsd_sbs_step" in names
+    assert "rsd_tree_attention" in names and "rsd_recursive_reject" in names
+    handle = ctypes.CDLL(binding.LIB_PATH)
+    for name in names:
+        assert hasattr(handle, name), name
+    assert sorted(binding.exported_symbols()) == names
+
+
+def test_status_strings_and_version():
+    lib = binding.lib()
+    assert lib.rsd_version() >= 100
+    seen = set()
+    for code in range(0, -7, -1):
+        text = lib.rsd_status_string(code)
+        assert text and text not in seen
+        seen.add(text)
+    assert lib.rsd_status_string(-99) == b"unknown status"
+
+
+def test_host_tree_validation():
+    assert binding.validate_tree([-1]) == 0
+    assert binding.validate_tree([-1, 0, 0, 1, 3]) == 0
+    assert binding.validate_tree([-1, 1]) == -3          # parent must precede the child
+    assert binding.validate_tree([0, 0]) == -3           # root must have parent -1
+    assert binding.validate_tree([-1, -1]) == -3
+    assert binding.validate_tree([-1] + [0] * 256) == -2  # more than RSD_NODES_MAX nodes
+    assert binding.lib().rsd_validate_tree(None, 3) == -1
+
+
+def test_argument_errors_are_returned_before_any_launch():
+    lib = binding.lib()
+    null = None
+    fake = ctypes.c_void_p(4096)        # never dereferenced: validation fails first
+    assert lib.rsd_log_softmax_lse(null, 64, 1, 64, 1.0, fake, null) == -1
+    assert lib.rsd_log_softmax_lse(fake, 62, 1, 62, 1.0, fake, null) == -2      # ld % 4
+    assert lib.rsd_gumbel_topk(null, 64, 1, 64, 2, null, 1.0, null, null, 0, 0,
+                               fake, null, null, null, null, null, 0, null) == -1
+    assert lib.rsd_gumbel_topk(fake, 64, 1, 64, 17, null, 1.0, null, null, 0, 0,
+                               fake, null, null, null, null, null, 0, null) == -2
+    assert lib.rsd_gumbel_topk(ctypes.c_void_p(4100), 64, 1, 64, 2, null, 1.0, null, null, 0, 0,
+                               fake, null, null, null, null, null, 0, null) == -2  # misaligned
+    assert lib.rsd_sbs_step(fake, fake, fake, fake, null, null, 2, 17, 64, 2, 1.0, 0, 0,
+                            fake, fake, fake, fake, fake, null, fake, 1 << 20, null) == -2
+    assert lib.rsd_sbs_step(fake, fake, fake, fake, null, null, 2, 4, 64, 2, 1.0, 0, 0,
+                            fake, fake, fake, fake, fake, null, null, 0, null) == -4
+    assert lib.rsd_tree_attention(fake, fake, fake, fake, fake, 0, 1, 3, 2, 8, 128, 64, 0, 0, 128,
+                                  fake, fake, fake, 1.0, 0, fake, null, null, 0, null) == -2  # Hq % Hkv
+    assert lib.rsd_tree_attention(fake, fake, fake, fake, fake, 0, 1, 2, 2, 8, 96, 64, 0, 0, 96,
+                                  fake, fake, fake, 1.0, 0, fake, null, null, 0, null) == -6  # head dim
+    assert lib.rsd_tree_attention(fake, fake, fake, fake, fake, 0, 1, 2, 2, 300, 128, 64, 0, 0, 128,
+                                  fake, fake, fake, 1.0, 0, fake, null, null, 0, null) == -2  # too many nodes
+    assert lib.rsd_recursive_reject(fake, fake, 1, 8, 62, 1.0, fake, fake, fake, null, 0, 0, 0,
+                                    fake, null, 8, fake, fake, null, null, null, null, fake, 1 << 20,
+                                    null) == -2
+    assert lib.rsd_recursive_reject(fake, fake, 1, 8, 64, 1.0, fake, fake, fake, null, 7, 0, 0,
+                                    fake, null, 8, fake, fake, null, null, null, null, fake, 1 << 20,
+                                    null) == -6
+    assert lib.rsd_recursive_reject(fake, fake, 1, 8, 64, 1.0, fake, fake, fake, null, 0, 0, 0,
+                                    fake, null, 8, fake, fake, null, null, null, null, null, 0,
+                                    null) == -4
+
+
+def test_workspace_sizes_are_consistent():
+    lib = binding.lib()
+    assert lib.rsd_gumbel_topk_workspace_bytes(100, 32000, 8) == 0
+    assert lib.rsd_sbs_step_workspace_bytes(8, 6, 50272, 6) >= 8 * 6 * (3 * 6 + 1) * 4
+    one = lib.rsd_tree_attention_workspace_bytes(0, 64, 32, 32, 64, 128, 8192, 1)
+    four = lib.rsd_tree_attention_workspace_bytes(0, 1, 32, 32, 34, 128, 1024, 4)
+    assert one == 0 and four >= 1 * 32 * 34 * 4 * (128 + 2) * 4
+    assert lib.rsd_recursive_reject_workspace_bytes(64, 64, 32000) > 64 * 64 * 300
