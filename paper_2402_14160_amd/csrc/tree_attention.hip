@@ -298,6 +298,250 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     }
 }
 
+
+// ---------------------------------------------------------------------------
+// Variant for many stacked rows (grouped-query attention): 4 waves x 32 query rows with
+// v_mfma_f32_32x32x16_bf16.  Same orientation (S^T = K Q^T, O^T += V^T P^T); every K / V
+// fragment read from LDS now feeds a 32 x 32 tile, halving LDS traffic per flop, and the
+// wider row block re-reads K and V from L2 half as often.
+// C layout of the 32x32 tile: lane l holds column l % 32 and rows 8 (r / 4) + 4 (l / 32) + r % 4
+// for its registers r = 0..15; registers 8 m .. 8 m + 7 of a score tile are therefore the
+// eight key slots lane group l / 32 feeds to the m-th 16-key step of the second product.
+// ---------------------------------------------------------------------------
+typedef float floatx16 __attribute__((ext_vector_type(16)));
+constexpr int kRowsPerBlock32 = 128;
+
+__device__ __forceinline__ float max_across_halves(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return fmaxf(__uint_as_float(r[0]), __uint_as_float(r[1]));
+}
+
+__device__ __forceinline__ float sum_across_halves(float v) {
+    const auto r = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+    return __uint_as_float(r[0]) + __uint_as_float(r[1]);
+}
+
+template <int D>
+__global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(AttnArgs a) {
+    constexpr int KPAD = D + 8;    // K rows: conflict-free 16-byte reads by 32 consecutive rows
+    constexpr int VPAD = D + 32;   // V rows: conflict-free transposing reads (4 rows x 32 columns)
+    constexpr int DCH = D / 8;
+    constexpr int LPT = kTile * DCH / kAttnThreads;
+    constexpr int KS = D / 16;     // k-steps of the first product
+    constexpr int DT = D / 32;     // 32-row output tiles of the second product
+    extern __shared__ __align__(16) unsigned char smem[];
+    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                      // [2][kTile][KPAD]
+    __bf16 *Vs = Ks + 2 * kTile * KPAD;                                 // [2][kTile][VPAD]
+    uint64_t *anc = reinterpret_cast<uint64_t *>(Vs + 2 * kTile * VPAD);  // [N][kAncWords]
+
+    const int b = blockIdx.z, kvh = blockIdx.y;
+    const int rb = blockIdx.x / a.splits, sp = blockIdx.x - rb * a.splits;
+    const int n = min(max(a.nn[b], 0), a.N);
+    const int plen = min(max(a.plen[b], 0), a.P_max);
+    const int G = a.Hq / a.Hkv;
+    const int rows = G * n;
+    if (rb * kRowsPerBlock32 >= rows) return;
+
+    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int q32 = lane & 31, h = lane >> 5;
+    const bool do_tree = (sp == a.splits - 1);
+    if (do_tree) build_ancestors(a.par + (int64_t)b * a.N, n, anc, kAttnThreads);
+
+    const int R = rb * kRowsPerBlock32 + wave * 32 + q32;
+    const bool qvalid = R < rows;
+    const bool wave_active = rb * kRowsPerBlock32 + wave * 32 < rows;  // wave-uniform
+    const int hq = kvh * G + (qvalid ? R / n : 0);
+    const int qi = qvalid ? R % n : 0;
+    const __bf16 *qptr = reinterpret_cast<const __bf16 *>(a.q) + (((int64_t)b * a.Hq + hq) * a.N + qi) * D;
+    bf16x8 qf[KS];
+#pragma unroll
+    for (int ks = 0; ks < KS; ++ks) {
+        if (qvalid) {
+            qf[ks] = *reinterpret_cast<const bf16x8 *>(qptr + ks * 16 + h * 8);
+        } else {
+#pragma unroll
+            for (int e = 0; e < 8; ++e) qf[ks][e] = (__bf16)0.f;
+        }
+    }
+
+    const int Tp = (plen + kTile - 1) / kTile, Tt = (n + kTile - 1) / kTile;
+    const int t0 = (int)((int64_t)Tp * sp / a.splits), t1 = (int)((int64_t)Tp * (sp + 1) / a.splits);
+    const int npre = t1 - t0;
+    const int ntiles = npre + (do_tree ? Tt : 0);
+
+    const __bf16 *kp = reinterpret_cast<const __bf16 *>(a.kp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
+    const __bf16 *vp = reinterpret_cast<const __bf16 *>(a.vp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
+    const __bf16 *kt = reinterpret_cast<const __bf16 *>(a.kt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
+    const __bf16 *vt = reinterpret_cast<const __bf16 *>(a.vt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
+
+    uint4 kr[LPT], vr[LPT];
+    auto issue_loads = [&](int u) {
+        const __bf16 *ksrc, *vsrc;
+        int64_t stride;
+        int row0, limit;
+        if (u < npre) {
+            row0 = (t0 + u) * kTile; limit = plen; ksrc = kp; vsrc = vp; stride = a.sp;
+        } else {
+            row0 = (u - npre) * kTile; limit = n; ksrc = kt; vsrc = vt; stride = D;
+        }
+#pragma unroll
+        for (int it = 0; it < LPT; ++it) {
+            const int c = it * kAttnThreads + tid;
+            const int row = c / DCH, part = c - row * DCH;
+            if (row0 + row < limit) {
+                const int64_t off = (int64_t)(row0 + row) * stride + part * 8;
+                kr[it] = *reinterpret_cast<const uint4 *>(ksrc + off);
+                vr[it] = *reinterpret_cast<const uint4 *>(vsrc + off);
+            } else {
+                kr[it] = make_uint4(0, 0, 0, 0);
+                vr[it] = make_uint4(0, 0, 0, 0);
+            }
+        }
+    };
+    auto store_tile = [&](int buf) {
+        __bf16 *kdst = Ks + buf * kTile * KPAD;
+        __bf16 *vdst = Vs + buf * kTile * VPAD;
+#pragma unroll
+        for (int it = 0; it < LPT; ++it) {
+            const int c = it * kAttnThreads + tid;
+            const int row = c / DCH, part = c - row * DCH;
+            *reinterpret_cast<uint4 *>(kdst + row * KPAD + part * 8) = kr[it];
+            *reinterpret_cast<uint4 *>(vdst + row * VPAD + part * 8) = vr[it];
+        }
+    };
+
+    floatx16 o[DT];
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+        for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
+    float m = -INFINITY, l = 0.f;  // running max of the raw scores times scale_log2, partial row sum
+
+    if (ntiles > 0) {
+        issue_loads(0);
+        store_tile(0);
+    }
+    __syncthreads();
+
+    for (int u = 0; u < ntiles; ++u) {
+        const int buf = u & 1;
+        if (u + 1 < ntiles) issue_loads(u + 1);
+
+        if (wave_active) {
+            // ---- S^T = K Q^T: two 32-key tiles ------------------------------------
+            const __bf16 *kb = Ks + buf * kTile * KPAD + q32 * KPAD + h * 8;
+            floatx16 s[2];
+#pragma unroll
+            for (int t = 0; t < 2; ++t) {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kb + t * 32 * KPAD + ks * 16);
+                    s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[t], 0, 0, 0);
+                }
+            }
+
+            // ---- mask (tree tiles and ragged tails only), online softmax ------------
+            const bool is_tree = u >= npre;
+            const int row0 = is_tree ? (u - npre) * kTile : (t0 + u) * kTile;
+            const int limit = is_tree ? n : plen;
+            if (is_tree || row0 + kTile > limit) {
+                uint64_t vis = ~0ull;
+                if (is_tree) vis = anc[qi * kAncWords + (u - npre)];
+                if (row0 + kTile > limit) vis &= (1ull << (limit - row0)) - 1ull;
+#pragma unroll
+                for (int t = 0; t < 2; ++t)
+#pragma unroll
+                    for (int r = 0; r < 16; ++r) {
+                        const int kk = t * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                        s[t][r] = ((vis >> kk) & 1ull) ? s[t][r] : -INFINITY;
+                    }
+            }
+            float mx = -INFINITY;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
+            mx = max_across_halves(mx) * a.scale_log2;
+            const float m_new = fmaxf(m, mx);
+            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m - m_use);
+            float psum = 0.f;
+#pragma unroll
+            for (int t = 0; t < 2; ++t)
+#pragma unroll
+                for (int r = 0; r < 16; ++r) {
+                    const float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], a.scale_log2, -m_use));
+                    s[t][r] = p;
+                    psum += p;
+                }
+            l = l * alpha + psum;
+            m = m_new;
+            if (__any(alpha != 1.f)) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+            }
+
+            // ---- O^T += V^T P^T: four 16-key steps --------------------------------
+            bf16x8 pf[4];
+#pragma unroll
+            for (int mm = 0; mm < 4; ++mm)
+#pragma unroll
+                for (int e = 0; e < 8; ++e) pf[mm][e] = (__bf16)s[mm >> 1][8 * (mm & 1) + e];
+            // transposing read: lane i of each 16-lane block loads row (key) i / 4 of the
+            // 4-key run, four columns at 16 (block % 2) + 4 (i % 4)
+            const int i16 = lane & 15;
+            const __bf16 *vb = Vs + buf * kTile * VPAD + (4 * h + (i16 >> 2)) * VPAD +
+                               16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+#pragma unroll
+            for (int mm = 0; mm < 4; ++mm) {
+#pragma unroll
+                for (int dt = 0; dt < DT; ++dt) {
+                    const bf16x4 lo = lds_read_tr(vb + (16 * mm) * VPAD + dt * 32);
+                    const bf16x4 hi = lds_read_tr(vb + (16 * mm + 8) * VPAD + dt * 32);
+                    const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mm], o[dt], 0, 0, 0);
+                }
+            }
+        }
+
+        if (u + 1 < ntiles) store_tile(buf ^ 1);
+        __syncthreads();
+    }
+
+    // ---- epilogue -------------------------------------------------------------------
+    const float lt = sum_across_halves(l);
+    if (!qvalid) return;
+    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + qi;
+    if (a.splits == 1) {
+        const float inv = lt > 0.f ? 1.f / lt : 0.f;
+        float *dst = a.out + orow * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const float4 v = make_float4(o[dt][4 * rq] * inv, o[dt][4 * rq + 1] * inv,
+                                             o[dt][4 * rq + 2] * inv, o[dt][4 * rq + 3] * inv);
+                *reinterpret_cast<float4 *>(dst + dt * 32 + 8 * rq + 4 * h) = v;
+            }
+        if (a.lse_out && h == 0) a.lse_out[orow] = (m + log2f(lt)) * kLn2;
+    } else {
+        float *dst = a.ws_o + (orow * a.splits + sp) * D;
+#pragma unroll
+        for (int dt = 0; dt < DT; ++dt)
+#pragma unroll
+            for (int rq = 0; rq < 4; ++rq) {
+                const float4 v = make_float4(o[dt][4 * rq], o[dt][4 * rq + 1], o[dt][4 * rq + 2], o[dt][4 * rq + 3]);
+                *reinterpret_cast<float4 *>(dst + dt * 32 + 8 * rq + 4 * h) = v;
+            }
+        if (h == 0) {
+            a.ws_m[orow * a.splits + sp] = m;
+            a.ws_l[orow * a.splits + sp] = lt;
+        }
+    }
+}
+
 // Merge the per-split partial results of one query row: one wave per row.
 __global__ __launch_bounds__(kWave) void tree_attn_merge_kernel(AttnArgs a) {
     const int i = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
@@ -409,13 +653,21 @@ __global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnArgs a) {
 static size_t align_up(size_t x, size_t al) { return (x + al - 1) / al * al; }
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
+// 32-row waves pay off once a (sequence, KV head) pair has at least three of them
+static bool use_wide_rows(int Hq, int Hkv, int N) { return (Hq / Hkv) * N >= 96; }
+
+static int rows_per_block(int Hq, int Hkv, int N) {
+    return use_wide_rows(Hq, Hkv, N) ? kRowsPerBlock32 : kRowsPerBlock;
+}
+
 static int choose_splits(int dtype, int B, int Hq, int Hkv, int N, int P_max, int requested) {
     if (dtype != RSD_DTYPE_BF16) return 1;
     const int tiles = (P_max + kTile - 1) / kTile;
     int s = requested;
     if (s <= 0) {
         const int G = Hq / Hkv;
-        const long blocks = (long)((G * N + kRowsPerBlock - 1) / kRowsPerBlock) * Hkv * B;
+        const int rpb = rows_per_block(Hq, Hkv, N);
+        const long blocks = (long)((G * N + rpb - 1) / rpb) * Hkv * B;
         s = (int)((1024 + blocks - 1) / (blocks > 0 ? blocks : 1));
         if (s > 32) s = 32;
     }
@@ -425,8 +677,22 @@ static int choose_splits(int dtype, int B, int Hq, int Hkv, int N, int P_max, in
 }
 
 template <int D>
-static size_t attn_smem_bytes(int N) {
-    return (size_t)2 * kTile * (D + 8) * 2 + (size_t)2 * kTile * (D + 16) * 2 + (size_t)N * kAncWords * 8;
+static size_t attn_smem_bytes(int N, bool wide) {
+    return (size_t)2 * kTile * (D + 8) * 2 + (size_t)2 * kTile * (D + (wide ? 32 : 16)) * 2 +
+           (size_t)N * kAncWords * 8;
+}
+
+template <typename Kernel>
+static hipError_t launch_attn(Kernel kernel, bool &attr_set, size_t smem_max, size_t smem, dim3 grid,
+                              hipStream_t st, const AttnArgs &a) {
+    if (!attr_set) {  // the limit covers the largest tree, set once per kernel
+        const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_max);
+        if (err != hipSuccess) return err;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(kernel, grid, dim3(kAttnThreads), smem, st, a);
+    return hipGetLastError();
 }
 
 }  // namespace rsd
@@ -487,8 +753,10 @@ extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const
     }
 
     const int G = H_q / H_kv;
+    const bool wide = use_wide_rows(H_q, H_kv, N_max);
+    const int rpb = rows_per_block(H_q, H_kv, N_max);
     a.splits = choose_splits(dtype, B, H_q, H_kv, N_max, P_max, num_splits);
-    a.row_blocks = (G * N_max + kRowsPerBlock - 1) / kRowsPerBlock;
+    a.row_blocks = (G * N_max + rpb - 1) / rpb;
     if (a.splits > 1) {
         const size_t need = rsd_tree_attention_workspace_bytes(dtype, B, H_q, H_kv, N_max, D, P_max, num_splits);
         if (!workspace || workspace_bytes < need) return RSD_ERR_WORKSPACE;
@@ -500,31 +768,21 @@ extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const
                                            align_up(rows * a.splits * 4, 256));
     }
     const dim3 grid(a.row_blocks * a.splits, H_kv, B);
+    static bool set128 = false, set64 = false, set128w = false, set64w = false;
     hipError_t err;
-    if (D == 128) {
-        const size_t smem = attn_smem_bytes<128>(N_max);
-        static bool attr_set = false;  // the limit covers the largest N_max, set once
-        if (!attr_set) {
-            err = hipFuncSetAttribute(reinterpret_cast<const void *>(tree_attn_bf16_kernel<128>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)attn_smem_bytes<128>(RSD_NODES_MAX));
-            if (err != hipSuccess) return RSD_ERR_LAUNCH;
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(tree_attn_bf16_kernel<128>, grid, dim3(kAttnThreads), smem, st, a);
-    } else {
-        const size_t smem = attn_smem_bytes<64>(N_max);
-        static bool attr_set = false;
-        if (!attr_set) {
-            err = hipFuncSetAttribute(reinterpret_cast<const void *>(tree_attn_bf16_kernel<64>),
-                                      hipFuncAttributeMaxDynamicSharedMemorySize,
-                                      (int)attn_smem_bytes<64>(RSD_NODES_MAX));
-            if (err != hipSuccess) return RSD_ERR_LAUNCH;
-            attr_set = true;
-        }
-        hipLaunchKernelGGL(tree_attn_bf16_kernel<64>, grid, dim3(kAttnThreads), smem, st, a);
-    }
-    if (hipGetLastError() != hipSuccess) return RSD_ERR_LAUNCH;
+    if (D == 128 && wide)
+        err = launch_attn(tree_attn_bf16_w32_kernel<128>, set128w, attn_smem_bytes<128>(RSD_NODES_MAX, true),
+                          attn_smem_bytes<128>(N_max, true), grid, st, a);
+    else if (D == 128)
+        err = launch_attn(tree_attn_bf16_kernel<128>, set128, attn_smem_bytes<128>(RSD_NODES_MAX, false),
+                          attn_smem_bytes<128>(N_max, false), grid, st, a);
+    else if (wide)
+        err = launch_attn(tree_attn_bf16_w32_kernel<64>, set64w, attn_smem_bytes<64>(RSD_NODES_MAX, true),
+                          attn_smem_bytes<64>(N_max, true), grid, st, a);
+    else
+        err = launch_attn(tree_attn_bf16_kernel<64>, set64, attn_smem_bytes<64>(RSD_NODES_MAX, false),
+                          attn_smem_bytes<64>(N_max, false), grid, st, a);
+    if (err != hipSuccess) return RSD_ERR_LAUNCH;
     if (a.splits > 1) {
         hipLaunchKernelGGL(tree_attn_merge_kernel, dim3(N_max, H_q, B), dim3(kWave), 0, st, a);
         if (hipGetLastError() != hipSuccess) return RSD_ERR_LAUNCH;

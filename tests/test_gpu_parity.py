@@ -213,6 +213,10 @@ def test_tree_attention_fp32_config0():
     (1, 2, 1, 16, 64, 96, 0, None, None),             # head_dim 64
     (1, 2, 2, 20, 128, 0, 0, None, None),             # no prefix at all
     (2, 2, 2, 12, 128, 80, 0, [0, 12], [80, 0]),      # empty tree in one sequence, empty prefix in other
+    (2, 8, 2, 40, 128, 200, 0, [40, 17], [200, 77]),  # wide-row variant: 160 stacked rows, ragged blocks
+    (1, 16, 2, 65, 128, 257, 3, None, None),          # wide rows, forced splits, 65 nodes
+    (1, 8, 1, 24, 64, 130, 0, None, None),            # wide rows with head_dim 64
+    (1, 4, 1, 130, 128, 64, 1, None, None),           # wide rows, three ancestor words
 ])
 def test_tree_attention_bf16(B, Hq, Hkv, N, D, P, splits, n_nodes, plens):
     say(f"attention bf16 B={B} Hq={Hq} Hkv={Hkv} N={N} D={D} P={P} splits={splits}")
