@@ -11,10 +11,12 @@
 // In this orientation a lane holds scores of ONE query, so the running softmax
 // maximum and the rescale factor are per-lane scalars, and the fp32 scores of
 // two 16-key tiles are, after conversion to bf16, already laid out as the B
-// operand of the second product: P never goes through LDS.  K and V tiles are
-// stored row-major in LDS; the V^T operand is fetched with the gfx950
-// transposing LDS read (ds_read_b64_tr_b16), which hands each lane four keys of
-// one head-dim column.  The tree mask is an ancestor bit-set per node (a node's
+// operand of the second product: P never goes through LDS.  K and V tiles go from
+// global memory straight into LDS (global_load_lds, 16 bytes per lane, no staging
+// registers), row-major, with the 16-byte chunks of every row XOR-swizzled by the row
+// index so that all fragment reads are bank-conflict free without padding; the V^T
+// operand is fetched with the gfx950 transposing LDS read (ds_read_b64_tr_b16), which
+// hands each lane four keys of one head-dim column.  The tree mask is an ancestor bit-set per node (a node's
 // set is its parent's set plus itself), applied only to the tree-key tiles.
 //
 // A long prefix can be split over several workgroups (flash-decoding style);
@@ -76,6 +78,46 @@ __device__ __forceinline__ void build_ancestors(const int *par, int n, uint64_t 
     }
 }
 
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void global_void;
+
+// Swizzle of the 16-byte chunks of tile row r: chunk c is stored at position c ^ swz(r).
+// For 16 chunks per row (D = 128) the four row bits are permuted so that (a) 16 consecutive
+// rows give 16 different values (K fragments: one chunk of 16 or 32 consecutive rows),
+// (b) 4 consecutive rows differ in the two high bits while rows 4 and 8 apart differ in the
+// low bits (V fragments: four-row runs, two or four neighbouring chunks).
+template <int D>
+__device__ __forceinline__ int swz(int r) {
+    if (D == 128) return ((r & 3) << 2) | (((r >> 2) & 1) << 1) | ((r >> 3) & 1);
+    return (r >> 1) & 7;  // 8 chunks per row: two rows span the 64 banks
+}
+
+// One 64-row tile of K and of V from global memory into LDS.  Wave w, instruction it fills
+// 64 consecutive chunk positions (4 or 8 rows); a lane fetches the chunk that belongs at its
+// position.  Rows at or beyond `limit` re-read the last valid row (finite data; their scores
+// are masked), so no lane is ever switched off and no LDS byte is left stale.
+template <int D>
+__device__ __forceinline__ void stage_tile(const __bf16 *ksrc, const __bf16 *vsrc, int64_t stride,
+                                           int row0, int limit, __bf16 *kdst, __bf16 *vdst) {
+    constexpr int DCH = D / 8;          // chunks per row
+    constexpr int RPI = 64 / DCH;       // rows per wave instruction
+    constexpr int NIT = kTile / (RPI * (kAttnThreads / 64));
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int rbase = (it * (kAttnThreads / 64) + wave) * RPI;
+        const int r = rbase + lane / DCH;
+        const int c = (lane % DCH) ^ swz<D>(r);
+        const int rs = min(row0 + r, limit - 1);
+        const int64_t off = (int64_t)rs * stride + c * 8;
+        __builtin_amdgcn_global_load_lds((global_void *)(ksrc + off), (lds_void *)(kdst + rbase * D), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_void *)(vsrc + off), (lds_void *)(vdst + rbase * D), 16, 0, 0);
+    }
+}
+
+// All outstanding global->LDS loads of this wave have landed.
+__device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+
 // Transposing LDS read: within each block of 16 lanes, lane i supplies the address of four
 // contiguous 16-bit elements and receives element (i % 4) of the loads of lanes
 // i/4, 4 + i/4, 8 + i/4 and 12 + i/4.  Seen as a 4 x 16 tile (row k read by lanes 4k..4k+3,
@@ -86,16 +128,12 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16 *p) {
 
 template <int D>
 __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArgs a) {
-    constexpr int KPAD = D + 8;       // K tile row stride (elements): conflict-free 16-byte reads
-    constexpr int VPAD = D + 16;      // V tile row stride (elements): conflict-free transposing reads
-    constexpr int DCH = D / 8;        // 16-byte chunks per row
-    constexpr int LPT = kTile * DCH / kAttnThreads;  // chunks per thread per tile
     constexpr int KS = D / 32;        // k-steps of the first product
     constexpr int DT = D / 16;        // output tiles of the second product
     extern __shared__ __align__(16) unsigned char smem[];
-    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);          // [2][kTile][KPAD]
-    __bf16 *Vs = Ks + 2 * kTile * KPAD;                     // [2][kTile][VPAD]
-    uint64_t *anc = reinterpret_cast<uint64_t *>(Vs + 2 * kTile * VPAD);  // [N][kAncWords]
+    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);          // [2][kTile][D], swizzled chunks
+    __bf16 *Vs = Ks + 2 * kTile * D;                        // [2][kTile][D], swizzled chunks
+    uint64_t *anc = reinterpret_cast<uint64_t *>(Vs + 2 * kTile * D);  // [N][kAncWords]
 
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int rb = blockIdx.x / a.splits, sp = blockIdx.x - rb * a.splits;
@@ -138,40 +176,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     const __bf16 *kt = reinterpret_cast<const __bf16 *>(a.kt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
     const __bf16 *vt = reinterpret_cast<const __bf16 *>(a.vt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
 
-    uint4 kr[LPT], vr[LPT];
-    auto issue_loads = [&](int u) {
-        const __bf16 *ksrc, *vsrc;
-        int64_t stride;
-        int row0, limit;
-        if (u < npre) {
-            row0 = (t0 + u) * kTile; limit = plen; ksrc = kp; vsrc = vp; stride = a.sp;
-        } else {
-            row0 = (u - npre) * kTile; limit = n; ksrc = kt; vsrc = vt; stride = D;
-        }
-#pragma unroll
-        for (int it = 0; it < LPT; ++it) {
-            const int c = it * kAttnThreads + tid;
-            const int row = c / DCH, part = c - row * DCH;
-            if (row0 + row < limit) {
-                const int64_t off = (int64_t)(row0 + row) * stride + part * 8;
-                kr[it] = *reinterpret_cast<const uint4 *>(ksrc + off);
-                vr[it] = *reinterpret_cast<const uint4 *>(vsrc + off);
-            } else {
-                kr[it] = make_uint4(0, 0, 0, 0);
-                vr[it] = make_uint4(0, 0, 0, 0);
-            }
-        }
-    };
-    auto store_tile = [&](int buf) {
-        __bf16 *kdst = Ks + buf * kTile * KPAD;
-        __bf16 *vdst = Vs + buf * kTile * VPAD;
-#pragma unroll
-        for (int it = 0; it < LPT; ++it) {
-            const int c = it * kAttnThreads + tid;
-            const int row = c / DCH, part = c - row * DCH;
-            *reinterpret_cast<uint4 *>(kdst + row * KPAD + part * 8) = kr[it];
-            *reinterpret_cast<uint4 *>(vdst + row * VPAD + part * 8) = vr[it];
-        }
+    auto stage = [&](int u) {  // tile u of this block's schedule into buffer u & 1
+        const int buf = u & 1;
+        if (u < npre)
+            stage_tile<D>(kp, vp, a.sp, (t0 + u) * kTile, plen, Ks + buf * kTile * D, Vs + buf * kTile * D);
+        else
+            stage_tile<D>(kt, vt, D, (u - npre) * kTile, n, Ks + buf * kTile * D, Vs + buf * kTile * D);
     };
 
     floatx4 o[DT];
@@ -179,25 +189,25 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     for (int dt = 0; dt < DT; ++dt) o[dt] = floatx4{0.f, 0.f, 0.f, 0.f};
     float m = -INFINITY, l = 0.f;
 
-    if (ntiles > 0) {
-        issue_loads(0);
-        store_tile(0);
-    }
+    if (ntiles > 0) stage(0);
+    wait_tile_loads();
     __syncthreads();
 
     for (int u = 0; u < ntiles; ++u) {
         const int buf = u & 1;
-        if (u + 1 < ntiles) issue_loads(u + 1);
+        if (u + 1 < ntiles) stage(u + 1);  // lands while this tile is consumed
 
         // ---- S^T = K Q^T for the 64 keys of this tile ----------------------
-        const __bf16 *kb = Ks + buf * kTile * KPAD;
+        // lane (c16, g) reads chunk 4 ks + g of tile row 16 t + c16 (swizzle depends on c16 only)
+        const __bf16 *kb = Ks + buf * kTile * D + c16 * D;
+        const int ksw = swz<D>(c16);
         floatx4 s[4];
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
             s[t] = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
             for (int ks = 0; ks < KS; ++ks) {
-                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kb + (t * 16 + c16) * KPAD + ks * 32 + g * 8);
+                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kb + t * 16 * D + (((ks * 4 + g) ^ ksw) << 3));
                 s[t] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf, qf[ks], s[t], 0, 0, 0);
             }
         }
@@ -254,19 +264,22 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
         // lane (c16, g) of the A operand needs V[key][16 dt + c16] for the keys
         // 32 j + 16 a + 4 g + r (a = 0,1; r = 0..3): two transposing reads, in which this
         // lane loads row 32 j + 16 a + 4 g + c16 / 4, columns 16 dt + 4 (c16 % 4) .. + 3.
-        const __bf16 *vb = Vs + buf * kTile * VPAD + (g * 4 + (c16 >> 2)) * VPAD + (c16 & 3) * 4;
+        const int vrow = g * 4 + (c16 >> 2);       // + 32 j + 16 a: the swizzle sees vrow only
+        const __bf16 *vb = Vs + buf * kTile * D + vrow * D + (c16 & 1) * 4;
+        const int vsw = swz<D>(vrow), vch = (c16 >> 1) & 1;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
+            const int voff = ((dt * 2 + vch) ^ vsw) << 3;
 #pragma unroll
             for (int j = 0; j < 2; ++j) {
-                const bf16x4 lo = lds_read_tr(vb + (j * 32) * VPAD + dt * 16);
-                const bf16x4 hi = lds_read_tr(vb + (j * 32 + 16) * VPAD + dt * 16);
+                const bf16x4 lo = lds_read_tr(vb + (j * 32) * D + voff);
+                const bf16x4 hi = lds_read_tr(vb + (j * 32 + 16) * D + voff);
                 const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                 o[dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pf[j], o[dt], 0, 0, 0);
             }
         }
 
-        if (u + 1 < ntiles) store_tile(buf ^ 1);
+        wait_tile_loads();
         __syncthreads();
     }
 
@@ -323,16 +336,12 @@ __device__ __forceinline__ float sum_across_halves(float v) {
 
 template <int D>
 __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(AttnArgs a) {
-    constexpr int KPAD = D + 8;    // K rows: conflict-free 16-byte reads by 32 consecutive rows
-    constexpr int VPAD = D + 32;   // V rows: conflict-free transposing reads (4 rows x 32 columns)
-    constexpr int DCH = D / 8;
-    constexpr int LPT = kTile * DCH / kAttnThreads;
     constexpr int KS = D / 16;     // k-steps of the first product
     constexpr int DT = D / 32;     // 32-row output tiles of the second product
     extern __shared__ __align__(16) unsigned char smem[];
-    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                      // [2][kTile][KPAD]
-    __bf16 *Vs = Ks + 2 * kTile * KPAD;                                 // [2][kTile][VPAD]
-    uint64_t *anc = reinterpret_cast<uint64_t *>(Vs + 2 * kTile * VPAD);  // [N][kAncWords]
+    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                      // [2][kTile][D], swizzled chunks
+    __bf16 *Vs = Ks + 2 * kTile * D;                                    // [2][kTile][D], swizzled chunks
+    uint64_t *anc = reinterpret_cast<uint64_t *>(Vs + 2 * kTile * D);   // [N][kAncWords]
 
     const int b = blockIdx.z, kvh = blockIdx.y;
     const int rb = blockIdx.x / a.splits, sp = blockIdx.x - rb * a.splits;
@@ -374,40 +383,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(Att
     const __bf16 *kt = reinterpret_cast<const __bf16 *>(a.kt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
     const __bf16 *vt = reinterpret_cast<const __bf16 *>(a.vt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
 
-    uint4 kr[LPT], vr[LPT];
-    auto issue_loads = [&](int u) {
-        const __bf16 *ksrc, *vsrc;
-        int64_t stride;
-        int row0, limit;
-        if (u < npre) {
-            row0 = (t0 + u) * kTile; limit = plen; ksrc = kp; vsrc = vp; stride = a.sp;
-        } else {
-            row0 = (u - npre) * kTile; limit = n; ksrc = kt; vsrc = vt; stride = D;
-        }
-#pragma unroll
-        for (int it = 0; it < LPT; ++it) {
-            const int c = it * kAttnThreads + tid;
-            const int row = c / DCH, part = c - row * DCH;
-            if (row0 + row < limit) {
-                const int64_t off = (int64_t)(row0 + row) * stride + part * 8;
-                kr[it] = *reinterpret_cast<const uint4 *>(ksrc + off);
-                vr[it] = *reinterpret_cast<const uint4 *>(vsrc + off);
-            } else {
-                kr[it] = make_uint4(0, 0, 0, 0);
-                vr[it] = make_uint4(0, 0, 0, 0);
-            }
-        }
-    };
-    auto store_tile = [&](int buf) {
-        __bf16 *kdst = Ks + buf * kTile * KPAD;
-        __bf16 *vdst = Vs + buf * kTile * VPAD;
-#pragma unroll
-        for (int it = 0; it < LPT; ++it) {
-            const int c = it * kAttnThreads + tid;
-            const int row = c / DCH, part = c - row * DCH;
-            *reinterpret_cast<uint4 *>(kdst + row * KPAD + part * 8) = kr[it];
-            *reinterpret_cast<uint4 *>(vdst + row * VPAD + part * 8) = vr[it];
-        }
+    auto stage = [&](int u) {  // tile u of this block's schedule into buffer u & 1
+        const int buf = u & 1;
+        if (u < npre)
+            stage_tile<D>(kp, vp, a.sp, (t0 + u) * kTile, plen, Ks + buf * kTile * D, Vs + buf * kTile * D);
+        else
+            stage_tile<D>(kt, vt, D, (u - npre) * kTile, n, Ks + buf * kTile * D, Vs + buf * kTile * D);
     };
 
     floatx16 o[DT];
@@ -417,19 +398,19 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(Att
         for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
     float m = -INFINITY, l = 0.f;  // running max of the raw scores times scale_log2, partial row sum
 
-    if (ntiles > 0) {
-        issue_loads(0);
-        store_tile(0);
-    }
+    if (ntiles > 0) stage(0);
+    wait_tile_loads();
     __syncthreads();
 
     for (int u = 0; u < ntiles; ++u) {
         const int buf = u & 1;
-        if (u + 1 < ntiles) issue_loads(u + 1);
+        if (u + 1 < ntiles) stage(u + 1);  // lands while this tile is consumed
 
         if (wave_active) {
             // ---- S^T = K Q^T: two 32-key tiles ------------------------------------
-            const __bf16 *kb = Ks + buf * kTile * KPAD + q32 * KPAD + h * 8;
+            // lane (q32, h) reads chunk 2 ks + h of tile row 32 t + q32
+            const __bf16 *kb = Ks + buf * kTile * D + q32 * D;
+            const int ksw = swz<D>(q32);
             floatx16 s[2];
 #pragma unroll
             for (int t = 0; t < 2; ++t) {
@@ -437,7 +418,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(Att
                 for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
 #pragma unroll
                 for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kb + t * 32 * KPAD + ks * 16);
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kb + t * 32 * D + (((ks * 2 + h) ^ ksw) << 3));
                     s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[t], 0, 0, 0);
                 }
             }
@@ -492,21 +473,23 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(Att
             // transposing read: lane i of each 16-lane block loads row (key) i / 4 of the
             // 4-key run, four columns at 16 (block % 2) + 4 (i % 4)
             const int i16 = lane & 15;
-            const __bf16 *vb = Vs + buf * kTile * VPAD + (4 * h + (i16 >> 2)) * VPAD +
-                               16 * ((lane >> 4) & 1) + 4 * (i16 & 3);
+            const int vrow = 4 * h + (i16 >> 2);                     // + 16 mm (+ 8 for the second run)
+            const int vch = 2 * ((lane >> 4) & 1) + ((i16 >> 1) & 1);  // chunk within the 32-column tile
+            const __bf16 *vb = Vs + buf * kTile * D + vrow * D + (i16 & 1) * 4;
+            const int vsw_lo = swz<D>(vrow), vsw_hi = swz<D>(vrow + 8);
 #pragma unroll
             for (int mm = 0; mm < 4; ++mm) {
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
-                    const bf16x4 lo = lds_read_tr(vb + (16 * mm) * VPAD + dt * 32);
-                    const bf16x4 hi = lds_read_tr(vb + (16 * mm + 8) * VPAD + dt * 32);
+                    const bf16x4 lo = lds_read_tr(vb + (16 * mm) * D + (((dt * 4 + vch) ^ vsw_lo) << 3));
+                    const bf16x4 hi = lds_read_tr(vb + (16 * mm + 8) * D + (((dt * 4 + vch) ^ vsw_hi) << 3));
                     const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
                     o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mm], o[dt], 0, 0, 0);
                 }
             }
         }
 
-        if (u + 1 < ntiles) store_tile(buf ^ 1);
+        wait_tile_loads();
         __syncthreads();
     }
 
@@ -665,10 +648,12 @@ static int choose_splits(int dtype, int B, int Hq, int Hkv, int N, int P_max, in
     const int tiles = (P_max + kTile - 1) / kTile;
     int s = requested;
     if (s <= 0) {
+        // two workgroups fit on a compute unit: split the prefix only as far as the launch
+        // still fits the chip in one round (512 workgroups on 256 compute units)
         const int G = Hq / Hkv;
         const int rpb = rows_per_block(Hq, Hkv, N);
         const long blocks = (long)((G * N + rpb - 1) / rpb) * Hkv * B;
-        s = (int)((1024 + blocks - 1) / (blocks > 0 ? blocks : 1));
+        s = (int)(512 / (blocks > 0 ? blocks : 1));
         if (s > 32) s = 32;
     }
     if (s > tiles) s = tiles;
@@ -677,9 +662,8 @@ static int choose_splits(int dtype, int B, int Hq, int Hkv, int N, int P_max, in
 }
 
 template <int D>
-static size_t attn_smem_bytes(int N, bool wide) {
-    return (size_t)2 * kTile * (D + 8) * 2 + (size_t)2 * kTile * (D + (wide ? 32 : 16)) * 2 +
-           (size_t)N * kAncWords * 8;
+static size_t attn_smem_bytes(int N, bool) {
+    return (size_t)4 * kTile * D * 2 + (size_t)N * kAncWords * 8;
 }
 
 template <typename Kernel>
