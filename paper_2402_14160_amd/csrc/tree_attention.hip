@@ -56,6 +56,23 @@ struct AttnArgs {
     float *ws_l;  // [B,Hq,N,splits]  running sum
 };
 
+// Workgroup -> (sequence, KV head, row block, prefix split).  The launch is one-dimensional
+// and consecutive workgroup ids go round-robin to the 8 XCDs, each with its own L2.  The
+// ids that land on one XCD are mapped to consecutive work items, so the row blocks (and
+// splits) that stream the same K/V rows share an L2 and run at about the same time.
+constexpr int kXcds = 8;
+
+__device__ __forceinline__ void decode_block(const AttnArgs &a, int &b, int &kvh, int &rb, int &sp) {
+    const int nblk = gridDim.x, i = blockIdx.x;
+    const int per = nblk / kXcds, rem = nblk % kXcds;
+    const int xcd = i % kXcds, slot = i / kXcds;
+    int item = xcd * per + min(xcd, rem) + slot;
+    sp = item % a.splits; item /= a.splits;
+    rb = item % a.row_blocks; item /= a.row_blocks;
+    kvh = item % a.Hkv;
+    b = item / a.Hkv;
+}
+
 // Ancestor-or-self bit-sets of all nodes of one tree into `anc` ([n][kAncWords]).
 // Parent values are clamped into [0, j-1], so the walk always terminates.
 __device__ __forceinline__ void build_ancestors(const int *par, int n, uint64_t *anc, int threads) {
@@ -135,8 +152,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     __bf16 *Vs = Ks + 2 * kTile * D;                        // [2][kTile][D], swizzled chunks
     uint64_t *anc = reinterpret_cast<uint64_t *>(Vs + 2 * kTile * D);  // [N][kAncWords]
 
-    const int b = blockIdx.z, kvh = blockIdx.y;
-    const int rb = blockIdx.x / a.splits, sp = blockIdx.x - rb * a.splits;
+    int b, kvh, rb, sp;
+    decode_block(a, b, kvh, rb, sp);
     const int n = min(max(a.nn[b], 0), a.N);
     const int plen = min(max(a.plen[b], 0), a.P_max);
     const int G = a.Hq / a.Hkv;
@@ -343,8 +360,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(Att
     __bf16 *Vs = Ks + 2 * kTile * D;                                    // [2][kTile][D], swizzled chunks
     uint64_t *anc = reinterpret_cast<uint64_t *>(Vs + 2 * kTile * D);   // [N][kAncWords]
 
-    const int b = blockIdx.z, kvh = blockIdx.y;
-    const int rb = blockIdx.x / a.splits, sp = blockIdx.x - rb * a.splits;
+    int b, kvh, rb, sp;
+    decode_block(a, b, kvh, rb, sp);
     const int n = min(max(a.nn[b], 0), a.N);
     const int plen = min(max(a.plen[b], 0), a.P_max);
     const int G = a.Hq / a.Hkv;
@@ -751,7 +768,7 @@ extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const
         a.ws_l = reinterpret_cast<float *>(ws + align_up(rows * a.splits * D * 4, 256) +
                                            align_up(rows * a.splits * 4, 256));
     }
-    const dim3 grid(a.row_blocks * a.splits, H_kv, B);
+    const dim3 grid((unsigned)((long)a.row_blocks * a.splits * H_kv * B));
     static bool set128 = false, set64 = false, set128w = false, set64w = false;
     hipError_t err;
     if (D == 128 && wide)
