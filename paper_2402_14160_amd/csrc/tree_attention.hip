@@ -47,8 +47,10 @@ struct AttnArgs {
     const int *nn;
     const int *par;
     float scale_log2;  // softmax scale * log2(e)
-    int splits;
+    int splits;     // prefix splits of this launch
+    int ws_splits;  // split stride of the partial-result workspace (largest split count)
     int row_blocks;
+    int row_base;   // first stacked row covered by this launch
     float *out;
     float *lse_out;
     float *ws_o;  // [B,Hq,N,splits,D]
@@ -113,16 +115,17 @@ __device__ __forceinline__ int swz(int r) {
 // 64 consecutive chunk positions (4 or 8 rows); a lane fetches the chunk that belongs at its
 // position.  Rows at or beyond `limit` re-read the last valid row (finite data; their scores
 // are masked), so no lane is ever switched off and no LDS byte is left stale.
-template <int D>
+template <int D, int THREADS>
 __device__ __forceinline__ void stage_tile(const __bf16 *ksrc, const __bf16 *vsrc, int64_t stride,
                                            int row0, int limit, __bf16 *kdst, __bf16 *vdst) {
     constexpr int DCH = D / 8;          // chunks per row
     constexpr int RPI = 64 / DCH;       // rows per wave instruction
-    constexpr int NIT = kTile / (RPI * (kAttnThreads / 64));
+    constexpr int NIT = kTile / (RPI * (THREADS / 64));
+    static_assert(NIT >= 1, "tile smaller than one pass of the workgroup");
     const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
 #pragma unroll
     for (int it = 0; it < NIT; ++it) {
-        const int rbase = (it * (kAttnThreads / 64) + wave) * RPI;
+        const int rbase = (it * (THREADS / 64) + wave) * RPI;
         const int r = rbase + lane / DCH;
         const int c = (lane % DCH) ^ swz<D>(r);
         const int rs = min(row0 + r, limit - 1);
@@ -132,8 +135,14 @@ __device__ __forceinline__ void stage_tile(const __bf16 *ksrc, const __bf16 *vsr
     }
 }
 
-// All outstanding global->LDS loads of this wave have landed.
-__device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(0)" ::: "memory"); }
+// Number of global->LDS load instructions one thread issues per staged tile (K and V).
+template <int D, int THREADS>
+constexpr int tile_loads_per_thread() { return 2 * (kTile / ((64 / (D / 8)) * (THREADS / 64))); }
+
+// Wait until at most PENDING of this wave's global->LDS loads are still in flight (loads
+// complete in issue order, so everything older than the newest PENDING has landed).
+template <int PENDING>
+__device__ __forceinline__ void wait_tile_loads() { asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PENDING) : "memory"); }
 
 // Transposing LDS read: within each block of 16 lanes, lane i supplies the address of four
 // contiguous 16-bit elements and receives element (i % 4) of the loads of lanes
@@ -158,7 +167,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     const int plen = min(max(a.plen[b], 0), a.P_max);
     const int G = a.Hq / a.Hkv;
     const int rows = G * n;
-    if (rb * kRowsPerBlock >= rows) return;
+    if (a.row_base + rb * kRowsPerBlock >= rows) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c16 = lane & 15, g = lane >> 4;
@@ -166,7 +175,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     if (do_tree) build_ancestors(a.par + (int64_t)b * a.N, n, anc, kAttnThreads);
 
     // ---- this lane's query ------------------------------------------------
-    const int R = rb * kRowsPerBlock + wave * 16 + c16;
+    const int R = a.row_base + rb * kRowsPerBlock + wave * 16 + c16;
     const bool qvalid = R < rows;
     const int hq = kvh * G + (qvalid ? R / n : 0);
     const int qi = qvalid ? R % n : 0;
@@ -196,9 +205,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     auto stage = [&](int u) {  // tile u of this block's schedule into buffer u & 1
         const int buf = u & 1;
         if (u < npre)
-            stage_tile<D>(kp, vp, a.sp, (t0 + u) * kTile, plen, Ks + buf * kTile * D, Vs + buf * kTile * D);
+            stage_tile<D, kAttnThreads>(kp, vp, a.sp, (t0 + u) * kTile, plen, Ks + buf * kTile * D, Vs + buf * kTile * D);
         else
-            stage_tile<D>(kt, vt, D, (u - npre) * kTile, n, Ks + buf * kTile * D, Vs + buf * kTile * D);
+            stage_tile<D, kAttnThreads>(kt, vt, D, (u - npre) * kTile, n, Ks + buf * kTile * D, Vs + buf * kTile * D);
     };
 
     floatx4 o[DT];
@@ -207,7 +216,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     float m = -INFINITY, l = 0.f;
 
     if (ntiles > 0) stage(0);
-    wait_tile_loads();
+    wait_tile_loads<0>();
     __syncthreads();
 
     for (int u = 0; u < ntiles; ++u) {
@@ -296,7 +305,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
             }
         }
 
-        wait_tile_loads();
+        wait_tile_loads<0>();
         __syncthreads();
     }
 
@@ -315,15 +324,15 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
         }
         if (a.lse_out && g == 0) a.lse_out[orow] = (m + log2f(lt)) * kLn2;
     } else {
-        float *dst = a.ws_o + (orow * a.splits + sp) * D;
+        float *dst = a.ws_o + (orow * a.ws_splits + sp) * D;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             float4 v = make_float4(o[dt][0], o[dt][1], o[dt][2], o[dt][3]);
             *reinterpret_cast<float4 *>(dst + dt * 16 + g * 4) = v;
         }
         if (g == 0) {
-            a.ws_m[orow * a.splits + sp] = m;
-            a.ws_l[orow * a.splits + sp] = lt;
+            a.ws_m[orow * a.ws_splits + sp] = m;
+            a.ws_l[orow * a.ws_splits + sp] = lt;
         }
     }
 }
@@ -351,14 +360,18 @@ __device__ __forceinline__ float sum_across_halves(float v) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int D>
-__global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(AttnArgs a) {
+template <int D, int WAVES, int STAGES>
+__global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnArgs a) {
+    constexpr int THREADS = WAVES * 64;
+    constexpr int RPB = WAVES * 32;  // stacked query rows per workgroup
+    constexpr int LOADS = tile_loads_per_thread<D, THREADS>();
+    static_assert(STAGES == 2 || STAGES == 3, "ring depth");
     constexpr int KS = D / 16;     // k-steps of the first product
     constexpr int DT = D / 32;     // 32-row output tiles of the second product
     extern __shared__ __align__(16) unsigned char smem[];
-    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                      // [2][kTile][D], swizzled chunks
-    __bf16 *Vs = Ks + 2 * kTile * D;                                    // [2][kTile][D], swizzled chunks
-    uint64_t *anc = reinterpret_cast<uint64_t *>(Vs + 2 * kTile * D);   // [N][kAncWords]
+    __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                         // [STAGES][kTile][D], swizzled
+    __bf16 *Vs = Ks + STAGES * kTile * D;                                  // [STAGES][kTile][D], swizzled
+    uint64_t *anc = reinterpret_cast<uint64_t *>(Vs + STAGES * kTile * D);  // [N][kAncWords]
 
     int b, kvh, rb, sp;
     decode_block(a, b, kvh, rb, sp);
@@ -366,16 +379,16 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(Att
     const int plen = min(max(a.plen[b], 0), a.P_max);
     const int G = a.Hq / a.Hkv;
     const int rows = G * n;
-    if (rb * kRowsPerBlock32 >= rows) return;
+    if (a.row_base + rb * RPB >= rows) return;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q32 = lane & 31, h = lane >> 5;
     const bool do_tree = (sp == a.splits - 1);
-    if (do_tree) build_ancestors(a.par + (int64_t)b * a.N, n, anc, kAttnThreads);
+    if (do_tree) build_ancestors(a.par + (int64_t)b * a.N, n, anc, THREADS);
 
-    const int R = rb * kRowsPerBlock32 + wave * 32 + q32;
+    const int R = a.row_base + rb * RPB + wave * 32 + q32;
     const bool qvalid = R < rows;
-    const bool wave_active = rb * kRowsPerBlock32 + wave * 32 < rows;  // wave-uniform
+    const bool wave_active = a.row_base + rb * RPB + wave * 32 < rows;  // wave-uniform
     const int hq = kvh * G + (qvalid ? R / n : 0);
     const int qi = qvalid ? R % n : 0;
     const __bf16 *qptr = reinterpret_cast<const __bf16 *>(a.q) + (((int64_t)b * a.Hq + hq) * a.N + qi) * D;
@@ -400,12 +413,12 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(Att
     const __bf16 *kt = reinterpret_cast<const __bf16 *>(a.kt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
     const __bf16 *vt = reinterpret_cast<const __bf16 *>(a.vt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
 
-    auto stage = [&](int u) {  // tile u of this block's schedule into buffer u & 1
-        const int buf = u & 1;
+    auto stage = [&](int u) {  // tile u of this block's schedule into ring buffer u % STAGES
+        const int buf = u % STAGES;
         if (u < npre)
-            stage_tile<D>(kp, vp, a.sp, (t0 + u) * kTile, plen, Ks + buf * kTile * D, Vs + buf * kTile * D);
+            stage_tile<D, THREADS>(kp, vp, a.sp, (t0 + u) * kTile, plen, Ks + buf * kTile * D, Vs + buf * kTile * D);
         else
-            stage_tile<D>(kt, vt, D, (u - npre) * kTile, n, Ks + buf * kTile * D, Vs + buf * kTile * D);
+            stage_tile<D, THREADS>(kt, vt, D, (u - npre) * kTile, n, Ks + buf * kTile * D, Vs + buf * kTile * D);
     };
 
     floatx16 o[DT];
@@ -415,13 +428,21 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(Att
         for (int r = 0; r < 16; ++r) o[dt][r] = 0.f;
     float m = -INFINITY, l = 0.f;  // running max of the raw scores times scale_log2, partial row sum
 
-    if (ntiles > 0) stage(0);
-    wait_tile_loads();
+    // prologue: STAGES - 1 tiles in flight; tile 0 must have landed
+#pragma unroll
+    for (int u = 0; u < STAGES - 1; ++u)
+        if (u < ntiles) stage(u);
+    if (ntiles > STAGES - 2 && STAGES > 2) {
+        if (ntiles > 1) wait_tile_loads<(STAGES - 2) * LOADS>(); else wait_tile_loads<0>();
+    } else {
+        wait_tile_loads<0>();
+    }
     __syncthreads();
 
     for (int u = 0; u < ntiles; ++u) {
-        const int buf = u & 1;
-        if (u + 1 < ntiles) stage(u + 1);  // lands while this tile is consumed
+        const int buf = u % STAGES;
+        // the buffer of tile u + STAGES - 1 was last read in iteration u - 1
+        if (u + STAGES - 1 < ntiles) stage(u + STAGES - 1);
 
         if (wave_active) {
             // ---- S^T = K Q^T: two 32-key tiles ------------------------------------
@@ -506,7 +527,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(Att
             }
         }
 
-        wait_tile_loads();
+        // tile u + 1 must have landed; the STAGES - 2 newer tiles may still be in flight
+        if (STAGES > 2 && u + STAGES - 1 < ntiles)
+            wait_tile_loads<(STAGES - 2) * LOADS>();
+        else
+            wait_tile_loads<0>();
         __syncthreads();
     }
 
@@ -527,7 +552,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(Att
             }
         if (a.lse_out && h == 0) a.lse_out[orow] = (m + log2f(lt)) * kLn2;
     } else {
-        float *dst = a.ws_o + (orow * a.splits + sp) * D;
+        float *dst = a.ws_o + (orow * a.ws_splits + sp) * D;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -536,32 +561,36 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_w32_kernel(Att
                 *reinterpret_cast<float4 *>(dst + dt * 32 + 8 * rq + 4 * h) = v;
             }
         if (h == 0) {
-            a.ws_m[orow * a.splits + sp] = m;
-            a.ws_l[orow * a.splits + sp] = lt;
+            a.ws_m[orow * a.ws_splits + sp] = m;
+            a.ws_l[orow * a.ws_splits + sp] = lt;
         }
     }
 }
 
-// Merge the per-split partial results of one query row: one wave per row.
+// Merge the per-split partial results of the stacked rows [row_base, row_base + gridDim.x) of
+// every (sequence, KV head) pair: one wave per row, `splits` partial results each.
 __global__ __launch_bounds__(kWave) void tree_attn_merge_kernel(AttnArgs a) {
-    const int i = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
+    const int R = a.row_base + blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
     const int n = min(max(a.nn[b], 0), a.N);
-    if (i >= n) return;
+    const int G = a.Hq / a.Hkv;
+    if (R >= G * n) return;
+    const int hq = kvh * G + R / n, i = R % n;
+    const int splits = a.splits;
     const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + i;
     const int lane = threadIdx.x;
+    const float *wm = a.ws_m + orow * a.ws_splits, *wl = a.ws_l + orow * a.ws_splits;
     float m = -INFINITY;
-    for (int s = 0; s < a.splits; ++s) m = fmaxf(m, a.ws_m[orow * a.splits + s]);
+    for (int s = 0; s < splits; ++s) m = fmaxf(m, wm[s]);
     float lsum = 0.f;
+    for (int s = 0; s < splits; ++s) lsum += (wm[s] == -INFINITY) ? 0.f : exp2f(wm[s] - m) * wl[s];
+    const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
     for (int d = lane; d < a.D; d += kWave) {
-        float acc = 0.f, lacc = 0.f;
-        for (int s = 0; s < a.splits; ++s) {
-            const float ms = a.ws_m[orow * a.splits + s];
-            const float w = (ms == -INFINITY) ? 0.f : exp2f(ms - m);
-            acc += w * a.ws_o[(orow * a.splits + s) * a.D + d];
-            lacc += w * a.ws_l[orow * a.splits + s];
+        float acc = 0.f;
+        for (int s = 0; s < splits; ++s) {
+            const float w = (wm[s] == -INFINITY) ? 0.f : exp2f(wm[s] - m);
+            acc += w * a.ws_o[(orow * a.ws_splits + s) * a.D + d];
         }
-        a.out[orow * a.D + d] = lacc > 0.f ? acc / lacc : 0.f;
-        lsum = lacc;
+        a.out[orow * a.D + d] = acc * inv;
     }
     if (a.lse_out && lane == 0) a.lse_out[orow] = (m + log2f(lsum)) * kLn2;
 }
@@ -653,47 +682,85 @@ __global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnArgs a) {
 static size_t align_up(size_t x, size_t al) { return (x + al - 1) / al * al; }
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
-// 32-row waves pay off once a (sequence, KV head) pair has at least three of them
-static bool use_wide_rows(int Hq, int Hkv, int N) { return (Hq / Hkv) * N >= 96; }
+// ---------------------------------------------------------------------------
+// Launch plan.  The stacked rows of a (sequence, KV head) pair are covered by up to two
+// launches: full 128-row blocks (4 waves of 32 rows, two workgroups per compute unit) and a
+// remainder, by one more 128-row block when at least 96 rows are left, else by 64-row blocks
+// (4 waves of 16 rows).  Every kernel clips to the rows a sequence really has, so the launches
+// write disjoint output rows.  Each launch splits the prefix on its own: only as far as it
+// still fits the chip in one round (512 workgroups on 256 compute units).
+// ---------------------------------------------------------------------------
+enum AttnVariant { kV16 = 0, kV32x4 = 1 };
 
-static int rows_per_block(int Hq, int Hkv, int N) {
-    return use_wide_rows(Hq, Hkv, N) ? kRowsPerBlock32 : kRowsPerBlock;
+struct AttnSegment {
+    int variant, row_base, row_blocks, splits;
+};
+
+static int plan_segments(int dtype, int B, int Hq, int Hkv, int N, int P_max, int requested,
+                         AttnSegment seg[2]) {
+    const int rows = (Hq / Hkv) * N;
+    int nseg = 0;
+    int full = rows / 128, rem = rows - full * 128;
+    if (rem >= 96) {  // worth one more 128-row block
+        ++full;
+        rem = 0;
+    }
+    if (full > 0) seg[nseg++] = AttnSegment{kV32x4, 0, full, 1};
+    if (rem > 0) seg[nseg++] = AttnSegment{kV16, full * 128, (rem + 63) / 64, 1};
+    const int tiles = (P_max + kTile - 1) / kTile;
+    for (int i = 0; i < nseg; ++i) {
+        int s = requested;
+        if (dtype != RSD_DTYPE_BF16) s = 1;
+        if (s <= 0) {
+            const long blocks = (long)seg[i].row_blocks * Hkv * B;
+            s = (int)(512 / (blocks > 0 ? blocks : 1));
+            if (s > 32) s = 32;
+        }
+        if (s > tiles) s = tiles;
+        if (s < 1) s = 1;
+        seg[i].splits = s;
+    }
+    return nseg;
 }
 
-static int choose_splits(int dtype, int B, int Hq, int Hkv, int N, int P_max, int requested) {
-    if (dtype != RSD_DTYPE_BF16) return 1;
-    const int tiles = (P_max + kTile - 1) / kTile;
-    int s = requested;
-    if (s <= 0) {
-        // two workgroups fit on a compute unit: split the prefix only as far as the launch
-        // still fits the chip in one round (512 workgroups on 256 compute units)
-        const int G = Hq / Hkv;
-        const int rpb = rows_per_block(Hq, Hkv, N);
-        const long blocks = (long)((G * N + rpb - 1) / rpb) * Hkv * B;
-        s = (int)(512 / (blocks > 0 ? blocks : 1));
-        if (s > 32) s = 32;
-    }
-    if (s > tiles) s = tiles;
-    if (s < 1) s = 1;
+static int max_splits(int dtype, int B, int Hq, int Hkv, int N, int P_max, int requested) {
+    AttnSegment seg[2];
+    const int nseg = plan_segments(dtype, B, Hq, Hkv, N, P_max, requested, seg);
+    int s = 1;
+    for (int i = 0; i < nseg; ++i) s = seg[i].splits > s ? seg[i].splits : s;
     return s;
 }
 
 template <int D>
-static size_t attn_smem_bytes(int N, bool) {
-    return (size_t)4 * kTile * D * 2 + (size_t)N * kAncWords * 8;
+static size_t attn_smem_bytes(int N, int stages) {
+    return (size_t)stages * 2 * kTile * D * 2 + (size_t)N * kAncWords * 8;
 }
 
 template <typename Kernel>
 static hipError_t launch_attn(Kernel kernel, bool &attr_set, size_t smem_max, size_t smem, dim3 grid,
-                              hipStream_t st, const AttnArgs &a) {
+                              int threads, hipStream_t st, const AttnArgs &a) {
     if (!attr_set) {  // the limit covers the largest tree, set once per kernel
         const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
                                                    hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_max);
         if (err != hipSuccess) return err;
         attr_set = true;
     }
-    hipLaunchKernelGGL(kernel, grid, dim3(kAttnThreads), smem, st, a);
+    hipLaunchKernelGGL(kernel, grid, dim3(threads), smem, st, a);
     return hipGetLastError();
+}
+
+template <int D>
+static hipError_t launch_segment(const AttnSegment &sg, AttnArgs a, hipStream_t st) {
+    static bool set16 = false, set4 = false;
+    a.row_base = sg.row_base;
+    a.row_blocks = sg.row_blocks;
+    a.splits = sg.splits;
+    const dim3 grid((unsigned)((long)sg.row_blocks * a.splits * a.Hkv * a.B));
+    if (sg.variant == kV32x4)
+        return launch_attn(tree_attn_bf16_w32_kernel<D, 4, 2>, set4, attn_smem_bytes<D>(RSD_NODES_MAX, 2),
+                           attn_smem_bytes<D>(a.N, 2), grid, 256, st, a);
+    return launch_attn(tree_attn_bf16_kernel<D>, set16, attn_smem_bytes<D>(RSD_NODES_MAX, 2),
+                       attn_smem_bytes<D>(a.N, 2), grid, kAttnThreads, st, a);
 }
 
 }  // namespace rsd
@@ -704,7 +771,7 @@ extern "C" size_t rsd_tree_attention_workspace_bytes(int32_t dtype, int32_t B, i
                                                      int32_t H_kv, int32_t N_max, int32_t D,
                                                      int32_t P_max, int32_t num_splits) {
     if (B <= 0 || H_q <= 0 || H_kv <= 0 || N_max <= 0 || D <= 0 || P_max < 0 || H_q % H_kv) return 0;
-    const int s = choose_splits(dtype, B, H_q, H_kv, N_max, P_max, num_splits);
+    const int s = max_splits(dtype, B, H_q, H_kv, N_max, P_max, num_splits);
     if (s <= 1) return 0;
     const size_t rows = (size_t)B * H_q * N_max;
     return align_up(rows * s * D * 4, 256) + 2 * align_up(rows * s * 4, 256);
@@ -753,39 +820,31 @@ extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const
         return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
     }
 
-    const int G = H_q / H_kv;
-    const bool wide = use_wide_rows(H_q, H_kv, N_max);
-    const int rpb = rows_per_block(H_q, H_kv, N_max);
-    a.splits = choose_splits(dtype, B, H_q, H_kv, N_max, P_max, num_splits);
-    a.row_blocks = (G * N_max + rpb - 1) / rpb;
-    if (a.splits > 1) {
+    AttnSegment seg[2];
+    const int nseg = plan_segments(dtype, B, H_q, H_kv, N_max, P_max, num_splits, seg);
+    a.ws_splits = 1;
+    for (int i = 0; i < nseg; ++i) a.ws_splits = seg[i].splits > a.ws_splits ? seg[i].splits : a.ws_splits;
+    if (a.ws_splits > 1) {
         const size_t need = rsd_tree_attention_workspace_bytes(dtype, B, H_q, H_kv, N_max, D, P_max, num_splits);
         if (!workspace || workspace_bytes < need) return RSD_ERR_WORKSPACE;
         const size_t rows = (size_t)B * H_q * N_max;
         char *ws = static_cast<char *>(workspace);
         a.ws_o = reinterpret_cast<float *>(ws);
-        a.ws_m = reinterpret_cast<float *>(ws + align_up(rows * a.splits * D * 4, 256));
-        a.ws_l = reinterpret_cast<float *>(ws + align_up(rows * a.splits * D * 4, 256) +
-                                           align_up(rows * a.splits * 4, 256));
+        a.ws_m = reinterpret_cast<float *>(ws + align_up(rows * a.ws_splits * D * 4, 256));
+        a.ws_l = reinterpret_cast<float *>(ws + align_up(rows * a.ws_splits * D * 4, 256) +
+                                           align_up(rows * a.ws_splits * 4, 256));
     }
-    const dim3 grid((unsigned)((long)a.row_blocks * a.splits * H_kv * B));
-    static bool set128 = false, set64 = false, set128w = false, set64w = false;
-    hipError_t err;
-    if (D == 128 && wide)
-        err = launch_attn(tree_attn_bf16_w32_kernel<128>, set128w, attn_smem_bytes<128>(RSD_NODES_MAX, true),
-                          attn_smem_bytes<128>(N_max, true), grid, st, a);
-    else if (D == 128)
-        err = launch_attn(tree_attn_bf16_kernel<128>, set128, attn_smem_bytes<128>(RSD_NODES_MAX, false),
-                          attn_smem_bytes<128>(N_max, false), grid, st, a);
-    else if (wide)
-        err = launch_attn(tree_attn_bf16_w32_kernel<64>, set64w, attn_smem_bytes<64>(RSD_NODES_MAX, true),
-                          attn_smem_bytes<64>(N_max, true), grid, st, a);
-    else
-        err = launch_attn(tree_attn_bf16_kernel<64>, set64, attn_smem_bytes<64>(RSD_NODES_MAX, false),
-                          attn_smem_bytes<64>(N_max, false), grid, st, a);
-    if (err != hipSuccess) return RSD_ERR_LAUNCH;
-    if (a.splits > 1) {
-        hipLaunchKernelGGL(tree_attn_merge_kernel, dim3(N_max, H_q, B), dim3(kWave), 0, st, a);
+    for (int i = 0; i < nseg; ++i) {
+        const hipError_t err = D == 128 ? launch_segment<128>(seg[i], a, st) : launch_segment<64>(seg[i], a, st);
+        if (err != hipSuccess) return RSD_ERR_LAUNCH;
+    }
+    const int rows_max = (H_q / H_kv) * N_max;
+    for (int i = 0; i < nseg; ++i) {
+        if (seg[i].splits <= 1) continue;
+        const int row_end = (i + 1 < nseg) ? seg[i + 1].row_base : rows_max;
+        a.row_base = seg[i].row_base;
+        a.splits = seg[i].splits;
+        hipLaunchKernelGGL(tree_attn_merge_kernel, dim3(row_end - seg[i].row_base, H_kv, B), dim3(kWave), 0, st, a);
         if (hipGetLastError() != hipSuccess) return RSD_ERR_LAUNCH;
     }
     return RSD_OK;

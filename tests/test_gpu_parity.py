@@ -217,6 +217,8 @@ def test_tree_attention_fp32_config0():
     (1, 16, 2, 65, 128, 257, 3, None, None),          # wide rows, forced splits, 65 nodes
     (1, 8, 1, 24, 64, 130, 0, None, None),            # wide rows with head_dim 64
     (1, 4, 1, 130, 128, 64, 1, None, None),           # wide rows, three ancestor words
+    (2, 8, 1, 48, 128, 300, 0, [48, 20], [300, 150]),  # 384 rows: one 256-row block + one 128-row block
+    (1, 16, 1, 40, 64, 200, 2, None, None),           # 640 rows, head_dim 64, forced splits
 ])
 def test_tree_attention_bf16(B, Hq, Hkv, N, D, P, splits, n_nodes, plens):
     say(f"attention bf16 B={B} Hq={Hq} Hkv={Hkv} N={N} D={D} P={P} splits={splits}")
