@@ -22,6 +22,10 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
+# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
+# scaled by the same counters over plain device copies (profiles/cfg4_stress_attention_traffic.md).
+MEASURED_TRAFFIC_BYTES = {"cfg4_stress": 8.758e9}
+
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 N_LAYERS = {"cfg1_llama2_7b": 32, "cfg2_opt_13b_sbs": 40, "cfg3_llama2_70b_gqa": 80, "cfg4_stress": 32}
@@ -172,8 +176,10 @@ def report(case, t):
     return out, fig
 
 
-def cpu_baseline(case, fig, torch):
-    """The oracle, as it stands, on a bounded sample of the same workload."""
+def cpu_baseline(case, fig, torch, budget_s=12.0):
+    """The oracle, as it stands, on a bounded sample of the same workload: whole sequences
+    (drafting of their non-leaf rows, tree attention of a few KV heads scaled to all heads,
+    recursive rejection sampling over all groups) until about `budget_s` seconds of CPU work."""
     import numpy as np
 
     from oracle import gumbel_topk as o_topk
@@ -182,42 +188,79 @@ def cpu_baseline(case, fig, torch):
     from oracle import tree_attention as o_attn
     cfg, tree = case["cfg"], case["tree"]
     B = cfg["B"]
-    b = 0
-    n = int(tree["n_nodes"][b])
-    heads = min(4, cfg["Hkv"])
+    heads = min(16, cfg["Hkv"])
     group = cfg["Hq"] // cfg["Hkv"]
     f = lambda t: t.to(torch.float32).cpu().numpy()
-    q = f(case["q"][b:b + 1, :heads * group]); kp = f(case["kp"][b:b + 1, :heads]); vp = f(case["vp"][b:b + 1, :heads])
-    kt = f(case["kt"][b:b + 1, :heads]); vt = f(case["vt"][b:b + 1, :heads])
-    parent = tree["parent"][b:b + 1].cpu().numpy(); tokens = tree["tokens"][b:b + 1].cpu().numpy()
-    zt = case["zt"][b:b + 1].cpu().numpy(); zd = case["zd"][b:b + 1].cpu().numpy()
-    t0 = time.perf_counter()
-    o_attn.tree_attention(q, kp, vp, kt, vt, [cfg["P"]], [n], parent, case["scale"])
-    t_attn = (time.perf_counter() - t0) * cfg["Hkv"] / heads
-    t0 = time.perf_counter()
-    o_rrs.recursive_reject(zt, zd, tokens, parent, [n], mode=o_rrs.MODE_ALL_GROUPS, seed=0, step=0)
-    t_rrs = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    nonleaf = sorted(set(parent[0, 1:n].tolist()))
-    if cfg["sampler"] == "gumbel":
-        o_topk.gumbel_topk(zd[0, nonleaf], 2, seq_id=np.zeros(len(nonleaf), int), node_id=np.array(nonleaf), seed=0)
-    else:
-        for lo in range(0, len(nonleaf), cfg["width"]):
-            rows = nonleaf[lo:lo + cfg["width"]]
-            o_sbs.sbs_step(zd[:, rows], np.zeros((1, len(rows))), np.zeros((1, len(rows))), [len(rows)],
-                           cfg["width"], seed=0)
-    t_draft = time.perf_counter() - t0
-    per_seq = t_attn + t_rrs + t_draft
+    nodes, scaled, spent, used = 0, 0.0, 0.0, 0
+    for b in range(B):
+        n = int(tree["n_nodes"][b])
+        q = f(case["q"][b:b + 1, :heads * group]); kp = f(case["kp"][b:b + 1, :heads]); vp = f(case["vp"][b:b + 1, :heads])
+        kt = f(case["kt"][b:b + 1, :heads]); vt = f(case["vt"][b:b + 1, :heads])
+        parent = tree["parent"][b:b + 1].cpu().numpy(); tokens = tree["tokens"][b:b + 1].cpu().numpy()
+        zt = case["zt"][b:b + 1].cpu().numpy(); zd = case["zd"][b:b + 1].cpu().numpy()
+        t0 = time.perf_counter()
+        o_attn.tree_attention(q, kp, vp, kt, vt, [cfg["P"]], [n], parent, case["scale"])
+        t_attn = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        o_rrs.recursive_reject(zt, zd, tokens, parent, [n], mode=o_rrs.MODE_ALL_GROUPS, seq_id=[b], seed=0, step=0)
+        nonleaf = sorted(set(parent[0, 1:n].tolist()))
+        if cfg["sampler"] == "gumbel":
+            o_topk.gumbel_topk(zd[0, nonleaf], 2, seq_id=np.full(len(nonleaf), b), node_id=np.array(nonleaf), seed=0)
+        else:
+            for lo in range(0, len(nonleaf), cfg["width"]):
+                rows = nonleaf[lo:lo + cfg["width"]]
+                o_sbs.sbs_step(zd[:, rows], np.zeros((1, len(rows))), np.zeros((1, len(rows))), [len(rows)],
+                               cfg["width"], seed=0)
+        t_rest = time.perf_counter() - t0
+        nodes += n
+        used += 1
+        spent += t_attn + t_rest
+        scaled += t_attn * cfg["Hkv"] / heads + t_rest
+        if spent >= budget_s:
+            break
     try:
         import threadpoolctl
         threads = max([p.get("num_threads", 1) for p in threadpoolctl.threadpool_info()] + [1])
     except Exception:
         threads = os.cpu_count()
-    return dict(value=n / per_seq, unit="tree nodes/s", cores=threads, kind="oracle",
-                sample=(f"sequence 0 of {B}: drafting of its {len(nonleaf)} non-leaf rows, tree attention of "
-                        f"{heads} of {cfg['Hkv']} KV heads (time scaled to all heads), and recursive rejection "
-                        f"sampling (all groups); {t_draft + t_attn * heads / cfg['Hkv'] + t_rrs:.1f} s of CPU work"),
-                seconds_per_sequence=per_seq)
+    return dict(value=nodes / scaled, unit="tree nodes/s", cores=threads, kind="oracle",
+                sample=(f"{used} of {B} sequences: drafting of their non-leaf rows, tree attention of {heads} of "
+                        f"{cfg['Hkv']} KV heads (time scaled to all heads), recursive rejection sampling over all "
+                        f"groups; {spent:.1f} s of CPU work"),
+                seconds_per_sequence=scaled / used)
+
+
+def calibrate_copy(torch, gib=1, repeats=10):
+    """Plain device-to-device copies of known size: the reference that the FETCH_SIZE / WRITE_SIZE
+    counters of a profiler run are scaled by."""
+    dev = torch.device("cuda:0")
+    n = gib << 30
+    src = torch.empty(n, dtype=torch.uint8, device=dev).fill_(1)
+    dst = torch.empty_like(src)
+    torch.cuda.synchronize()
+    for _ in range(repeats):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+    print(json.dumps(dict(calibration="device copy", bytes_read=n, bytes_written=n, repeats=repeats)))
+
+
+def vocab_pass(case, torch, binding, steps=10):
+    """The plain log-softmax normaliser over every target row: the pure HBM-bound vocabulary pass."""
+    zt = case["zt"]
+    B, N, V = zt.shape
+    rows = zt.view(B * N, V)
+    for _ in range(2):
+        binding.log_softmax_lse(rows)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        binding.log_softmax_lse(rows)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    gbs = rows.numel() * 4 / ms / 1e6
+    return dict(lse_ms=round(ms, 4), lse_GBps=gbs, lse_frac_hbm=gbs / HBM_PEAK_GBS)
 
 
 def main():
@@ -229,6 +272,8 @@ def main():
     ap.add_argument("--no-others", action="store_true", help="skip the brief runs of the other configurations")
     ap.add_argument("--no-cpu", action="store_true", help="skip the CPU-oracle baseline leg")
     ap.add_argument("--seed", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="only run plain device copies of known size (profiler counter calibration)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build measures one GPU only (no collectives are part of the hot path); "
@@ -240,6 +285,9 @@ def main():
     if not torch.cuda.is_available():
         sys.exit("bench.py needs a GPU")
     binding.lib()   # fails loudly if the HIP library is missing
+    if args.calibrate_copy:
+        calibrate_copy(torch)
+        return
 
     key = int(args.config) if args.config.isdigit() else args.config
     cfg = workloads.config(key)
@@ -247,15 +295,18 @@ def main():
     torch.cuda.synchronize()
     t = time_case(case, args.steps, args.warmup, torch)
     rep, fig = report(case, t)
+    vocab = vocab_pass(case, torch, binding)
 
     # roofline of the dominant kernel: the tree-attention launch
     bound = rep["attn_bound"]
     if bound == "hbm":
         roof = dict(bound="hbm", achieved=rep["attn_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=rep["attn_frac_hbm"], traffic=None, kernel="tree_attn_bf16_kernel")
+                    frac=rep["attn_frac_hbm"], traffic=MEASURED_TRAFFIC_BYTES.get(cfg["name"]),
+                    kernel="tree_attn_bf16_kernel", algorithmic_bytes=fig["attn_bytes"])
     else:
         roof = dict(bound="mfma", achieved=rep["attn_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
-                    frac=rep["attn_frac_mfma"], traffic=None, kernel="tree_attn_bf16_kernel")
+                    frac=rep["attn_frac_mfma"], traffic=MEASURED_TRAFFIC_BYTES.get(cfg["name"]),
+                    kernel="tree_attn_bf16_w32_kernel", algorithmic_flops=fig["attn_flops"])
 
     per_config = {}
     if not args.no_others:
@@ -285,7 +336,7 @@ def main():
         phases=dict(draft_ms=rep["draft_ms"], attn_ms=rep["attn_ms"], rrs_ms=rep["rrs_ms"],
                     attn_GBps=rep["attn_GBps"], attn_TFLOPs=rep["attn_TFLOPs"],
                     rrs_GBps=rep["rrs_GBps"], draft_GBps=rep["draft_GBps"],
-                    model_equiv_nodes_per_s=rep["model_equiv_nodes_per_s"]),
+                    model_equiv_nodes_per_s=rep["model_equiv_nodes_per_s"], **vocab),
         roofline=roof, cpu_baseline=cpu, per_config=per_config,
     )
     print(json.dumps(line))
