@@ -112,9 +112,10 @@ __device__ __forceinline__ void chain4(const float et[4], const float ed[4], con
     for (int i = 0; i < 4; ++i) q[i] = et[i] * r.inv_st;
 #pragma unroll
     for (int j = 0; j < RSD_K_MAX - 1; ++j) {
-        if (j >= nst) break;
+        if (j < nst) {  // wave-uniform; keeps the scalar arrays statically indexed
 #pragma unroll
-        for (int i = 0; i < 4; ++i) q[i] = fmaxf(q[i] - ed[i] * r.is[j], 0.f) * r.iS[j];
+            for (int i = 0; i < 4; ++i) q[i] = fmaxf(q[i] - ed[i] * r.is[j], 0.f) * r.iS[j];
+        }
     }
 }
 
@@ -124,9 +125,10 @@ __device__ __forceinline__ float chain1_masked(float et, float ed, int rs, const
     float q = et * r.inv_st;
 #pragma unroll
     for (int j = 0; j < RSD_K_MAX - 1; ++j) {
-        if (j >= nst) break;
-        const float p = (rs < j) ? 0.f : ed * r.is[j];
-        q = fmaxf(q - p, 0.f) * r.iS[j];
+        if (j < nst) {
+            const float p = (rs < j) ? 0.f : ed * r.is[j];
+            q = fmaxf(q - p, 0.f) * r.iS[j];
+        }
     }
     return q;
 }
@@ -182,6 +184,7 @@ __device__ void group_lse_pass(const float *zt, const float *zd, int V, float c2
             if (!((hits >> it) & 1ull)) {
                 ad.s += (exp2f(e[0] - ad.m) + exp2f(e[1] - ad.m)) + (exp2f(e[2] - ad.m) + exp2f(e[3] - ad.m));
             } else {
+#pragma unroll
                 for (int i = 0; i < 4; ++i)
                     if (removal_stage((c << 2) + i, sh.g.tok, sh.g.K) == sh.g.K) ad.s += exp2f(e[i] - ad.m);
             }
@@ -239,6 +242,7 @@ __device__ double group_residual_mass(const float *zt, const float *zd, int V, f
 #pragma unroll
             for (int i = 0; i < 4; ++i) r[i] = fmaxf(q[i] - ed[i] * inv_s, 0.f);
         } else {
+#pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int rs = removal_stage((c << 2) + i, g.tok, g.K);
                 const float p = (rs < nst) ? 0.f : ed[i] * inv_s;
@@ -347,10 +351,14 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
     const int nchunk = a.V >> 2;
     const float c2 = a.c2;
     // bit (4 j + e) set: this thread's register entry (j, e) is a child token
-    uint64_t elmask = 0;
+    static_assert(CH * 4 <= 128, "element mask holds 128 entries");
+    uint64_t elmask[2] = {0, 0};
     for (int i = 0; i < K; ++i) {
         const int x = sh.g.tok[i], c = x >> 2;
-        if (c % T == tid) elmask |= 1ull << (((c / T) << 2) | (x & 3));
+        if (c % T == tid) {
+            const int bit = ((c / T) << 2) | (x & 3);
+            if (bit < 64) elmask[0] |= 1ull << bit; else elmask[1] |= 1ull << (bit - 64);
+        }
     }
 
     float ut[CH * 4], ed[CH * 4];
@@ -396,7 +404,8 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
         st += (ut[4 * j] + ut[4 * j + 1]) + (ut[4 * j + 2] + ut[4 * j + 3]);
         float dsum[4];
 #pragma unroll
-        for (int e = 0; e < 4; ++e) dsum[e] = ((elmask >> (4 * j + e)) & 1ull) ? 0.f : ed[4 * j + e];
+        for (int e = 0; e < 4; ++e)
+            dsum[e] = ((elmask[(4 * j + e) >> 6] >> ((4 * j + e) & 63)) & 1ull) ? 0.f : ed[4 * j + e];
         sd += (dsum[0] + dsum[1]) + (dsum[2] + dsum[3]);
     }
     st = wave_sum(st);
@@ -463,7 +472,7 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
         }
         // x_k leaves the draft distribution either way
         if (tid == k) ce = 0.0;
-        if (elmask != 0ull) {
+        if ((elmask[0] | elmask[1]) != 0ull) {
             const int xk = sh.g.tok[k], ck = xk >> 2;
             const int target = (ck % T == tid) ? (((ck / T) << 2) | (xk & 3)) : -1;
 #pragma unroll
@@ -539,6 +548,7 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
 #pragma unroll
             for (int i = 0; i < 4; ++i) r[i] = fmaxf(q[i] - ed[i] * inv_s_last, 0.f);  // ~ q^(K+1)
         } else {
+#pragma unroll
             for (int i = 0; i < 4; ++i) {
                 const int rs = removal_stage((c << 2) + i, g.tok, K);
                 q[i] = chain1_masked(et[i], ed[i], rs, cr, K - 1);
@@ -894,9 +904,11 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
     a.work = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * N_max * 4, 256);
     a.wq = reinterpret_cast<int *>(ws + off);
     hipStream_t st = (hipStream_t)stream;
-    const bool reg8 = V <= kRegThreads * 4 * 16;
+    // rows of up to 32768 entries fit the register-resident variant (128 data registers per
+    // thread); a 25-chunk variant for 50k vocabularies spills and is slower than streaming
+    const bool reg16 = V <= kRegThreads * 4 * 16;
     if (mode == RSD_MODE_PATH) {
-        if (reg8)
+        if (reg16)
             hipLaunchKernelGGL((rrs_path_kernel<kRegThreads, 16>), dim3(B), dim3(kRegThreads), 0, st, a);
         else
             hipLaunchKernelGGL((rrs_path_kernel<kGroupThreads, 0>), dim3(B), dim3(kGroupThreads), 0, st, a);
@@ -912,7 +924,7 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
         const long items_max = (long)B * N_max;
         const int grid = (int)(items_max < n_cu ? items_max : n_cu);
         hipLaunchKernelGGL(rrs_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a);
-        if (reg8)
+        if (reg16)
             hipLaunchKernelGGL((rrs_group_kernel<kRegThreads, 16>), dim3(grid), dim3(kRegThreads), 0, st, a);
         else
             hipLaunchKernelGGL((rrs_group_kernel<kGroupThreads, 0>), dim3(2 * grid), dim3(kGroupThreads), 0, st, a);

@@ -363,7 +363,8 @@ __global__ __launch_bounds__(256) void sbs_select_kernel(SbsSelectArgs a) {
     s_key[t] = live ? (w * a.V + tok) : INT_MAX;
     __syncthreads();
     int total = 0, rank = 0;
-    for (int o = 0; o < 256; ++o) {
+    const int slots = a.W_in * a.W;  // thread slots that can hold a candidate
+    for (int o = 0; o < slots; ++o) {
         const double op = s_psi[o];
         const int ok = s_key[o];
         const bool olive = ok != INT_MAX;
