@@ -22,6 +22,7 @@
 // A long prefix can be split over several workgroups (flash-decoding style);
 // a small second kernel merges the partial (max, sum, output) triples.
 #include <hip/hip_runtime.h>
+#include <type_traits>
 #include <math.h>
 
 #include "../../include/rsd.h"
@@ -132,6 +133,36 @@ __device__ __forceinline__ void stage_tile(const __bf16 *ksrc, const __bf16 *vsr
         const int64_t off = (int64_t)rs * stride + c * 8;
         __builtin_amdgcn_global_load_lds((global_void *)(ksrc + off), (lds_void *)(kdst + rbase * D), 16, 0, 0);
         __builtin_amdgcn_global_load_lds((global_void *)(vsrc + off), (lds_void *)(vdst + rbase * D), 16, 0, 0);
+    }
+}
+
+// The same for a tile that lies wholly below `limit`: the per-thread part of the source offset
+// (`lane_off` bytes: the thread's row within one pass of the workgroup and its swizzled chunk)
+// never changes; `ksrc` / `vsrc` are the wave-uniform byte addresses of the tile's first row,
+// `pass_bytes` the distance between the rows of consecutive passes, and the LDS destinations
+// are computed from the scalar wave index `wave_s`.  Requires that `lane_off` fits 32 bits.
+template <int D, int THREADS>
+__device__ __forceinline__ uint32_t stage_lane_offset(int64_t stride) {
+    constexpr int DCH = D / 8, RPI = 64 / DCH;
+    const int wave = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const int r = wave * RPI + lane / DCH;  // the swizzle only sees r % 16, equal in every pass
+    const int c = (lane % DCH) ^ swz<D>(r);
+    return (uint32_t)((r * stride + c * 8) * 2);
+}
+
+template <int D, int THREADS>
+__device__ __forceinline__ void stage_tile_full(const char *ksrc, const char *vsrc, int64_t pass_bytes,
+                                                uint32_t lane_off, int wave_s, __bf16 *kdst, __bf16 *vdst) {
+    constexpr int DCH = D / 8, RPI = 64 / DCH, WAVES = THREADS / 64;
+    constexpr int NIT = kTile / (RPI * WAVES);
+    static_assert((RPI * WAVES) % 16 == 0 || NIT == 1, "swizzle must repeat from pass to pass");
+#pragma unroll
+    for (int it = 0; it < NIT; ++it) {
+        const int rbase = (it * WAVES + wave_s) * RPI;
+        const char *kb = ksrc + it * pass_bytes;  // wave-uniform
+        const char *vb = vsrc + it * pass_bytes;
+        __builtin_amdgcn_global_load_lds((global_void *)(kb + lane_off), (lds_void *)(kdst + rbase * D), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_void *)(vb + lane_off), (lds_void *)(vdst + rbase * D), 16, 0, 0);
     }
 }
 
@@ -413,12 +444,27 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
     const __bf16 *kt = reinterpret_cast<const __bf16 *>(a.kt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
     const __bf16 *vt = reinterpret_cast<const __bf16 *>(a.vt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
 
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const bool lean_stage = a.sp < (1 << 24);  // per-thread byte offset fits 32 bits
+    const uint32_t lane_off = stage_lane_offset<D, THREADS>(lean_stage ? a.sp : 0);
+    const int64_t pass_bytes = (int64_t)(THREADS / 64) * (64 / (D / 8)) * a.sp * 2;
+    const int64_t tile_bytes = (int64_t)kTile * a.sp * 2;
+    int64_t pre_off = (int64_t)t0 * tile_bytes;  // byte offset of the next prefix tile (staged in order)
     auto stage = [&](int u) {  // tile u of this block's schedule into ring buffer u % STAGES
         const int buf = u % STAGES;
-        if (u < npre)
-            stage_tile<D, THREADS>(kp, vp, a.sp, (t0 + u) * kTile, plen, Ks + buf * kTile * D, Vs + buf * kTile * D);
-        else
-            stage_tile<D, THREADS>(kt, vt, D, (u - npre) * kTile, n, Ks + buf * kTile * D, Vs + buf * kTile * D);
+        __bf16 *kd = Ks + buf * kTile * D, *vd = Vs + buf * kTile * D;
+        if (u < npre) {
+            const int row0 = (t0 + u) * kTile;
+            if (lean_stage && row0 + kTile <= plen)
+                stage_tile_full<D, THREADS>(reinterpret_cast<const char *>(kp) + pre_off,
+                                            reinterpret_cast<const char *>(vp) + pre_off, pass_bytes,
+                                            lane_off, wave_s, kd, vd);
+            else
+                stage_tile<D, THREADS>(kp, vp, a.sp, row0, plen, kd, vd);
+            pre_off += tile_bytes;
+        } else {
+            stage_tile<D, THREADS>(kt, vt, D, (u - npre) * kTile, n, kd, vd);
+        }
     };
 
     floatx16 o[DT];
@@ -439,75 +485,84 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
     }
     __syncthreads();
 
-    for (int u = 0; u < ntiles; ++u) {
+    // Full prefix tiles (nearly all of them) run the mask-free copy of the loop body in a loop of
+    // their own; the ragged last prefix tile and the tree tiles follow in the masked copy.
+    const int nfull = min(max(plen / kTile - t0, 0), npre);
+    auto iteration = [&](int u, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
         const int buf = u % STAGES;
         // the buffer of tile u + STAGES - 1 was last read in iteration u - 1
         if (u + STAGES - 1 < ntiles) stage(u + STAGES - 1);
 
         if (wave_active) {
-            // ---- S^T = K Q^T: two 32-key tiles ------------------------------------
-            // lane (q32, h) reads chunk 2 ks + h of tile row 32 t + q32
+            // One 64-key tile is processed as two 32-key halves so that, inside this wave's own
+            // instruction stream, the exponentials of one half issue in the shadow of the matrix
+            // instructions of the other (matrix and vector work of different waves on one SIMD
+            // do not overlap; independent work inside one wave does):
+            //   S0 = K0 Q^T | max(S0) | S1 = K1 Q^T || P0 = exp2(S0 - m) | max(S1) |
+            //   O += V0^T P0 || P1 = exp2(S1 - m) | O += V1^T P1
+            // The running maximum m is only raised when some row's new maximum exceeds it by more
+            // than kSlack (in log2 units), so the common case has no branch and no rescale between
+            // the matrix groups; p <= 2^kSlack keeps bf16's relative precision.
+            constexpr float kSlack = 8.f;
             const __bf16 *kb = Ks + buf * kTile * D + q32 * D;
             const int ksw = swz<D>(q32);
-            floatx16 s[2];
-#pragma unroll
-            for (int t = 0; t < 2; ++t) {
-#pragma unroll
-                for (int r = 0; r < 16; ++r) s[t][r] = 0.f;
-#pragma unroll
-                for (int ks = 0; ks < KS; ++ks) {
-                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kb + t * 32 * D + (((ks * 2 + h) ^ ksw) << 3));
-                    s[t] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], s[t], 0, 0, 0);
-                }
-            }
-
-            // ---- mask (tree tiles and ragged tails only), online softmax ------------
             const bool is_tree = u >= npre;
             const int row0 = is_tree ? (u - npre) * kTile : (t0 + u) * kTile;
             const int limit = is_tree ? n : plen;
-            if (is_tree || row0 + kTile > limit) {
-                uint64_t vis = ~0ull;
+            uint64_t vis = ~0ull;
+            if (MASKED) {
                 if (is_tree) vis = anc[qi * kAncWords + (u - npre)];
                 if (row0 + kTile > limit) vis &= (1ull << (limit - row0)) - 1ull;
-#pragma unroll
-                for (int t = 0; t < 2; ++t)
-#pragma unroll
-                    for (int r = 0; r < 16; ++r) {
-                        const int kk = t * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
-                        s[t][r] = ((vis >> kk) & 1ull) ? s[t][r] : -INFINITY;
-                    }
             }
-            float mx = -INFINITY;
+            auto half_max = [&](const floatx16 &sv) -> float {  // scaled row maximum of one half
+                float mx = sv[0];
 #pragma unroll
-            for (int t = 0; t < 2; ++t)
-#pragma unroll
-                for (int r = 0; r < 16; ++r) mx = fmaxf(mx, s[t][r]);
-            mx = max_across_halves(mx) * a.scale_log2;
-            const float m_new = fmaxf(m, mx);
-            const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-            const float alpha = __builtin_amdgcn_exp2f(m - m_use);
-            float psum = 0.f;
-#pragma unroll
-            for (int t = 0; t < 2; ++t)
+                for (int r = 1; r < 16; ++r) mx = fmaxf(mx, sv[r]);
+                return max_across_halves(mx) * a.scale_log2;
+            };
+            // Masked keys enter as -inf in the accumulator the first product starts from (lane
+            // group h holds keys 32 t + 8 (r / 4) + 4 h + r % 4 of row q32 in register r of half t).
+            auto mask_init = [&](floatx16 &sv, int t) {
 #pragma unroll
                 for (int r = 0; r < 16; ++r) {
-                    const float p = __builtin_amdgcn_exp2f(fmaf(s[t][r], a.scale_log2, -m_use));
-                    s[t][r] = p;
-                    psum += p;
+                    const int kk = t * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                    sv[r] = ((vis >> kk) & 1ull) ? 0.f : -INFINITY;
                 }
-            l = l * alpha + psum;
-            m = m_new;
-            if (__any(alpha != 1.f)) {
+            };
+            auto raise_max = [&](float hm) {
+                if (__any(hm > m + kSlack)) {
+                    const float m_new = fmaxf(m, hm);
+                    const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
+                    l *= alpha;
 #pragma unroll
-                for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
-            }
-
-            // ---- O^T += V^T P^T: four 16-key steps --------------------------------
-            bf16x8 pf[4];
+                    for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+                    m = m_new;
+                }
+            };
+            auto half_exp = [&](floatx16 &sv, bf16x8 &p0, bf16x8 &p1) {
+                const float mu = (m == -INFINITY) ? 0.f : m;
+                float ps = 0.f;
 #pragma unroll
-            for (int mm = 0; mm < 4; ++mm)
+                for (int r = 0; r < 16; ++r) {
+                    sv[r] = __builtin_amdgcn_exp2f(fmaf(sv[r], a.scale_log2, -mu));
+                    ps += sv[r];
+                }
+                l += ps;
 #pragma unroll
-                for (int e = 0; e < 8; ++e) pf[mm][e] = (__bf16)s[mm >> 1][8 * (mm & 1) + e];
+                for (int e = 0; e < 8; ++e) {
+                    p0[e] = (__bf16)sv[e];
+                    p1[e] = (__bf16)sv[8 + e];
+                }
+            };
+            auto qk_half = [&](floatx16 &sv, int t) {
+#pragma unroll
+                for (int ks = 0; ks < KS; ++ks) {
+                    // lane (q32, h) reads chunk 2 ks + h of tile row 32 t + q32
+                    const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kb + t * 32 * D + (((ks * 2 + h) ^ ksw) << 3));
+                    sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sv, 0, 0, 0);
+                }
+            };
             // transposing read: lane i of each 16-lane block loads row (key) i / 4 of the
             // 4-key run, four columns at 16 (block % 2) + 4 (i % 4)
             const int i16 = lane & 15;
@@ -515,16 +570,35 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
             const int vch = 2 * ((lane >> 4) & 1) + ((i16 >> 1) & 1);  // chunk within the 32-column tile
             const __bf16 *vb = Vs + buf * kTile * D + vrow * D + (i16 & 1) * 4;
             const int vsw_lo = swz<D>(vrow), vsw_hi = swz<D>(vrow + 8);
-#pragma unroll
-            for (int mm = 0; mm < 4; ++mm) {
+            auto pv_step = [&](int mm, const bf16x8 &p) {  // keys 16 mm .. 16 mm + 15
 #pragma unroll
                 for (int dt = 0; dt < DT; ++dt) {
                     const bf16x4 lo = lds_read_tr(vb + (16 * mm) * D + (((dt * 4 + vch) ^ vsw_lo) << 3));
                     const bf16x4 hi = lds_read_tr(vb + (16 * mm + 8) * D + (((dt * 4 + vch) ^ vsw_hi) << 3));
                     const bf16x8 vf = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, pf[mm], o[dt], 0, 0, 0);
+                    o[dt] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf, p, o[dt], 0, 0, 0);
                 }
+            };
+
+            floatx16 s0, s1;
+            bf16x8 pf[4];
+            if (MASKED) {
+                mask_init(s0, 0);
+                mask_init(s1, 1);
+            } else {
+#pragma unroll
+                for (int r = 0; r < 16; ++r) s0[r] = s1[r] = 0.f;
             }
+            qk_half(s0, 0);
+            raise_max(half_max(s0));
+            qk_half(s1, 1);
+            half_exp(s0, pf[0], pf[1]);
+            raise_max(half_max(s1));
+            pv_step(0, pf[0]);
+            pv_step(1, pf[1]);
+            half_exp(s1, pf[2], pf[3]);
+            pv_step(2, pf[2]);
+            pv_step(3, pf[3]);
         }
 
         // tile u + 1 must have landed; the STAGES - 2 newer tiles may still be in flight
@@ -533,7 +607,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
         else
             wait_tile_loads<0>();
         __syncthreads();
-    }
+    };
+    int u = 0;
+    for (; u < nfull; ++u) iteration(u, std::false_type{});
+    for (; u < ntiles; ++u) iteration(u, std::true_type{});
 
     // ---- epilogue -------------------------------------------------------------------
     const float lt = sum_across_halves(l);
