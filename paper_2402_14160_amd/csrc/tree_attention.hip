@@ -530,13 +530,24 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
                     sv[r] = ((vis >> kk) & 1ull) ? 0.f : -INFINITY;
                 }
             };
-            auto raise_max = [&](float hm) {
+            floatx16 s0, s1;
+            bf16x8 pf[4];
+            // `first_half_pending`: P of the first half is already formed (kept as fp32 in s0) but
+            // not yet multiplied into O, so it moves to the new reference as well
+            auto raise_max = [&](float hm, bool first_half_pending) {
                 if (__any(hm > m + kSlack)) {
                     const float m_new = fmaxf(m, hm);
                     const float alpha = (m_new == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(m - m_new);
                     l *= alpha;
 #pragma unroll
                     for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+                    if (first_half_pending) {
+#pragma unroll
+                        for (int e = 0; e < 8; ++e) {
+                            pf[0][e] = (__bf16)(s0[e] * alpha);
+                            pf[1][e] = (__bf16)(s0[8 + e] * alpha);
+                        }
+                    }
                     m = m_new;
                 }
             };
@@ -580,8 +591,6 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
                 }
             };
 
-            floatx16 s0, s1;
-            bf16x8 pf[4];
             if (MASKED) {
                 mask_init(s0, 0);
                 mask_init(s1, 1);
@@ -590,10 +599,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
                 for (int r = 0; r < 16; ++r) s0[r] = s1[r] = 0.f;
             }
             qk_half(s0, 0);
-            raise_max(half_max(s0));
+            raise_max(half_max(s0), false);
             qk_half(s1, 1);
             half_exp(s0, pf[0], pf[1]);
-            raise_max(half_max(s1));
+            raise_max(half_max(s1), true);
             pv_step(0, pf[0]);
             pv_step(1, pf[1]);
             half_exp(s1, pf[2], pf[3]);
@@ -768,13 +777,14 @@ static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 // still fits the chip in one round (512 workgroups on 256 compute units).
 // ---------------------------------------------------------------------------
 enum AttnVariant { kV16 = 0, kV32x4 = 1 };
+constexpr int kMaxSegments = 2;
 
 struct AttnSegment {
     int variant, row_base, row_blocks, splits;
 };
 
 static int plan_segments(int dtype, int B, int Hq, int Hkv, int N, int P_max, int requested,
-                         AttnSegment seg[2]) {
+                         AttnSegment seg[kMaxSegments]) {
     const int rows = (Hq / Hkv) * N;
     int nseg = 0;
     int full = rows / 128, rem = rows - full * 128;
@@ -788,7 +798,7 @@ static int plan_segments(int dtype, int B, int Hq, int Hkv, int N, int P_max, in
     for (int i = 0; i < nseg; ++i) {
         int s = requested;
         if (dtype != RSD_DTYPE_BF16) s = 1;
-        if (s <= 0) {
+        if (s <= 0) {  // fill the chip in one round: two workgroups per CU
             const long blocks = (long)seg[i].row_blocks * Hkv * B;
             s = (int)(512 / (blocks > 0 ? blocks : 1));
             if (s > 32) s = 32;
@@ -801,7 +811,7 @@ static int plan_segments(int dtype, int B, int Hq, int Hkv, int N, int P_max, in
 }
 
 static int max_splits(int dtype, int B, int Hq, int Hkv, int N, int P_max, int requested) {
-    AttnSegment seg[2];
+    AttnSegment seg[kMaxSegments];
     const int nseg = plan_segments(dtype, B, Hq, Hkv, N, P_max, requested, seg);
     int s = 1;
     for (int i = 0; i < nseg; ++i) s = seg[i].splits > s ? seg[i].splits : s;
@@ -897,7 +907,7 @@ extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const
         return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
     }
 
-    AttnSegment seg[2];
+    AttnSegment seg[kMaxSegments];
     const int nseg = plan_segments(dtype, B, H_q, H_kv, N_max, P_max, num_splits, seg);
     a.ws_splits = 1;
     for (int i = 0; i < nseg; ++i) a.ws_splits = seg[i].splits > a.ws_splits ? seg[i].splits : a.ws_splits;

@@ -227,6 +227,33 @@ def test_tree_attention_bf16(B, Hq, Hkv, N, D, P, splits, n_nodes, plens):
     assert err < 1e-2
 
 
+def test_tree_attention_rising_scores():
+    """Scores that climb far above those of the first tile (by more than 64 in log2 units): blocks of
+    the 256-row kernel leave their fixed-reference pass and repeat with the running-maximum pass."""
+    say("attention bf16, scores rising by orders of magnitude along the prefix")
+    B, Hq, Hkv, N, D, P = 2, 8, 1, 40, 128, 320
+    rng = np.random.default_rng(11)
+    q, kp, vp, kt, vt = workloads.make_qkv(B, Hq, Hkv, N, D, P, "bf16", 11)
+    kp = kp.to(torch.float32)
+    kp[0, :, 128:] *= 40.0           # sequence 0: later keys score ~40x larger; sequence 1 stays ordinary
+    kp = kp.to(torch.bfloat16)
+    n_nodes = np.full(B, N, dtype=np.int32)
+    plens = np.full(B, P, dtype=np.int32)
+    parent = np.stack([_random_tree(rng, N) for _ in range(B)])
+    d = dev()
+    scale = workloads.attention_scale(D)
+    out, lse = binding.tree_attention(q.to(d), kp.to(d), vp.to(d), kt.to(d), vt.to(d),
+                                      torch.from_numpy(plens).to(d), torch.from_numpy(n_nodes).to(d),
+                                      torch.from_numpy(parent).to(d), scale, num_splits=1, return_lse=True)
+    f = lambda t: t.to(torch.float32).numpy()
+    ref, ref_lse = o_attn.tree_attention(f(q), f(kp), f(vp), f(kt), f(vt), plens, n_nodes, parent, scale)
+    span = (ref_lse[0].max() - ref_lse[1].max()) / np.log(2.0)
+    say(f"  lse gap between the sequences {span:.0f} (log2 units)")
+    assert span > 64
+    assert np.abs(to_np(out) - ref).max() < 1e-2
+    assert np.allclose(to_np(lse), ref_lse, rtol=2e-3, atol=2e-2)
+
+
 def test_tree_attention_strided_prefix_and_bad_arguments():
     say("attention strided prefix cache")
     d = dev()
