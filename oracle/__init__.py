@@ -13,6 +13,7 @@ gumbel_topk     Gumbel-Top-k sampling without replacement (RSD-C sampler)
 sbs             one Stochastic Beam Search step (RSD-S sampler)
 tree_attention  dense tree-masked attention in fp64
 rrs             recursive rejection sampling (single level and over a tree)
+filter_kv       FilterKVCache: the accepted path's rows appended to the cache
 
 Every function is pinned by tests/test_oracle_*.py to something other than
 itself (known-answer vectors, exact enumeration, closed forms, library
