@@ -263,6 +263,31 @@ def vocab_pass(case, torch, binding, steps=10):
     return dict(lse_ms=round(ms, 4), lse_GBps=gbs, lse_frac_hbm=gbs / HBM_PEAK_GBS)
 
 
+def filter_kv_pass(case, torch, binding, steps=20):
+    """FilterKVCache (the step after the verification) on the step's own accepted paths, into a small
+    cache of the same head layout: a latency-bound gather, timed on its own and not part of `value`."""
+    cfg = case["cfg"]
+    B, Hkv, D = cfg["B"], cfg["Hkv"], cfg["D"]
+    res = case["rrs"]()
+    kt, vt = case["kt"], case["vt"]
+    cap = 8 + res["accepted_nodes"].shape[1] + 1
+    kc = torch.zeros((B, Hkv, cap, D), dtype=kt.dtype, device=kt.device)
+    vc = torch.zeros_like(kc)
+    plen = torch.full((B,), 8, dtype=torch.int32, device=kt.device)
+    run = lambda: binding.filter_kv_cache(kc, vc, kt, vt, plen, res["accepted_nodes"], res["n_accepted"])
+    for _ in range(2):
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    rows = int(res["n_accepted"].sum().item()) + B
+    return dict(filter_kv_ms=round(e0.elapsed_time(e1) / steps, 4), filter_kv_rows=rows * Hkv)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -296,6 +321,7 @@ def main():
     t = time_case(case, args.steps, args.warmup, torch)
     rep, fig = report(case, t)
     vocab = vocab_pass(case, torch, binding)
+    vocab.update(filter_kv_pass(case, torch, binding))
 
     # roofline of the dominant kernel: the tree-attention launch
     bound = rep["attn_bound"]

@@ -220,6 +220,36 @@ int32_t rsd_recursive_reject(const float *draft_logits, const float *target_logi
                              uint32_t *flags, void *workspace, size_t workspace_bytes,
                              void *stream);
 
+/* ---------------------------------------------------------------------------
+ * FilterKVCache (Alg. 2 / Alg. 7, step 4): after the verification, append to the
+ * cache the key/value rows of the decoded tokens that the tree evaluation just
+ * produced: the root (tree node 0, the last known token) and then the accepted
+ * nodes in path order.  For sequence b and every KV head h:
+ *   cache[b, h, prefix_len[b] + j, :] = tree[b, h, node_j, :],  node_0 = 0,
+ *   node_j = accepted_nodes[b, j - 1]  (1 <= j <= n_accepted[b]),
+ *   prefix_len_out[b] = min(prefix_len[b] + 1 + n_accepted[b], capacity).
+ * Call once for the target cache and once for the draft cache.
+ * Inputs / in-out (all device pointers; the cache is modified in place)
+ *   k_cache, v_cache  element strides (cache_stride_b, cache_stride_h, cache_stride_p),
+ *                     D contiguous, `capacity` rows per (sequence, head)
+ *   k_tree, v_tree    [B, H_kv, N_max, D] contiguous; must not overlap the cache
+ *   prefix_len [B], accepted_nodes [B, depth_max] (-1 padded), n_accepted [B]
+ *   (the outputs of rsd_recursive_reject fit as they are)
+ * Outputs
+ *   prefix_len_out [B]  must not alias prefix_len
+ *   flags [B] or NULL   bit 0: rows beyond `capacity` were dropped
+ * Limits: dtype bf16 or f32; D * element size a multiple of 16; 16-byte aligned
+ *   pointers and strides; N_max, depth_max <= RSD_NODES_MAX.  Node ids outside
+ *   [0, N_max) are clamped on the device (no fault).  No workspace.
+ * ------------------------------------------------------------------------- */
+int32_t rsd_filter_kv_cache(void *k_cache, void *v_cache, const void *k_tree, const void *v_tree,
+                            int32_t dtype, int32_t B, int32_t H_kv, int32_t N_max, int32_t D,
+                            int32_t capacity, int64_t cache_stride_b, int64_t cache_stride_h,
+                            int64_t cache_stride_p, const int32_t *prefix_len,
+                            const int32_t *accepted_nodes, int32_t depth_max,
+                            const int32_t *n_accepted, int32_t *prefix_len_out, uint32_t *flags,
+                            void *stream);
+
 #ifdef __cplusplus
 }
 #endif

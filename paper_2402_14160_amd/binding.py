@@ -44,6 +44,8 @@ _SIGNATURES = {
     "rsd_recursive_reject": (_i32, [_vp, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _i32,
                                     _u64, _u32, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp,
                                     _vp, _sz, _vp]),
+    "rsd_filter_kv_cache": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i64, _i64, _i64,
+                                   _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
 }
 
 
@@ -233,3 +235,30 @@ def recursive_reject(draft_logits, target_logits, tokens, parent, n_nodes, inv_t
                                       _ptr(ws), ws.numel(), _stream()))
     return dict(accepted_nodes=acc, accepted_tokens=acc_tok, n_accepted=n_acc, last_token=last,
                 final_node=final_node, theta=theta, uniforms=uniforms, flags=flags)
+
+
+def filter_kv_cache(k_cache, v_cache, k_tree, v_tree, prefix_len, accepted_nodes, n_accepted):
+    """rsd_filter_kv_cache: appends the root's and the accepted nodes' rows of k_tree/v_tree
+    [B,Hkv,N,D] to k_cache/v_cache [B,Hkv,capacity,D] (any b/h/row strides) in place;
+    returns (new prefix_len [B], flags [B])."""
+    dtype = {torch.bfloat16: DTYPE_BF16, torch.float32: DTYPE_F32}[k_cache.dtype]
+    for t in (k_cache, v_cache):
+        if not t.is_cuda or t.dtype != k_cache.dtype or t.stride(3) != 1:
+            raise TypeError("cache tensors must be device tensors of one dtype with a contiguous last dim")
+    if v_cache.stride() != k_cache.stride():
+        raise ValueError("K and V cache need identical strides")
+    _dev(k_tree, k_cache.dtype)
+    _dev(v_tree, k_cache.dtype)
+    _dev(prefix_len, torch.int32)
+    _dev(accepted_nodes, torch.int32)
+    _dev(n_accepted, torch.int32)
+    B, H, cap, D = k_cache.shape
+    N = k_tree.shape[2]
+    L = accepted_nodes.shape[1]
+    new_len = torch.empty(B, dtype=torch.int32, device=k_cache.device)
+    flags = torch.empty(B, dtype=torch.int32, device=k_cache.device)
+    _check(lib().rsd_filter_kv_cache(_ptr(k_cache), _ptr(v_cache), _ptr(k_tree), _ptr(v_tree), dtype,
+                                     B, H, N, D, cap, k_cache.stride(0), k_cache.stride(1),
+                                     k_cache.stride(2), _ptr(prefix_len), _ptr(accepted_nodes), L,
+                                     _ptr(n_accepted), _ptr(new_len), _ptr(flags), _stream()))
+    return new_len, flags

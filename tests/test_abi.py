@@ -74,6 +74,13 @@ def test_argument_errors_are_returned_before_any_launch():
                                   fake, fake, fake, 1.0, 0, fake, null, null, 0, null) == -6  # head dim
     assert lib.rsd_tree_attention(fake, fake, fake, fake, fake, 0, 1, 2, 2, 300, 128, 64, 0, 0, 128,
                                   fake, fake, fake, 1.0, 0, fake, null, null, 0, null) == -2  # too many nodes
+    # filter_kv_cache: NULL cache, misaligned cache pointer, row size that is not a multiple of 16 bytes
+    assert lib.rsd_filter_kv_cache(null, null, null, null, 0, 1, 1, 4, 64, 8, 512, 512, 64, null, null, 2,
+                                   null, null, null, null) == -1
+    assert lib.rsd_filter_kv_cache(ctypes.c_void_p(4104), fake, fake, fake, 0, 1, 1, 4, 64, 8, 512, 512, 64,
+                                   fake, fake, 2, fake, fake, null, null) == -2
+    assert lib.rsd_filter_kv_cache(fake, fake, fake, fake, 0, 1, 1, 4, 60, 8, 480, 480, 60,
+                                   fake, fake, 2, fake, fake, null, null) == -2
     assert lib.rsd_recursive_reject(fake, fake, 1, 8, 62, 1.0, fake, fake, fake, null, 0, 0, 0,
                                     fake, null, 8, fake, fake, null, null, null, null, fake, 1 << 20,
                                     null) == -2

@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import filter_kv as o_filter
 from oracle import rrs as o_rrs
 from oracle import sbs as o_sbs
 from oracle import tree_attention as o_attn
@@ -269,6 +270,46 @@ def test_tree_attention_strided_prefix_and_bad_arguments():
         binding.tree_attention(q.to(d)[..., :96].contiguous(), None, None, kt.to(d)[..., :96].contiguous(),
                                vt.to(d)[..., :96].contiguous(), *args)
     assert e.value.code == -6
+
+
+# ------------------------------------------------------------------ FilterKVCache
+@pytest.mark.parametrize("dtype,B,H,N,D,cap,L", [
+    ("bf16", 3, 4, 12, 128, 40, 5),     # ordinary case, ragged prefix lengths and path lengths
+    ("bf16", 2, 2, 9, 64, 12, 6),       # cache nearly full: rows dropped, flag raised
+    ("f32", 2, 3, 7, 48, 32, 3),        # fp32 rows of 192 bytes
+    ("bf16", 64, 32, 64, 128, 96, 4),   # stress-configuration head count and tree size
+])
+def test_filter_kv_cache(dtype, B, H, N, D, cap, L):
+    say(f"filter_kv_cache {dtype} B={B} H={H} N={N} D={D} capacity={cap} depth={L}")
+    rng = np.random.default_rng(5)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    g = torch.Generator().manual_seed(5)
+    kc = torch.randn((B, H, cap + 8, D), generator=g).to(tdt)   # 8 spare rows: capacity < allocation
+    vc = torch.randn((B, H, cap + 8, D), generator=g).to(tdt)
+    kt = torch.randn((B, H, N, D), generator=g).to(tdt)
+    vt = torch.randn((B, H, N, D), generator=g).to(tdt)
+    plen = rng.integers(0, cap - 2, size=B).astype(np.int32)
+    plen[0] = cap - 3                                            # forces an overflow when the path is long
+    n_acc = rng.integers(0, L + 1, size=B).astype(np.int32)
+    n_acc[0] = L
+    acc = -np.ones((B, L), dtype=np.int32)
+    for b in range(B):
+        acc[b, :n_acc[b]] = np.sort(rng.choice(np.arange(1, N), size=n_acc[b], replace=False))
+    d = dev()
+    kc_d, vc_d = kc.to(d), vc.to(d)
+    new_len, flags = binding.filter_kv_cache(kc_d[:, :, :cap], vc_d[:, :, :cap], kt.to(d), vt.to(d),
+                                             torch.from_numpy(plen).to(d), torch.from_numpy(acc).to(d),
+                                             torch.from_numpy(n_acc).to(d))
+    f = lambda t: t.to(torch.float32).numpy()
+    k_ref, v_ref, len_ref, flag_ref = o_filter.filter_kv_cache(f(kc[:, :, :cap]), f(vc[:, :, :cap]), f(kt), f(vt),
+                                                               plen, acc, n_acc)
+    assert np.array_equal(to_np(new_len), len_ref)
+    assert np.array_equal(to_np(flags), flag_ref)
+    assert flag_ref[0] == (1 if plen[0] + 1 + L > cap else 0)
+    assert np.array_equal(f(kc_d.cpu())[:, :, :cap], k_ref)      # byte copies: exact
+    assert np.array_equal(f(vc_d.cpu())[:, :, :cap], v_ref)
+    assert torch.equal(kc_d.cpu()[:, :, cap:], kc[:, :, cap:])   # rows beyond the capacity untouched
+    assert torch.equal(vc_d.cpu()[:, :, cap:], vc[:, :, cap:])
 
 
 # ------------------------------------------------------- recursive rejection sampling
