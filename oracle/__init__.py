@@ -14,6 +14,7 @@ sbs             one Stochastic Beam Search step (RSD-S sampler)
 tree_attention  dense tree-masked attention in fp64
 rrs             recursive rejection sampling (single level and over a tree)
 filter_kv       FilterKVCache: the accepted path's rows appended to the cache
+prob_filter     top-k / nucleus (top-p) filtering of a logit row
 
 Every function is pinned by tests/test_oracle_*.py to something other than
 itself (known-answer vectors, exact enumeration, closed forms, library
