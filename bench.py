@@ -288,6 +288,27 @@ def filter_kv_pass(case, torch, binding, steps=20):
     return dict(filter_kv_ms=round(e0.elapsed_time(e1) / steps, 4), filter_kv_rows=rows * Hkv)
 
 
+def filter_logits_pass(case, torch, binding, steps=5):
+    """Nucleus filtering (top-p 0.95, the paper's instruction-following setting) of every target row:
+    a preprocessing pass of that setting, timed on its own and not part of `value`."""
+    zt = case["zt"]
+    B, N, V = zt.shape
+    rows = zt.view(B * N, V)
+    out = torch.empty_like(rows)
+    for _ in range(2):
+        binding.filter_logits(rows, top_p=0.95, out=out)
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        binding.filter_logits(rows, top_p=0.95, out=out)
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    del out
+    return dict(top_p_filter_ms=round(ms, 4), top_p_filter_GBps=rows.numel() * 8 / ms / 1e6)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -322,6 +343,7 @@ def main():
     rep, fig = report(case, t)
     vocab = vocab_pass(case, torch, binding)
     vocab.update(filter_kv_pass(case, torch, binding))
+    vocab.update(filter_logits_pass(case, torch, binding))
 
     # roofline of the dominant kernel: the tree-attention launch
     bound = rep["attn_bound"]

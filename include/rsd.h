@@ -250,6 +250,28 @@ int32_t rsd_filter_kv_cache(void *k_cache, void *v_cache, const void *k_tree, co
                             const int32_t *n_accepted, int32_t *prefix_len_out, uint32_t *flags,
                             void *stream);
 
+/* ---------------------------------------------------------------------------
+ * Top-k / nucleus (top-p) filtering of logit rows (Sec. 4, experiment setup:
+ * nucleus sampling with p = 0.95; the samplers of Alg. 4 and Alg. 9 drop
+ * candidates whose log-probability is -inf after such filtering).  Per row, with
+ * P = softmax(logits * inv_temperature) over the finite entries:
+ *   top_k > 0 : keep the top_k most probable entries;
+ *   top_p < 1 : keep the smallest set of most probable entries whose mass reaches
+ *               top_p (of the distribution renormalised over the top-k set when
+ *               both are given);
+ *   entries as probable as the least probable kept entry are kept too.
+ * Kept entries are copied unchanged (not scaled), all others become -inf, so the
+ * result feeds rsd_gumbel_topk / rsd_sbs_step / rsd_recursive_reject directly.
+ * Inputs   logits [R, V] fp32 device, row stride ld (multiple of 4, >= V), 16-byte aligned
+ * Outputs  out    [R, V] fp32 device, row stride out_ld (same rules); may be `logits` itself
+ *          kept   [R] number of kept entries, or NULL
+ * Limits: 1 <= V <= RSD_VOCAB_MAX; inv_temperature > 0; top_k >= 0 (0 = off);
+ *   top_p > 0 (>= 1 = off).  -inf / NaN entries are never kept.  No workspace.
+ * ------------------------------------------------------------------------- */
+int32_t rsd_filter_logits(const float *logits, int64_t ld, int32_t R, int32_t V,
+                          float inv_temperature, int32_t top_k, float top_p, float *out,
+                          int64_t out_ld, int32_t *kept, void *stream);
+
 #ifdef __cplusplus
 }
 #endif

@@ -44,6 +44,7 @@ _SIGNATURES = {
     "rsd_recursive_reject": (_i32, [_vp, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _i32,
                                     _u64, _u32, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp,
                                     _vp, _sz, _vp]),
+    "rsd_filter_logits": (_i32, [_vp, _i64, _i32, _i32, _f32, _i32, _f32, _vp, _i64, _vp, _vp]),
     "rsd_filter_kv_cache": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i64, _i64, _i64,
                                    _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
 }
@@ -262,3 +263,32 @@ def filter_kv_cache(k_cache, v_cache, k_tree, v_tree, prefix_len, accepted_nodes
                                      k_cache.stride(2), _ptr(prefix_len), _ptr(accepted_nodes), L,
                                      _ptr(n_accepted), _ptr(new_len), _ptr(flags), _stream()))
     return new_len, flags
+
+
+def filter_logits(logits, inv_temperature=1.0, top_k=0, top_p=1.0, out=None, return_kept=False):
+    """rsd_filter_logits on rows [R,V] (row-strided views allowed) or on contiguous [B,N,V]:
+    entries outside the top-k / nucleus set become -inf.  `out=logits` filters in place."""
+    def rows_of(t):
+        if not t.is_cuda or t.dtype != torch.float32:
+            raise TypeError("logits must be fp32 GPU tensors")
+        if t.dim() == 3:
+            if not t.is_contiguous():
+                raise ValueError("a 3-D logits tensor must be contiguous")
+            t = t.view(-1, t.shape[-1])
+        if t.dim() != 2 or t.stride(1) != 1:
+            raise ValueError("logits rows must be contiguous")
+        return t
+    rows = rows_of(logits)
+    R, V = rows.shape
+    if out is None:
+        ld = (V + 3) // 4 * 4
+        out = torch.empty((R, ld), dtype=torch.float32, device=logits.device)[:, :V]
+        out = out.view(logits.shape) if logits.dim() == 3 and ld == V else out
+    orows = rows_of(out)
+    if orows.shape != rows.shape:
+        raise ValueError("out must have the shape of logits")
+    stride = lambda t: t.stride(0) if R > 1 else max(V, t.stride(0))
+    kept = torch.empty(R, dtype=torch.int32, device=logits.device) if return_kept else None
+    _check(lib().rsd_filter_logits(_ptr(rows), stride(rows), R, V, inv_temperature, top_k, top_p,
+                                   _ptr(orows), stride(orows), _ptr(kept), _stream()))
+    return (out, kept) if return_kept else out

@@ -74,6 +74,10 @@ def test_argument_errors_are_returned_before_any_launch():
                                   fake, fake, fake, 1.0, 0, fake, null, null, 0, null) == -6  # head dim
     assert lib.rsd_tree_attention(fake, fake, fake, fake, fake, 0, 1, 2, 2, 300, 128, 64, 0, 0, 128,
                                   fake, fake, fake, 1.0, 0, fake, null, null, 0, null) == -2  # too many nodes
+    # filter_logits: NULL, misaligned row stride, top_p out of range
+    assert lib.rsd_filter_logits(null, 64, 1, 64, 1.0, 0, 0.9, null, 64, null, null) == -1
+    assert lib.rsd_filter_logits(fake, 66, 2, 64, 1.0, 0, 0.9, fake, 64, null, null) == -2
+    assert lib.rsd_filter_logits(fake, 64, 2, 64, 1.0, 0, 0.0, fake, 64, null, null) == -2
     # filter_kv_cache: NULL cache, misaligned cache pointer, row size that is not a multiple of 16 bytes
     assert lib.rsd_filter_kv_cache(null, null, null, null, 0, 1, 1, 4, 64, 8, 512, 512, 64, null, null, 2,
                                    null, null, null, null) == -1

@@ -4,6 +4,7 @@ import pytest
 import torch
 
 from oracle import filter_kv as o_filter
+from oracle import prob_filter as o_pfilter
 from oracle import rrs as o_rrs
 from oracle import sbs as o_sbs
 from oracle import tree_attention as o_attn
@@ -270,6 +271,107 @@ def test_tree_attention_strided_prefix_and_bad_arguments():
         binding.tree_attention(q.to(d)[..., :96].contiguous(), None, None, kt.to(d)[..., :96].contiguous(),
                                vt.to(d)[..., :96].contiguous(), *args)
     assert e.value.code == -6
+
+
+# ------------------------------------------------------------- probability filtering
+FILTER_TOL = 1e-6   # probability mass: fp32 exponentials and sums on the GPU against the fp64 oracle
+
+
+def _check_filtered(got, z, ref, margin, inv_t, top_k, top_p):
+    """Every row: the kept set is a top set, keeps the logits unchanged, and is a valid answer up to
+    FILTER_TOL of probability mass (reaches the target, and would fall short without its least probable
+    entry).  Rows that the oracle decided by a margin above FILTER_TOL must match it exactly."""
+    near = 0
+    for r in range(z.shape[0]):
+        kept = np.isfinite(got[r])
+        assert np.array_equal(got[r][kept], z[r][kept])
+        if margin[r] >= FILTER_TOL:
+            assert np.array_equal(got[r], ref[r]), r
+            continue
+        near += 1
+        fin = np.isfinite(z[r])
+        assert kept.any() and not (kept & ~fin).any()
+        assert z[r][kept].min() >= z[r][fin & ~kept].max(initial=-np.inf)         # a top set
+        x = z[r].astype(np.float64) * np.float64(np.float32(inv_t))
+        prob = np.where(fin, np.exp(x - x[fin].max()), 0.0)
+        if top_k:                                                               # top-k acts first
+            kth = np.sort(prob)[::-1][min(top_k, int(fin.sum())) - 1]
+            in_k = prob >= kth * (1 - 1e-6)
+            assert not (kept & ~in_k).any()
+            prob = np.where(in_k, prob, 0.0)
+        prob /= prob.sum()
+        if top_p < 1.0:
+            mass = prob[kept].sum()
+            assert mass >= top_p - FILTER_TOL and mass - prob[kept].min() < top_p + FILTER_TOL
+    return near
+
+
+@pytest.mark.parametrize("kind,R,V,inv_t,top_k,top_p", [
+    ("zipf", 6, 32000, 1.0, 0, 0.95),        # the instruction-following setting: nucleus 0.95 at T = 1
+    ("zipf", 4, 50272, 1.0, 0, 0.95),
+    ("zipf", 5, 32000, 1.0 / 0.3, 0, 0.9),   # sharper rows
+    ("normal", 7, 1001, 1.0, 50, 1.0),       # top-k only, ragged tail
+    ("normal", 5, 1003, 1.0, 40, 0.8),       # both filters
+    ("normal", 3, 64, 1.0, 0, 0.5),
+    ("zipf", 2, 65536, 1.0, 1000, 0.99),     # largest row
+])
+def test_filter_logits(kind, R, V, inv_t, top_k, top_p):
+    say(f"filter_logits {kind} R={R} V={V} 1/T={inv_t:.2f} top_k={top_k} top_p={top_p}")
+    zt, _ = workloads.make_logits(kind, 1, R, V, seed=4)
+    z = zt[0].clone()
+    z[0, 5:40] = -float("inf")                                    # already-filtered entries stay out
+    ld = (V + 3) // 4 * 4
+    buf = torch.zeros((R, ld), dtype=torch.float32)
+    buf[:, :V] = z
+    d_in = buf.to(dev())[:, :V]
+    out, kept = binding.filter_logits(d_in, inv_t, top_k, top_p, return_kept=True)
+    ref, kept_ref, margin = o_pfilter.filter_logits(z.numpy(), inv_t, top_k, top_p)
+    near = _check_filtered(to_np(out), z.numpy(), ref, margin, inv_t, top_k, top_p)
+    say(f"  kept per row {kept_ref.tolist()}, rows decided within {FILTER_TOL} of mass: {near}")
+    assert np.array_equal(to_np(kept), np.isfinite(to_np(out)).sum(1))
+    ok = margin >= FILTER_TOL
+    assert np.array_equal(to_np(kept)[ok], kept_ref[ok])
+    assert np.abs(to_np(kept) - kept_ref).max() <= 2
+    # in place
+    binding.filter_logits(d_in, inv_t, top_k, top_p, out=d_in)
+    assert torch.equal(d_in, out)
+
+
+def test_filtered_logits_through_drafting_and_verification():
+    """Nucleus-filtered draft and target logits (p = 0.95, T = 1) through tree drafting and recursive
+    rejection sampling: the samplers and the verifier take the -inf entries as they are."""
+    say("top-p 0.95 on both models, then draft tree + RRS")
+    B, V, counts_shape, n_cap = 3, 32000, (3, 2, 2), 22
+    zt, zd = workloads.make_logits("zipf", B, n_cap, V, seed=9)
+    ft, _, mt = o_pfilter.filter_logits(zt.reshape(-1, V).numpy(), 1.0, 0, 0.95)
+    fd, _, md = o_pfilter.filter_logits(zd.reshape(-1, V).numpy(), 1.0, 0, 0.95)
+    d = dev()
+    # the GPU filter on the same rows (its own parity is the test above); drafting and verification
+    # below take the oracle-filtered rows on both sides, so that one tail entry decided within
+    # FILTER_TOL cannot make the two sides work on different distributions
+    got_t = to_np(binding.filter_logits(zt.to(d), top_p=0.95)).reshape(-1, V)
+    _check_filtered(got_t, zt.reshape(-1, V).numpy(), ft, mt, 1.0, 0, 0.95)
+    gt = torch.from_numpy(ft).reshape(B, n_cap, V).to(d)
+    gd = torch.from_numpy(fd).reshape(B, n_cap, V).to(d)
+    counts = [workloads.full_tree_child_counts(counts_shape)] * B
+    tree = draft_tree.create_draft_tree_const(gd, counts, seed=9, step=1)
+    for b in range(B):                                             # the tree itself, against the oracle's
+        rt = oracle_tree_const(fd.reshape(B, n_cap, V)[b], counts[b], b, 9, 1)
+        assert np.array_equal(to_np(tree["tokens"])[b, :n_cap], rt["tokens"])
+        assert np.array_equal(to_np(tree["parent"])[b, :n_cap], rt["parent"])
+    g = binding.recursive_reject(gd, gt, tree["tokens"], tree["parent"], tree["n_nodes"],
+                                 mode=binding.MODE_ALL_GROUPS, seed=9, step=1)
+    ref = o_rrs.recursive_reject(ft.reshape(B, n_cap, V), fd.reshape(B, n_cap, V), to_np(tree["tokens"]),
+                                 to_np(tree["parent"]), to_np(tree["n_nodes"]), mode=o_rrs.MODE_ALL_GROUPS,
+                                 seed=9, step=1)
+    for b in range(B):
+        if ref["near_tie"][b] or ref["last_gap"][b] < NEAR_TIE:
+            continue
+        k = int(ref["n_accepted"][b])
+        assert int(g["n_accepted"][b]) == k
+        assert np.array_equal(to_np(g["accepted_nodes"])[b, :k], ref["accepted_nodes"][b, :k])
+        assert int(g["last_token"][b]) == int(ref["last_token"][b])
+        assert np.isfinite(ft.reshape(B, n_cap, V)[b, int(ref["final_node"][b]), int(ref["last_token"][b])])
 
 
 # ------------------------------------------------------------------ FilterKVCache
