@@ -487,3 +487,59 @@ def test_recursive_reject_identical_models_and_single_node():
     assert to_np(g["n_accepted"]).tolist() == [4, 0] == ref["n_accepted"].tolist()
     assert to_np(g["last_token"]).tolist() == ref["last_token"].tolist()
     assert to_np(g["final_node"]).tolist() == [4, 0]
+
+
+# ------------------------------------------------------------------ limits, degenerate inputs
+@pytest.mark.parametrize("mode", [binding.MODE_PATH, binding.MODE_ALL_GROUPS])
+def test_recursive_reject_at_the_limits(mode):
+    """Sixteen siblings under one parent (the largest group), and a 256-node chain (the largest tree,
+    255 levels deep)."""
+    say(f"rrs limits mode={mode}")
+    near, ref = _rrs_case("zipf", 2, 32000, [workloads.full_tree_child_counts((16,))] * 2, 17, 21, 1.0, mode)
+    assert near <= 1
+    d = dev()
+    B, N, V = 2, 256, 64
+    zt, zd = workloads.make_logits("normal", B, N, V, seed=22)
+    rng = np.random.default_rng(22)
+    tokens = torch.from_numpy(rng.integers(0, V, size=(B, N)).astype(np.int32))
+    parent = torch.arange(-1, N - 1, dtype=torch.int32)[None].repeat(B, 1)
+    n_nodes = torch.tensor([N, 100], dtype=torch.int32)
+    # a target close to the draft, so that the walk goes deep into the chain
+    zt = zd + 0.05 * (zt - zd)
+    g = binding.recursive_reject(zd.to(d), zt.to(d), tokens.to(d), parent.to(d), n_nodes.to(d), mode=mode, seed=3)
+    ref = o_rrs.recursive_reject(zt.numpy(), zd.numpy(), tokens.numpy(), parent.numpy(), n_nodes.numpy(),
+                                 mode=mode, seed=3)
+    say(f"  chain: accepted {ref['n_accepted'].tolist()}")
+    for b in range(B):
+        if ref["near_tie"][b] or ref["last_gap"][b] < NEAR_TIE:
+            continue
+        k = int(ref["n_accepted"][b])
+        assert int(g["n_accepted"][b]) == k
+        assert np.array_equal(to_np(g["accepted_nodes"])[b, :k], ref["accepted_nodes"][b, :k])
+        assert int(g["last_token"][b]) == int(ref["last_token"][b])
+    assert max(ref["n_accepted"]) >= 8
+
+
+def test_tree_attention_largest_tree():
+    say("attention bf16 with 256 nodes (four ancestor words, four tree tiles)")
+    err = _attention_case(1, 2, 1, 256, 128, 70, "bf16", 5, n_nodes=[256], plens=[70])
+    say(f"  max abs err {err:.2e}")
+    assert err < 1e-2
+    err = _attention_case(2, 2, 2, 256, 64, 0, "bf16", 6, n_nodes=[256, 200], plens=[0, 0])
+    assert err < 1e-2
+
+
+def test_non_finite_logits_are_flagged_not_fatal():
+    say("rrs with a NaN in a target row")
+    d = dev()
+    zt, zd = workloads.make_logits("normal", 2, 7, 64, seed=23)
+    counts = [workloads.full_tree_child_counts((2, 2))] * 2
+    tree = draft_tree.create_draft_tree_const(zd.to(d), counts, seed=23, step=0)
+    zt[1, 0, 5] = float("nan")
+    for mode in (binding.MODE_PATH, binding.MODE_ALL_GROUPS):
+        g = binding.recursive_reject(zd.to(d), zt.to(d), tree["tokens"], tree["parent"], tree["n_nodes"],
+                                     mode=mode, seed=23)
+        torch.cuda.synchronize()
+        flags = to_np(g["flags"])
+        assert flags[0] == 0 and flags[1] & binding.FLAG_NONFINITE
+        assert 0 <= int(g["n_accepted"][1]) <= 2 and -1 <= int(g["last_token"][1]) < 64
