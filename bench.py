@@ -28,6 +28,13 @@ MEASURED_TRAFFIC_BYTES = {"cfg4_stress": 8.758e9}
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
+# plain vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (half the
+# published 157.3 TFLOP/s fp32 vector figure counts an FMA as two flops and packs two per lane)
+VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
+# vector instructions the tokens-only Gumbel-Top-k kernel issues per vocabulary entry (rocprofv3
+# SQ_INSTS_VALU x 64 lanes / entries on the stress configuration); a fifth of them are quarter-rate
+# 64-bit multiplies of the Philox rounds and hardware logs, so the pipeline is busier than this fraction
+GUMBEL_VALU_PER_ENTRY = 27.3
 N_LAYERS = {"cfg1_llama2_7b": 32, "cfg2_opt_13b_sbs": 40, "cfg3_llama2_70b_gqa": 80, "cfg4_stress": 32}
 
 
@@ -126,8 +133,12 @@ def algorithmic_figures(case):
     # every sibling group reads its draft row and its target row once; the last token reads
     # one more row pair per sequence
     rrs_bytes = (groups + B) * 2 * V * 4
+    # the residual step as the method states it: one pass over a target row and a draft row per
+    # verified sibling (all of them in ALL_GROUPS mode) plus one per last token
+    rrs_bytes_per_sibling = (sum(n - 1 for n in n_nodes) + B) * 2 * V * 4
     draft_bytes = case["draft_rows"] * V * 4
     return dict(attn_bytes=attn_bytes, attn_flops=attn_flops, rrs_bytes=rrs_bytes,
+                rrs_bytes_per_sibling=rrs_bytes_per_sibling,
                 draft_bytes=draft_bytes, nodes=sum(n_nodes), groups=groups)
 
 
@@ -168,6 +179,9 @@ def report(case, t):
         attn_frac_mfma=fig["attn_flops"] / attn_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         attn_bound="mfma" if intensity > ridge else "hbm",
         rrs_GBps=fig["rrs_bytes"] / rrs_s / 1e9, rrs_frac_hbm=fig["rrs_bytes"] / rrs_s / 1e9 / HBM_PEAK_GBS,
+        rrs_per_sibling_GBps=fig["rrs_bytes_per_sibling"] / rrs_s / 1e9,
+        draft_alu_frac=(fig["draft_bytes"] / 4 * GUMBEL_VALU_PER_ENTRY / draft_s / VALU_PEAK_LANE_OPS
+                        if draft_s > 0 and cfg["sampler"] == "gumbel" else None),
         draft_GBps=fig["draft_bytes"] / draft_s / 1e9 if draft_s > 0 else None,
         draft_frac_hbm=fig["draft_bytes"] / draft_s / 1e9 / HBM_PEAK_GBS if draft_s > 0 else None,
         model_equiv_nodes_per_s=(fig["nodes"] / (N_LAYERS[cfg["name"]] * attn_s + rrs_s)
@@ -387,7 +401,8 @@ def main():
         value_attn_rrs_only=rep["nodes_per_s_attn_rrs"],
         phases=dict(draft_ms=rep["draft_ms"], attn_ms=rep["attn_ms"], rrs_ms=rep["rrs_ms"],
                     attn_GBps=rep["attn_GBps"], attn_TFLOPs=rep["attn_TFLOPs"],
-                    rrs_GBps=rep["rrs_GBps"], draft_GBps=rep["draft_GBps"],
+                    rrs_GBps=rep["rrs_GBps"], rrs_per_sibling_GBps=rep["rrs_per_sibling_GBps"],
+                    draft_GBps=rep["draft_GBps"], draft_alu_frac=rep["draft_alu_frac"],
                     model_equiv_nodes_per_s=rep["model_equiv_nodes_per_s"], **vocab),
         roofline=roof, cpu_baseline=cpu, per_config=per_config,
     )
