@@ -277,6 +277,25 @@ def vocab_pass(case, torch, binding, steps=10):
     return dict(lse_ms=round(ms, 4), lse_GBps=gbs, lse_frac_hbm=gbs / HBM_PEAK_GBS)
 
 
+def rrs_path_pass(case, torch, binding, steps=20):
+    """The same verification in path mode (only the sibling groups along the accepted path, as the
+    paper's level-by-level loop does): identical decisions, less work; reported beside the timed
+    all-groups call."""
+    tree = case["tree"]
+    run = lambda: binding.recursive_reject(case["zd"], case["zt"], tree["tokens"], tree["parent"], tree["n_nodes"],
+                                           mode=binding.MODE_PATH, seed=0, step=0, diagnostics=False)
+    for _ in range(2):
+        run()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    return dict(rrs_path_mode_ms=round(e0.elapsed_time(e1) / steps, 4))
+
+
 def filter_kv_pass(case, torch, binding, steps=20):
     """FilterKVCache (the step after the verification) on the step's own accepted paths, into a small
     cache of the same head layout: a latency-bound gather, timed on its own and not part of `value`."""
@@ -360,6 +379,7 @@ def main():
     t = time_case(case, args.steps, args.warmup, torch)
     rep, fig = report(case, t)
     vocab = vocab_pass(case, torch, binding)
+    vocab.update(rrs_path_pass(case, torch, binding))
     vocab.update(filter_kv_pass(case, torch, binding))
     vocab.update(filter_logits_pass(case, torch, binding))
 
