@@ -70,3 +70,42 @@ def test_first_emitted_token_follows_the_target_distribution(mode):
     assert pval > 1e-4
     assert np.all(np.abs(obs - q * B) <= 5 * np.sqrt(q * B) + 1)
     assert 0.2 < np.mean(n_acc > 0) < 0.999            # both branches of the verification are exercised
+
+
+def test_two_sbs_levels_sample_sequences_without_replacement():
+    """Theorem 3.2 on the GPU path: with a tabulated toy model (the next-token logits depend on the
+    previous token only) two Stochastic Beam Search levels of width 2 return, in order, two length-2
+    sequences drawn without replacement from the model's sequence distribution."""
+    V, W, B = 4, 2, 40000
+    say(f"law of the two sequences kept by {B} two-level beam searches, vocabulary {V}")
+    rng = np.random.default_rng(2)
+    root = rng.normal(0, 1.2, size=V).astype(np.float32)
+    nxt = rng.normal(0, 1.2, size=(V, V)).astype(np.float32)
+    p_root = special.softmax(root.astype(np.float64))
+    p_next = special.softmax(nxt.astype(np.float64), axis=1)
+    seqs = list(itertools.product(range(V), range(V)))
+    p_seq = {s: p_root[s[0]] * p_next[s[0], s[1]] for s in seqs}
+    keys = list(itertools.permutations(seqs, 2))
+    exp = np.array([p_seq[a] * p_seq[b] / (1 - p_seq[a]) for a, b in keys]) * B
+    d = dev()
+    zeros = torch.zeros((B, 1), dtype=torch.float32, device=d)
+    l0 = binding.sbs_step(torch.from_numpy(root).to(d).expand(B, 1, V).contiguous(), zeros, zeros,
+                          torch.ones(B, dtype=torch.int32, device=d), W, seed=9, step=0)
+    t0 = l0["tokens"].long()                                            # [B, W] first tokens of the beams
+    z1 = torch.from_numpy(nxt).to(d)[t0]                                 # [B, W, V]: rows of the table
+    node = torch.tensor([[1, 2]], dtype=torch.int32, device=d).expand(B, W).contiguous()
+    l1 = binding.sbs_step(z1.contiguous(), l0["sum_logprob"], l0["trunc_gumbel"],
+                          torch.full((B,), W, dtype=torch.int32, device=d), W, node_id=node, seed=9, step=0)
+    first = torch.gather(t0, 1, l1["parent"].long())
+    out = torch.stack([first, l1["tokens"].long()], dim=2).cpu().numpy()  # [B, W, 2]
+    index = {key: i for i, key in enumerate(keys)}
+    obs = np.zeros(len(keys))
+    for pair in out:
+        obs[index[((int(pair[0, 0]), int(pair[0, 1])), (int(pair[1, 0]), int(pair[1, 1])))]] += 1
+    pval = _chi2_ok(obs, exp)
+    say(f"  chi-square p-value {pval:.3f}")
+    assert pval > 1e-4
+    # the carried sum of log-probabilities is the log-probability of the kept sequence
+    s_out = to_np(l1["sum_logprob"])
+    want = np.log(np.array([[p_seq[(int(p[0, 0]), int(p[0, 1]))], p_seq[(int(p[1, 0]), int(p[1, 1]))]] for p in out[:200]]))
+    assert np.allclose(s_out[:200], want, rtol=0, atol=1e-5)
