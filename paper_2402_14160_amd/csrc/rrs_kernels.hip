@@ -24,7 +24,7 @@ constexpr int kGroupThreads = 512;   // streaming variant (any vocabulary size)
 constexpr int kRegThreads = 512;     // register-resident variant: 2 waves per SIMD, 256 VGPRs each
 constexpr int kGroupWaves = kRegThreads / kWave;
 constexpr int kFinalThreads = 512;
-constexpr int kFinalSplits = 8;
+constexpr int kFinalSplitsMax = 8;
 
 // Per (sequence, node) record produced by the group pass, kept in workspace.
 struct GroupRec {
@@ -713,7 +713,8 @@ __global__ __launch_bounds__(kWave) void rrs_walk_kernel(RrsArgs a) {
     a.fdone[b] = 0;
 }
 
-// ALL_GROUPS, kernel 3: last token; the vocabulary is split over kFinalSplits workgroups.
+// ALL_GROUPS, kernel 3: last token; the vocabulary is split over gridDim.x workgroups (more of them
+// for small batches; one per sequence, with no atomics at all, once the batch fills the chip).
 __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
     __shared__ GroupRec g;
     __shared__ float s_v[kFinalThreads / kWave];
@@ -732,24 +733,32 @@ __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
     }
     __syncthreads();
     const int nchunk = a.V >> 2;
-    const int per = (nchunk + kFinalSplits - 1) / kFinalSplits;
+    const int nsplit = gridDim.x;
+    const int per = (nchunk + nsplit - 1) / nsplit;
     const int c_lo = min(split * per, nchunk), c_hi = min(c_lo + per, nchunk);
     float bv, av;
     int bi, ai;
     final_sample_range<kFinalThreads>(a, b, node, g, c_lo, c_hi, bv, bi, av, ai);
     block_argmax<kFinalThreads>(bv, bi, s_v, s_i);
     block_argmax<kFinalThreads>(av, ai, s_v, s_i);
-    if (threadIdx.x == 0) {
-        if (bi != INT_MAX) atomicMax(&a.fkey[2 * b], pack_key(bv, bi));
-        if (ai != INT_MAX) atomicMax(&a.fkey[2 * b + 1], pack_key(av, ai));
-        __threadfence();
-        s_last = (atomicAdd(&a.fdone[b], 1) == kFinalSplits - 1);
+    if (nsplit > 1) {
+        if (threadIdx.x == 0) {
+            if (bi != INT_MAX) atomicMax(&a.fkey[2 * b], pack_key(bv, bi));
+            if (ai != INT_MAX) atomicMax(&a.fkey[2 * b + 1], pack_key(av, ai));
+            __threadfence();
+            s_last = (atomicAdd(&a.fdone[b], 1) == nsplit - 1);
+        }
+        __syncthreads();
+        if (!s_last) return;
     }
-    __syncthreads();
-    if (s_last && threadIdx.x == 0) {
-        __threadfence();
-        const unsigned long long k0 = atomicMax(&a.fkey[2 * b], 0ull);
-        const unsigned long long k1 = atomicMax(&a.fkey[2 * b + 1], 0ull);
+    if (threadIdx.x == 0) {
+        unsigned long long k0 = (bi != INT_MAX) ? pack_key(bv, bi) : 0ull;
+        unsigned long long k1 = (ai != INT_MAX) ? pack_key(av, ai) : 0ull;
+        if (nsplit > 1) {
+            __threadfence();
+            k0 = atomicMax(&a.fkey[2 * b], 0ull);
+            k1 = atomicMax(&a.fkey[2 * b + 1], 0ull);
+        }
         uint32_t flags = a.fflags[b];
         const unsigned long long ninf = pack_key(-INFINITY, 0) >> 32;
         unsigned long long use = k0;
@@ -929,7 +938,10 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
         else
             hipLaunchKernelGGL((rrs_group_kernel<kGroupThreads, 0>), dim3(2 * grid), dim3(kGroupThreads), 0, st, a);
         hipLaunchKernelGGL(rrs_walk_kernel, dim3(B), dim3(kWave), 0, st, a);
-        hipLaunchKernelGGL(rrs_final_kernel, dim3(kFinalSplits, B), dim3(kFinalThreads), 0, st, a);
+        // enough workgroups to fill the chip, but no more: every split costs two device-wide fences
+        int fsplits = 256 / (B > 0 ? B : 1);
+        fsplits = fsplits < 1 ? 1 : (fsplits > kFinalSplitsMax ? kFinalSplitsMax : fsplits);
+        hipLaunchKernelGGL(rrs_final_kernel, dim3(fsplits, B), dim3(kFinalThreads), 0, st, a);
     }
     return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
 }
