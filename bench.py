@@ -163,6 +163,26 @@ def time_case(case, steps, warmup, torch):
     return dict(ms_per_step=wall * 1000.0 / steps, draft_ms=phase[0], attn_ms=phase[1], rrs_ms=phase[2])
 
 
+def graph_step_ms(case, torch, steps=20):
+    """The same step captured once into a HIP graph and replayed: what the GPU needs for it without the
+    host's per-call launch work (the difference matters for the small, latency-bound configurations)."""
+    torch.cuda.synchronize()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph):
+        case["draft"](); case["attn"](); case["rrs"]()
+    for _ in range(2):
+        graph.replay()
+    torch.cuda.synchronize()
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    e0.record()
+    for _ in range(steps):
+        graph.replay()
+    e1.record()
+    torch.cuda.synchronize()
+    del graph
+    return e0.elapsed_time(e1) / steps
+
+
 def report(case, t):
     fig = algorithmic_figures(case)
     cfg = case["cfg"]
@@ -379,6 +399,7 @@ def main():
     t = time_case(case, args.steps, args.warmup, torch)
     rep, fig = report(case, t)
     vocab = vocab_pass(case, torch, binding)
+    vocab["graph_ms_per_step"] = round(graph_step_ms(case, torch), 4)
     vocab.update(rrs_path_pass(case, torch, binding))
     vocab.update(filter_kv_pass(case, torch, binding))
     vocab.update(filter_logits_pass(case, torch, binding))
@@ -404,6 +425,7 @@ def main():
             case = build_case(dict(other), args.seed, torch, binding, draft_tree, workloads)
             tt = time_case(case, max(5, args.steps), args.warmup, torch)
             per_config[other["name"]], _ = report(case, tt)
+            per_config[other["name"]]["graph_ms_per_step"] = round(graph_step_ms(case, torch), 4)
         del case
         torch.cuda.empty_cache()
         case = build_case(cfg, args.seed, torch, binding, draft_tree, workloads)
