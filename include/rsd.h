@@ -156,7 +156,8 @@ int32_t rsd_sbs_step(const float *logits, const float *sum_logprob, const float 
  *   k_tree, v_tree     [B, H_kv, N_max, D] contiguous
  *   prefix_len [B], n_nodes [B] (0 <= n_nodes[b] <= N_max), parent [B, N_max]
  *   P_max              upper bound of prefix_len (used to size the launch)
- *   num_splits         key-range splits per (sequence, head); 0 = choose automatically
+ *   num_splits         key-range splits per (sequence, head); 0 = choose automatically,
+ *                      values above 32 are taken as 32
  * Outputs
  *   out     [B, H_q, N_max, D] fp32; rows i >= n_nodes[b] are not written
  *   lse_out [B, H_q, N_max] natural-log softmax normaliser, or NULL

@@ -661,21 +661,20 @@ __global__ __launch_bounds__(kWave) void tree_attn_merge_kernel(AttnArgs a) {
     const int G = a.Hq / a.Hkv;
     if (R >= G * n) return;
     const int hq = kvh * G + R / n, i = R % n;
-    const int splits = a.splits;
+    const int splits = a.splits;  // at most 32: lane s holds split s
     const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + i;
     const int lane = threadIdx.x;
-    const float *wm = a.ws_m + orow * a.ws_splits, *wl = a.ws_l + orow * a.ws_splits;
-    float m = -INFINITY;
-    for (int s = 0; s < splits; ++s) m = fmaxf(m, wm[s]);
-    float lsum = 0.f;
-    for (int s = 0; s < splits; ++s) lsum += (wm[s] == -INFINITY) ? 0.f : exp2f(wm[s] - m) * wl[s];
+    const float wm = lane < splits ? a.ws_m[orow * a.ws_splits + lane] : -INFINITY;
+    const float wl = lane < splits ? a.ws_l[orow * a.ws_splits + lane] : 0.f;
+    const float m = wave_max(wm);
+    const float w = (wm == -INFINITY) ? 0.f : exp2f(wm - m);  // weight of this lane's split
+    const float lsum = wave_sum(w * wl);
     const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
+    const float *po = a.ws_o + orow * a.ws_splits * a.D;
     for (int d = lane; d < a.D; d += kWave) {
         float acc = 0.f;
-        for (int s = 0; s < splits; ++s) {
-            const float w = (wm[s] == -INFINITY) ? 0.f : exp2f(wm[s] - m);
-            acc += w * a.ws_o[(orow * a.ws_splits + s) * a.D + d];
-        }
+#pragma unroll 4
+        for (int s = 0; s < splits; ++s) acc += __shfl(w, s, kWave) * po[(int64_t)s * a.D + d];
         a.out[orow * a.D + d] = acc * inv;
     }
     if (a.lse_out && lane == 0) a.lse_out[orow] = (m + log2f(lsum)) * kLn2;
@@ -778,6 +777,7 @@ static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 
 // ---------------------------------------------------------------------------
 enum AttnVariant { kV16 = 0, kV32x4 = 1 };
 constexpr int kMaxSegments = 2;
+constexpr int kMaxSplits = 32;
 
 struct AttnSegment {
     int variant, row_base, row_blocks, splits;
@@ -801,8 +801,10 @@ static int plan_segments(int dtype, int B, int Hq, int Hkv, int N, int P_max, in
         if (s <= 0) {  // fill the chip in one round: two workgroups per CU
             const long blocks = (long)seg[i].row_blocks * Hkv * B;
             s = (int)(512 / (blocks > 0 ? blocks : 1));
-            if (s > 32) s = 32;
+            // a split of fewer than four tiles costs more in set-up and merging than it gains
+            if (s > tiles / 4) s = tiles / 4;
         }
+        if (s > kMaxSplits) s = kMaxSplits;  // the merge holds one split per lane
         if (s > tiles) s = tiles;
         if (s < 1) s = 1;
         seg[i].splits = s;
