@@ -67,6 +67,26 @@ def test_two_symbol_toy_second_draft_is_always_accepted():
                     assert theta[1] == 1.0
 
 
+def test_toy_example_acceptance_rate_matches_the_paper():
+    """tests/golden/toy_bernoulli_acceptance.txt holds what the paper's toy example states; the rate is
+    computed here by exact enumeration over both orders in which the two tokens can be drafted."""
+    import os
+    path = os.path.join(os.path.dirname(__file__), "golden", "toy_bernoulli_acceptance.txt")
+    rows = [l.split() for l in open(path) if l.strip() and not l.startswith("#")]
+    assert rows == [["recursive_rejection_sampling", "2", "1.0"]]
+    K, want = int(rows[0][1]), float(rows[0][2])
+    for a in np.linspace(0.03, 0.97, 17):
+        for b in np.linspace(0.03, 0.97, 17):
+            q, p = np.array([a, 1 - a]), np.array([b, 1 - b])
+            rate = 0.0
+            for first in (0, 1):
+                order = [first, 1 - first][:K]
+                theta, _, _ = sibling_chain(q, p, order)
+                draw = p[first]                       # the second token is then certain (without replacement)
+                rate += draw * (theta[0] + (1 - theta[0]) * theta[1])
+            assert abs(rate - want) < 1e-12
+
+
 def test_second_stage_uses_without_replacement_conditional():
     # after rejecting x1 the draft conditional is p with x1 removed and renormalised,
     # and the threshold of x2 is q2(x2)/p2(x2) with q2 = Norm[(q-p)^+]
