@@ -74,6 +74,12 @@ struct TopkArgs {
     float *logprob;    // [R, k_max] or null
     float *lse;        // [R] or null
     int *count;        // [R] or null
+    // Row segments (SBS on few rows): nseg > 1 workgroups share a row, each takes a contiguous
+    // range of chunks and writes its own candidate list at index row * nseg + seg of tokens /
+    // perturbed / logprob / count -- scores and logits NOT yet reduced by the row normaliser,
+    // whose per-segment (max, sum) pair goes to seg_ms; `lse` is then left to the consumer.
+    int nseg;
+    MaxSum *seg_ms;    // [R * nseg] when nseg > 1
 };
 
 constexpr int kTopkThreads = 1024;
@@ -94,7 +100,9 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
     __shared__ int s_outi[RSD_K_MAX];
     __shared__ int s_nout;
 
-    const int row = blockIdx.x;
+    const int nseg = a.nseg;
+    const int row = blockIdx.x / nseg;
+    const int seg = blockIdx.x - row * nseg;
     const int tid = threadIdx.x;
     const int lane = tid & (kWave - 1);
     const int wave = tid / kWave;
@@ -117,24 +125,28 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
     const int V = a.V;
     const int nfull = dead ? 0 : (V >> 2);  // chunks of four entries that lie fully inside the row
     const float inv_t = a.inv_t;
+    // this workgroup's chunk range [c0, c1) of the row; the ragged tail goes with the last segment
+    const int per = (nfull + nseg - 1) / nseg;
+    const int c0 = min(seg * per, nfull), c1 = min(c0 + per, nfull);
+    const bool has_tail = seg == nseg - 1;
 
-    // Entry (j, e) of this thread is vocabulary index 4 * (j * 1024 + tid) + e; one extra slot
+    // Entry (j, e) of this thread is vocabulary index 4 * (c0 + j * 1024 + tid) + e; one extra slot
     // holds the up to three entries of a ragged tail (threads 0..2).
     float val[CH * 4 + 1];
     MaxSum acc{-INFINITY, 0.f};
     // all loads first (the row streams in while the first Philox blocks are computed) ...
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-        const int c = j * kTopkThreads + tid;
+        const int c = c0 + j * kTopkThreads + tid;
         float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-        if (c < nfull) t = z4[c];
+        if (c < c1) t = z4[c];
         val[j * 4 + 0] = t.x; val[j * 4 + 1] = t.y; val[j * 4 + 2] = t.z; val[j * 4 + 3] = t.w;
     }
     // ... then one chunk at a time, so that only one Philox block is live
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-        const int c = j * kTopkThreads + tid;
-        if (c < nfull) {
+        const int c = c0 + j * kTopkThreads + tid;
+        if (c < c1) {
             const uint4 r = philox4x32_10((uint32_t)c, node, seq, c3, key);
             const float s0 = val[j * 4 + 0] * inv_t, s1 = val[j * 4 + 1] * inv_t;
             const float s2 = val[j * 4 + 2] * inv_t, s3 = val[j * 4 + 3] * inv_t;
@@ -160,7 +172,7 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
     {
         float vt = -INFINITY;
         const int x = (nfull << 2) + tid;
-        if (!dead && tid < (V & 3)) {
+        if (!dead && has_tail && tid < (V & 3)) {
             const uint4 r = philox4x32_10((uint32_t)nfull, node, seq, c3, key);
             const uint32_t wd = tid == 0 ? r.x : (tid == 1 ? r.y : r.z);
             const float s = zrow[x] * inv_t;
@@ -177,7 +189,7 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
         val[CH * 4] = vt;
     }
     // vocabulary index of register slot i
-    auto slot_index = [&](int i) { return i < CH * 4 ? ((((i >> 2) * kTopkThreads + tid) << 2) | (i & 3)) : (nfull << 2) + tid; };
+    auto slot_index = [&](int i) { return i < CH * 4 ? (((c0 + (i >> 2) * kTopkThreads + tid) << 2) | (i & 3)) : (nfull << 2) + tid; };
 
     // ---- row normaliser -------------------------------------------------
     float lse_nat = 0.f;
@@ -286,14 +298,16 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
 
     // ---- outputs ----------------------------------------------------------
     const int nout = s_nout;
+    const int64_t orow = (int64_t)row * nseg + seg;  // list index: the row, or the row's segment
+    const float sub = nseg > 1 ? 0.f : lse_nat;       // segments leave the normaliser to the consumer
     if (tid < a.k_max) {
-        const int64_t o = (int64_t)row * a.k_max + tid;
+        const int64_t o = orow * a.k_max + tid;
         if (tid < nout) {
             const int t = s_outi[tid];
             a.tokens[o] = t;
             if (WANT_LSE) {
-                if (a.perturbed) a.perturbed[o] = s_outv[tid] - lse_nat;
-                if (a.logprob) a.logprob[o] = zrow[t] * a.inv_t - lse_nat;
+                if (a.perturbed) a.perturbed[o] = s_outv[tid] - sub;
+                if (a.logprob) a.logprob[o] = zrow[t] * a.inv_t - sub;
             }
         } else {
             a.tokens[o] = -1;
@@ -302,8 +316,9 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
         }
     }
     if (tid == 0) {
-        if (a.count) a.count[row] = nout;
-        if (WANT_LSE && a.lse) a.lse[row] = dead ? 0.f : lse_nat;
+        if (a.count) a.count[orow] = nout;
+        if (WANT_LSE && nseg > 1) a.seg_ms[orow] = dead ? MaxSum{-INFINITY, 0.f} : acc;
+        if (WANT_LSE && nseg == 1 && a.lse) a.lse[row] = dead ? 0.f : lse_nat;
     }
 }
 
@@ -313,65 +328,116 @@ __global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
 // T(u, .) is increasing within a row (Theorem 3.2's argument).
 // ---------------------------------------------------------------------------
 struct SbsSelectArgs {
-    const int *row_tok;      // [B*W_in, W]
-    const float *row_pert;   // [B*W_in, W]  z/T - lse + G
-    const float *row_logp;   // [B*W_in, W]  z/T - lse
-    const int *row_cnt;      // [B*W_in]
+    const int *row_tok;      // [B*W_in*nseg, W]
+    const float *row_pert;   // [B*W_in*nseg, W]  z/T + G  (- lse when nseg == 1)
+    const float *row_logp;   // [B*W_in*nseg, W]  z/T      (- lse when nseg == 1)
+    const int *row_cnt;      // [B*W_in*nseg]
+    const MaxSum *seg_ms;    // [B*W_in*nseg] partial normalisers when nseg > 1
     const float *sum_logprob;   // [B, W_in]
     const float *trunc_gumbel;  // [B, W_in]
     const int *n_in;
-    int W_in, W, V;
+    int W_in, W, V, nseg;
     int *tokens;
     int *parent;
     float *sum_out;
     float *gum_out;
     int *n_out;
+    float *lse;  // [B, W_in] written here when nseg > 1, or null
 };
 
+// One thread per candidate slot (row w, segment sg, position j): W_in * nseg * W <= 256.  With
+// segments, every slot of a row is a candidate (a superset of the row's top W, which is all
+// that can matter), the row normaliser is merged from the segments' (max, sum) pairs and the
+// row maximum Z is the largest first entry of the row's segment lists.
 __global__ __launch_bounds__(256) void sbs_select_kernel(SbsSelectArgs a) {
-    __shared__ double s_psi[256];
-    __shared__ int s_key[256];
+    __shared__ __align__(16) double s_psi[256];
+    __shared__ __align__(16) int s_key[256];
+    __shared__ float s_lse[RSD_K_MAX];   // per row (0 when the lists are already normalised)
+    __shared__ float s_top[RSD_K_MAX];   // per row: largest perturbed score (same offset as the lists)
+    __shared__ MaxSum s_sms[RSD_K_MAX * 8];
+    __shared__ float s_stop[RSD_K_MAX * 8];
     const int b = blockIdx.x;
     const int t = threadIdx.x;
-    const int w = t / a.W;
-    const int j = t - w * a.W;
+    const int nseg = a.nseg;
+    const int per_row = nseg * a.W;
+    const int w = t / per_row;
+    const int sg = (t - w * per_row) / a.W;
+    const int j = t - w * per_row - sg * a.W;
     const int n = min(max(a.n_in[b], 0), a.W_in);
+    // Everything a slot needs comes from global memory in one round of independent loads (the
+    // lists were written by other CUs a moment ago, so every dependent round trip costs
+    // microseconds); slots beyond a list's count read initialised padding.
+    const bool slot = t < a.W_in * per_row;
+    const int row = b * a.W_in + (slot ? w : 0);
+    const int list = row * nseg + (slot ? sg : 0);
+    const int cnt = a.row_cnt[list];
+    const int tok_in = a.row_tok[(int64_t)list * a.W + j % a.W];
+    const float pert_in = a.row_pert[(int64_t)list * a.W + j % a.W];
+    const float logp_in = a.row_logp[(int64_t)list * a.W + j % a.W];
+    const MaxSum ms_in = nseg > 1 ? a.seg_ms[list] : MaxSum{-INFINITY, 0.f};
+    const float sigma_in = a.sum_logprob[row], gamma_in = a.trunc_gumbel[row];
+    const bool row_live = slot && w < n;
+    if (slot && j == 0) {  // head of list (w, sg)
+        s_sms[w * nseg + sg] = row_live ? ms_in : MaxSum{-INFINITY, 0.f};
+        s_stop[w * nseg + sg] = (row_live && cnt > 0) ? pert_in : -INFINITY;
+    }
+    __syncthreads();
+    if (t < a.W_in) {
+        float lse = 0.f, top = -INFINITY;
+        MaxSum ms{-INFINITY, 0.f};
+        for (int g = 0; g < nseg; ++g) {
+            ms = merge(ms, s_sms[t * nseg + g]);
+            top = fmaxf(top, s_stop[t * nseg + g]);
+        }
+        if (nseg > 1 && t < n) lse = (ms.m + log2f(ms.s)) * kLn2;
+        s_lse[t] = lse;
+        s_top[t] = top;
+        if (a.lse && nseg > 1) a.lse[b * a.W_in + t] = lse;
+    }
+    __syncthreads();
     double psi = -INFINITY, phi = -INFINITY;
     int tok = -1;
-    bool live = false;
-    if (w < n && w < a.W_in) {
-        const int row = b * a.W_in + w;
-        if (j < a.row_cnt[row]) {
-            live = true;
-            tok = a.row_tok[row * a.W + j];
-            const double sigma = (double)a.sum_logprob[row];
-            const double gamma = (double)a.trunc_gumbel[row];
-            const double pj = (double)a.row_pert[row * a.W + j];
-            const double p0 = (double)a.row_pert[row * a.W];
-            phi = (double)a.row_logp[row * a.W + j] + sigma;
-            const double d = pj - p0;  // Phi~ - Z <= 0 (the row's sigma cancels)
-            if (j == 0 || !(d < 0.0)) {
-                psi = gamma;
-            } else {
-                const double log1m = d > -0.6931471805599453 ? log(-expm1(d)) : log1p(-exp(d));
-                const double v = gamma - (pj + sigma) + log1m;
-                psi = gamma - (fmax(v, 0.0) + log1p(exp(-fabs(v))));
-            }
+    const bool live = row_live && j < cnt;
+    if (live) {
+        tok = tok_in;
+        const double sigma = (double)sigma_in;
+        const double gamma = (double)gamma_in;
+        const double lse = (double)s_lse[w];
+        const double pj = (double)pert_in - lse;
+        const double p0 = (double)s_top[w] - lse;
+        phi = (double)logp_in - lse + sigma;
+        const double d = pj - p0;  // Phi~ - Z <= 0 (the row's sigma cancels)
+        if (!(d < 0.0)) {
+            psi = gamma;
+        } else {
+            const double log1m = d > -0.6931471805599453 ? log(-expm1(d)) : log1p(-exp(d));
+            const double v = gamma - (pj + sigma) + log1m;
+            psi = gamma - (fmax(v, 0.0) + log1p(exp(-fabs(v))));
         }
     }
     s_psi[t] = live ? psi : -INFINITY;
     s_key[t] = live ? (w * a.V + tok) : INT_MAX;
     __syncthreads();
+    // rank of this slot among all slots (all 256 entries of the two arrays are initialised, so
+    // the loop may run past the last used slot in steps of four: 16-byte LDS reads)
     int total = 0, rank = 0;
-    const int slots = a.W_in * a.W;  // thread slots that can hold a candidate
-    for (int o = 0; o < slots; ++o) {
-        const double op = s_psi[o];
-        const int ok = s_key[o];
-        const bool olive = ok != INT_MAX;
-        total += olive;
-        if (live && olive && ((op > psi) || (op == psi && ok < s_key[t]))) ++rank;
+    const int slots = a.W_in * per_row;  // thread slots that can hold a candidate
+    const int mykey = s_key[t];
+    for (int o = 0; o < slots; o += 4) {
+        const double2 p01 = *reinterpret_cast<const double2 *>(&s_psi[o]);
+        const double2 p23 = *reinterpret_cast<const double2 *>(&s_psi[o + 2]);
+        const int4 k4 = *reinterpret_cast<const int4 *>(&s_key[o]);
+        const double op[4] = {p01.x, p01.y, p23.x, p23.y};
+        const int ok[4] = {k4.x, k4.y, k4.z, k4.w};
+#pragma unroll
+        for (int q = 0; q < 4; ++q) {
+            // bitwise on purpose: no branches inside the loop
+            const bool olive = ok[q] != INT_MAX;
+            total += olive ? 1 : 0;
+            rank += (int)(olive & ((op[q] > psi) | ((op[q] == psi) & (ok[q] < mykey))));
+        }
     }
-    if (live && rank < a.W) {
+    if (live && rank < a.W) {  // (the rank of a slot that is not live is never used)
         const int o = b * a.W + rank;
         a.tokens[o] = tok;
         a.parent[o] = w;
@@ -395,13 +461,15 @@ static int32_t launch_topk(const TopkArgs &a, int R, hipStream_t st) {
     if (R == 0) return RSD_OK;
     // the normaliser costs an exponential per entry: skip it when only tokens are wanted
     const bool want_lse = a.perturbed || a.logprob || a.lse;
-    const int chunks = (a.V + kTopkThreads * 4 - 1) / (kTopkThreads * 4);  // float4 chunks per thread
+    const int nseg = a.nseg;
+    const int per = ((a.V >> 2) + nseg - 1) / nseg;                         // chunks of one segment
+    const int chunks = per > 0 ? (per + kTopkThreads - 1) / kTopkThreads : 1;  // float4 chunks per thread
 #define RSD_LAUNCH_TOPK(CH)                                                                          \
     do {                                                                                             \
         if (want_lse)                                                                                \
-            hipLaunchKernelGGL((gumbel_topk_kernel<CH, true>), dim3(R), dim3(kTopkThreads), 0, st, a);  \
+            hipLaunchKernelGGL((gumbel_topk_kernel<CH, true>), dim3(R * nseg), dim3(kTopkThreads), 0, st, a);  \
         else                                                                                         \
-            hipLaunchKernelGGL((gumbel_topk_kernel<CH, false>), dim3(R), dim3(kTopkThreads), 0, st, a); \
+            hipLaunchKernelGGL((gumbel_topk_kernel<CH, false>), dim3(R * nseg), dim3(kTopkThreads), 0, st, a); \
     } while (0)
     if (chunks <= 2)
         RSD_LAUNCH_TOPK(2);
@@ -447,16 +515,28 @@ extern "C" int32_t rsd_gumbel_topk(const float *logits, int64_t ld, int32_t R, i
     a.seq_id = seq_id; a.node_id = node_id; a.n_live = nullptr; a.rows_per_seq = 1;
     a.seq_default_is_b = 0; a.node_default_is_w = 0; a.inv_t = inv_temperature;
     a.seed = seed; a.step = step; a.tokens = tokens; a.perturbed = perturbed;
-    a.logprob = logprob; a.lse = lse; a.count = count;
+    a.logprob = logprob; a.lse = lse; a.count = count; a.nseg = 1; a.seg_ms = nullptr;
     return launch_topk(a, R, (hipStream_t)stream);
 }
 
 static size_t align_up(size_t x, size_t a) { return (x + a - 1) / a * a; }
 
-extern "C" size_t rsd_sbs_step_workspace_bytes(int32_t B, int32_t W_in, int32_t, int32_t W) {
+// Segments per row of one SBS step: split rows while the launch leaves most of the chip idle,
+// as long as every candidate slot still has a thread in the select kernel and a segment keeps
+// at least 4096 entries.
+static int sbs_segments(int B, int W_in, int V, int W) {
+    const long rows = (long)B * W_in;
+    int s = 1;
+    while (s < 8 && rows * (s * 2) <= 256 && (long)W_in * W * (s * 2) <= 256 && V / (s * 2) >= 4096 &&
+           (V & 3) == 0)
+        s *= 2;
+    return s;
+}
+
+extern "C" size_t rsd_sbs_step_workspace_bytes(int32_t B, int32_t W_in, int32_t V, int32_t W) {
     if (B < 0 || W_in < 0 || W < 0) return 0;
-    const size_t rows = (size_t)B * W_in;
-    return 3 * align_up(rows * W * 4, 256) + align_up(rows * 4, 256);
+    const size_t lists = (size_t)B * W_in * (size_t)sbs_segments(B, W_in, V > 0 ? V : 1, W > 0 ? W : 1);
+    return 3 * align_up(lists * W * 4, 256) + align_up(lists * 4, 256) + align_up(lists * sizeof(MaxSum), 256);
 }
 
 extern "C" int32_t rsd_sbs_step(const float *logits, const float *sum_logprob,
@@ -476,24 +556,28 @@ extern "C" int32_t rsd_sbs_step(const float *logits, const float *sum_logprob,
     const size_t need = rsd_sbs_step_workspace_bytes(B, W_in, V, W);
     if (!workspace || workspace_bytes < need) return RSD_ERR_WORKSPACE;
     const size_t rows = (size_t)B * W_in;
+    const int nseg = sbs_segments(B, W_in, V, W);
+    const size_t lists = rows * nseg;
     char *ws = static_cast<char *>(workspace);
-    const size_t seg = align_up(rows * W * 4, 256);
+    const size_t seg = align_up(lists * W * 4, 256);
     int *row_tok = reinterpret_cast<int *>(ws);
     float *row_pert = reinterpret_cast<float *>(ws + seg);
     float *row_logp = reinterpret_cast<float *>(ws + 2 * seg);
     int *row_cnt = reinterpret_cast<int *>(ws + 3 * seg);
+    MaxSum *seg_ms = reinterpret_cast<MaxSum *>(ws + 3 * seg + align_up(lists * 4, 256));
 
     TopkArgs a{};
     a.logits = logits; a.ld = V; a.V = V; a.k_max = W; a.k_per_row = nullptr;
     a.seq_id = seq_id; a.node_id = node_id; a.n_live = n_in; a.rows_per_seq = W_in;
     a.seq_default_is_b = 1; a.node_default_is_w = 1; a.inv_t = inv_temperature;
     a.seed = seed; a.step = step; a.tokens = row_tok; a.perturbed = row_pert;
-    a.logprob = row_logp; a.lse = lse; a.count = row_cnt;
+    a.logprob = row_logp; a.lse = lse; a.count = row_cnt; a.nseg = nseg; a.seg_ms = seg_ms;
     const int32_t rc = launch_topk(a, (int)rows, (hipStream_t)stream);
     if (rc != RSD_OK) return rc;
 
     SbsSelectArgs s{};
     s.row_tok = row_tok; s.row_pert = row_pert; s.row_logp = row_logp; s.row_cnt = row_cnt;
+    s.seg_ms = seg_ms; s.nseg = nseg; s.lse = lse;
     s.sum_logprob = sum_logprob; s.trunc_gumbel = trunc_gumbel; s.n_in = n_in;
     s.W_in = W_in; s.W = W; s.V = V; s.tokens = tokens; s.parent = parent;
     s.sum_out = sum_logprob_out; s.gum_out = trunc_gumbel_out; s.n_out = n_out;

@@ -133,6 +133,43 @@ def test_sbs_step_matches_oracle(B, W_in, V, W, inv_t):
     assert near <= 1
 
 
+def test_sbs_step_split_rows_with_sparse_and_dead_rows():
+    """Few rows: each row is split over several workgroups.  One live row keeps only three finite
+    entries (all in one segment, so the other segments have no candidate), another sequence has dead
+    rows, and the root step (one row per sequence) takes the widest split."""
+    say("sbs_step with rows split into segments, sparse and dead rows")
+    d = dev()
+    for B, W_in, V, W, seed in [(2, 4, 16384, 4, 5), (3, 1, 50272, 6, 6)]:
+        _, zd = workloads.make_logits("zipf", B, W_in, V, seed=seed)
+        zd = zd.clone()
+        keep = zd[B - 1, 0, [7, 4100, 4101]].clone()
+        zd[B - 1, 0, :] = -float("inf")
+        zd[B - 1, 0, [7, 4100, 4101]] = keep
+        rng = np.random.default_rng(seed)
+        sigma = (-rng.exponential(3.0, size=(B, W_in))).astype(np.float32)
+        gamma = (-np.sort(rng.exponential(1.0, size=(B, W_in)), axis=1)).astype(np.float32)
+        n_in = np.full(B, W_in, dtype=np.int32)
+        if W_in > 1:
+            n_in[0] = 2                                                  # rows 2, 3 of sequence 0 are dead
+        g = binding.sbs_step(zd.to(d), torch.from_numpy(sigma).to(d), torch.from_numpy(gamma).to(d),
+                             torch.from_numpy(n_in).to(d), W, seed=31, step=1)
+        ref = o_sbs.sbs_step(zd.numpy(), sigma, gamma, n_in, W, seed=31, step=1)
+        assert np.array_equal(to_np(g["n_out"]), ref["n_out"])
+        for b in range(B):
+            n = int(ref["n_out"][b])
+            if np.any(-np.diff(ref["trunc_gumbel"][b, :n]) < NEAR_TIE):
+                continue
+            assert np.array_equal(to_np(g["tokens"])[b, :n], ref["tokens"][b, :n])
+            assert np.array_equal(to_np(g["parent"])[b, :n], ref["parent"][b, :n])
+            assert np.allclose(to_np(g["sum_logprob"])[b, :n], ref["sum_logprob"][b, :n], rtol=1e-6, atol=LOGP_TOL)
+            assert np.allclose(to_np(g["trunc_gumbel"])[b, :n], ref["trunc_gumbel"][b, :n], rtol=1e-6, atol=2e-5)
+            assert np.all(to_np(g["tokens"])[b, n:] == -1)
+            live = int(n_in[b])
+            assert np.allclose(to_np(g["lse"])[b, :live], ref["lse"][b, :live], rtol=0, atol=LOGP_TOL)
+        if W_in == 1:
+            assert int(ref["n_out"][B - 1]) == 3                          # only three finite entries
+
+
 # ------------------------------------------------------------------ tree building
 def test_draft_trees_match_oracle_gumbel_and_sbs():
     say("draft trees (config 0 and a small config-1-like case)")
