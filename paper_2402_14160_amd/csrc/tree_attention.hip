@@ -673,7 +673,6 @@ __global__ __launch_bounds__(kWave) void tree_attn_merge_kernel(AttnArgs a) {
     const float *po = a.ws_o + orow * a.ws_splits * a.D;
     for (int d = lane; d < a.D; d += kWave) {
         float acc = 0.f;
-#pragma unroll 4
         for (int s = 0; s < splits; ++s) acc += __shfl(w, s, kWave) * po[(int64_t)s * a.D + d];
         a.out[orow * a.D + d] = acc * inv;
     }
