@@ -96,7 +96,8 @@ def test_gumbel_topk_rejects_bad_arguments():
 
 # -------------------------------------------------------------------------- SBS
 @pytest.mark.parametrize("B,W_in,V,W,inv_t", [(1, 1, 64, 2, 1.0), (3, 6, 32000, 6, 1.0),
-                                               (2, 6, 50272, 6, 1.0), (2, 12, 4000, 12, 1 / 0.3)])
+                                               (2, 6, 50272, 6, 1.0), (2, 12, 4000, 12, 1 / 0.3),
+                                               (1, 16, 8192, 16, 1.0)])   # widest beam: 256 candidate slots
 def test_sbs_step_matches_oracle(B, W_in, V, W, inv_t):
     say(f"sbs_step B={B} W_in={W_in} V={V} W={W}")
     _, zd = workloads.make_logits("zipf", B, W_in, V, seed=4)
