@@ -572,12 +572,18 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
 // ---------------------------------------------------------------------------
 constexpr int kPlanThreads = 1024;
 
+constexpr int kPlanLds = 8192;  // nodes whose child counts fit the workgroup's LDS
+
 __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
     __shared__ int hist[RSD_K_MAX + 1];
     __shared__ int offs[RSD_K_MAX + 1];
+    __shared__ int s_k[kPlanLds];
     const int tid = threadIdx.x;
     const int total = a.B * a.N;
-    for (int i = tid; i < total; i += kPlanThreads) a.kcount[i] = 0;
+    // the counts are accumulated in LDS when they fit (LDS atomics instead of global ones)
+    const bool in_lds = total <= kPlanLds;
+    int *cnt = in_lds ? s_k : a.kcount;
+    for (int i = tid; i < total; i += kPlanThreads) cnt[i] = 0;
     if (tid <= RSD_K_MAX) hist[tid] = 0;
     if (tid == 0) {
         a.wq[0] = 0;
@@ -589,12 +595,14 @@ __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
         const int n = min(max(a.n_nodes[b], 1), a.N);
         if (j >= 1 && j < n) {
             const int p = a.parent[i];
-            if (p >= 0 && p < j) atomicAdd(&a.kcount[b * a.N + p], 1);
+            if (p >= 0 && p < j) atomicAdd(&cnt[b * a.N + p], 1);
         }
     }
     __syncthreads();
     for (int i = tid; i < total; i += kPlanThreads) {
-        const int k = min(a.kcount[i], RSD_K_MAX);
+        const int c = cnt[i];
+        if (in_lds) a.kcount[i] = c;
+        const int k = min(c, RSD_K_MAX);
         if (k > 0) atomicAdd(&hist[k], 1);
     }
     __syncthreads();
@@ -608,7 +616,7 @@ __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
     }
     __syncthreads();
     for (int i = tid; i < total; i += kPlanThreads) {
-        const int k = min(a.kcount[i], RSD_K_MAX);
+        const int k = min(cnt[i], RSD_K_MAX);
         if (k > 0) a.work[atomicAdd(&offs[k], 1)] = i;
     }
 }
