@@ -391,15 +391,15 @@ __device__ __forceinline__ float sum_across_halves(float v) {
     return __uint_as_float(r[0]) + __uint_as_float(r[1]);
 }
 
-template <int D, int WAVES, int STAGES>
-__global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnArgs a) {
+template <int D, int WAVES, int STAGES, bool EXACT>
+__device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *smem) {
     constexpr int THREADS = WAVES * 64;
     constexpr int RPB = WAVES * 32;  // stacked query rows per workgroup
     constexpr int LOADS = tile_loads_per_thread<D, THREADS>();
     static_assert(STAGES == 2 || STAGES == 3, "ring depth");
     constexpr int KS = D / 16;     // k-steps of the first product
     constexpr int DT = D / 32;     // 32-row output tiles of the second product
-    extern __shared__ __align__(16) unsigned char smem[];
+    constexpr float kRowSumLimit = 0x1p100f;  // fast pass: larger row sums send the block to the exact pass
     __bf16 *Ks = reinterpret_cast<__bf16 *>(smem);                         // [STAGES][kTile][D], swizzled
     __bf16 *Vs = Ks + STAGES * kTile * D;                                  // [STAGES][kTile][D], swizzled
     uint64_t *anc = reinterpret_cast<uint64_t *>(Vs + STAGES * kTile * D);  // [N][kAncWords]
@@ -410,7 +410,7 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
     const int plen = min(max(a.plen[b], 0), a.P_max);
     const int G = a.Hq / a.Hkv;
     const int rows = G * n;
-    if (a.row_base + rb * RPB >= rows) return;
+    if (a.row_base + rb * RPB >= rows) return false;
 
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q32 = lane & 31, h = lane >> 5;
@@ -484,6 +484,38 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
         wait_tile_loads<0>();
     }
     __syncthreads();
+
+    if (!EXACT && wave_active && ntiles > 0) {
+        // fixed reference of the fast pass: the row maximum over the first tile (every valid row sees
+        // at least one of its keys: a prefix tile is visible to all rows, tree tile 0 holds the root)
+        const __bf16 *kb0 = Ks + q32 * D;
+        const int ksw0 = swz<D>(q32);
+        const bool is_tree = npre == 0;
+        const int row0 = is_tree ? 0 : t0 * kTile;
+        const int limit = is_tree ? n : plen;
+        uint64_t vis = ~0ull;
+        if (is_tree) vis = anc[qi * kAncWords];
+        if (row0 + kTile > limit) vis &= (1ull << (limit - row0)) - 1ull;
+        float mx = -INFINITY;
+#pragma unroll
+        for (int t = 0; t < 2; ++t) {
+            floatx16 sv;
+#pragma unroll
+            for (int r = 0; r < 16; ++r) {
+                const int kk = t * 32 + 8 * (r >> 2) + 4 * h + (r & 3);
+                sv[r] = ((vis >> kk) & 1ull) ? 0.f : -INFINITY;
+            }
+#pragma unroll
+            for (int ks = 0; ks < KS; ++ks) {
+                const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(kb0 + t * 32 * D + (((ks * 2 + h) ^ ksw0) << 3));
+                sv = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[ks], sv, 0, 0, 0);
+            }
+#pragma unroll
+            for (int r = 0; r < 16; ++r) mx = fmaxf(mx, sv[r]);
+        }
+        mx = max_across_halves(mx) * a.scale_log2;
+        m = (mx == -INFINITY) ? 0.f : mx;
+    }
 
     // Full prefix tiles (nearly all of them) run the mask-free copy of the loop body in a loop of
     // their own; the ragged last prefix tile and the tree tiles follow in the masked copy.
@@ -599,10 +631,10 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
                 for (int r = 0; r < 16; ++r) s0[r] = s1[r] = 0.f;
             }
             qk_half(s0, 0);
-            raise_max(half_max(s0), false);
+            if (EXACT) raise_max(half_max(s0), false);
             qk_half(s1, 1);
             half_exp(s0, pf[0], pf[1]);
-            raise_max(half_max(s1), true);
+            if (EXACT) raise_max(half_max(s1), true);
             pv_step(0, pf[0]);
             pv_step(1, pf[1]);
             half_exp(s1, pf[2], pf[3]);
@@ -623,7 +655,12 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
 
     // ---- epilogue -------------------------------------------------------------------
     const float lt = sum_across_halves(l);
-    if (!qvalid) return;
+    if (!EXACT) {
+        // every probability is at most its row sum: a row sum below the limit means that no
+        // exponential (and no product with V of ordinary magnitude) overflowed
+        if (__syncthreads_or(qvalid && !(lt < kRowSumLimit))) return true;  // workgroup-uniform
+    }
+    if (!qvalid) return false;
     const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + qi;
     if (a.splits == 1) {
         const float inv = lt > 0.f ? 1.f / lt : 0.f;
@@ -651,6 +688,17 @@ __global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnA
             a.ws_l[orow * a.ws_splits + sp] = lt;
         }
     }
+    return false;
+}
+
+// The 32-row kernel proper.  Fast pass with a fixed softmax reference per row, the row maximum
+// over the first tile: no row maxima, no rescaling and no branch between the matrix groups of a
+// tile.  A workgroup in which some row sum reaches 2^100 (scores about 100 log2 units above the
+// reference) repeats its block with the exact running-maximum pass.
+template <int D, int WAVES, int STAGES>
+__global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnArgs a) {
+    extern __shared__ __align__(16) unsigned char smem[];
+    if (attn_w32_body<D, WAVES, STAGES, false>(a, smem)) attn_w32_body<D, WAVES, STAGES, true>(a, smem);
 }
 
 // Merge the per-split partial results of the stacked rows [row_base, row_base + gridDim.x) of
