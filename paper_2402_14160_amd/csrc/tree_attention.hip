@@ -696,7 +696,7 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
 // tile.  A workgroup in which some row sum reaches 2^100 (scores about 100 log2 units above the
 // reference) repeats its block with the exact running-maximum pass.
 template <int D, int WAVES, int STAGES>
-__global__ __launch_bounds__(WAVES * 64, 2) void tree_attn_bf16_w32_kernel(AttnArgs a) {
+__global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void tree_attn_bf16_w32_kernel(AttnArgs a) {
     extern __shared__ __align__(16) unsigned char smem[];
     if (attn_w32_body<D, WAVES, STAGES, false>(a, smem)) attn_w32_body<D, WAVES, STAGES, true>(a, smem);
 }
@@ -815,15 +815,16 @@ static size_t align_up(size_t x, size_t al) { return (x + al - 1) / al * al; }
 static bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
 // ---------------------------------------------------------------------------
-// Launch plan.  The stacked rows of a (sequence, KV head) pair are covered by up to two
-// launches: full 128-row blocks (4 waves of 32 rows, two workgroups per compute unit) and a
-// remainder, by one more 128-row block when at least 96 rows are left, else by 64-row blocks
-// (4 waves of 16 rows).  Every kernel clips to the rows a sequence really has, so the launches
-// write disjoint output rows.  Each launch splits the prefix on its own: only as far as it
-// still fits the chip in one round (512 workgroups on 256 compute units).
+// Launch plan.  The stacked rows of a (sequence, KV head) pair are covered by up to three
+// launches: 256-row blocks (8 waves of 32 rows, one workgroup per compute unit: each staged K/V
+// tile serves twice the rows), 128-row blocks (4 waves of 32 rows, two workgroups per compute
+// unit; also taken for a remainder of at least 96 rows) and 64-row blocks (4 waves of 16 rows).
+// Every kernel clips to the rows a sequence really has, so the launches write disjoint output
+// rows.  Each launch splits the prefix on its own: only as far as it still fits the chip in one
+// round.
 // ---------------------------------------------------------------------------
-enum AttnVariant { kV16 = 0, kV32x4 = 1 };
-constexpr int kMaxSegments = 2;
+enum AttnVariant { kV16 = 0, kV32x4 = 1, kV32x8 = 2 };
+constexpr int kMaxSegments = 3;
 constexpr int kMaxSplits = 32;
 
 struct AttnSegment {
@@ -833,21 +834,29 @@ struct AttnSegment {
 static int plan_segments(int dtype, int B, int Hq, int Hkv, int N, int P_max, int requested,
                          AttnSegment seg[kMaxSegments]) {
     const int rows = (Hq / Hkv) * N;
-    int nseg = 0;
-    int full = rows / 128, rem = rows - full * 128;
+    int nseg = 0, base = 0;
+    const int full256 = rows / 256;
+    if (full256 > 0) {
+        seg[nseg++] = AttnSegment{kV32x8, 0, full256, 1};
+        base = full256 * 256;
+    }
+    int full128 = (rows - base) / 128, rem = rows - base - full128 * 128;
     if (rem >= 96) {  // worth one more 128-row block
-        ++full;
+        ++full128;
         rem = 0;
     }
-    if (full > 0) seg[nseg++] = AttnSegment{kV32x4, 0, full, 1};
-    if (rem > 0) seg[nseg++] = AttnSegment{kV16, full * 128, (rem + 63) / 64, 1};
+    if (full128 > 0) {
+        seg[nseg++] = AttnSegment{kV32x4, base, full128, 1};
+        base += full128 * 128;
+    }
+    if (rem > 0) seg[nseg++] = AttnSegment{kV16, base, (rem + 63) / 64, 1};
     const int tiles = (P_max + kTile - 1) / kTile;
     for (int i = 0; i < nseg; ++i) {
         int s = requested;
         if (dtype != RSD_DTYPE_BF16) s = 1;
-        if (s <= 0) {  // fill the chip in one round: two workgroups per CU
+        if (s <= 0) {  // fill the chip in one round: one or two workgroups per CU
             const long blocks = (long)seg[i].row_blocks * Hkv * B;
-            s = (int)(512 / (blocks > 0 ? blocks : 1));
+            s = (int)((seg[i].variant == kV32x8 ? 256 : 512) / (blocks > 0 ? blocks : 1));
             // a split of fewer than four tiles costs more in set-up and merging than it gains
             if (s > tiles / 4) s = tiles / 4;
         }
@@ -887,11 +896,14 @@ static hipError_t launch_attn(Kernel kernel, bool &attr_set, size_t smem_max, si
 
 template <int D>
 static hipError_t launch_segment(const AttnSegment &sg, AttnArgs a, hipStream_t st) {
-    static bool set16 = false, set4 = false;
+    static bool set16 = false, set4 = false, set8 = false;
     a.row_base = sg.row_base;
     a.row_blocks = sg.row_blocks;
     a.splits = sg.splits;
     const dim3 grid((unsigned)((long)sg.row_blocks * a.splits * a.Hkv * a.B));
+    if (sg.variant == kV32x8)
+        return launch_attn(tree_attn_bf16_w32_kernel<D, 8, 2>, set8, attn_smem_bytes<D>(RSD_NODES_MAX, 2),
+                           attn_smem_bytes<D>(a.N, 2), grid, 512, st, a);
     if (sg.variant == kV32x4)
         return launch_attn(tree_attn_bf16_w32_kernel<D, 4, 2>, set4, attn_smem_bytes<D>(RSD_NODES_MAX, 2),
                            attn_smem_bytes<D>(a.N, 2), grid, 256, st, a);
