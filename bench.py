@@ -36,6 +36,10 @@ VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 # 64-bit multiplies of the Philox rounds and hardware logs, so the pipeline is busier than this fraction
 GUMBEL_VALU_PER_ENTRY = 27.3
 N_LAYERS = {"cfg1_llama2_7b": 32, "cfg2_opt_13b_sbs": 40, "cfg3_llama2_70b_gqa": 80, "cfg4_stress": 32}
+# draft size / target size of the model pairs the shapes stand for (App. C: a 115M drafter for the
+# Llama 2 targets, OPT-125M for OPT-13B): the relative draft cost r of the memory-bound speed-up
+DRAFT_TO_TARGET = {"cfg1_llama2_7b": 0.115 / 7.0, "cfg2_opt_13b_sbs": 0.125 / 13.0,
+                   "cfg3_llama2_70b_gqa": 0.115 / 70.0, "cfg4_stress": 0.115 / 7.0}
 
 
 def build_case(cfg, seed, torch, binding, draft_tree, workloads):
@@ -341,8 +345,13 @@ def filter_kv_pass(case, torch, binding, steps=20):
     # tokens decoded per iteration (accepted draft tokens + the sampled last token), the paper's block
     # efficiency, here on synthetic logits whose draft/target gap is a recipe, not a trained pair
     block_eff = rows / B
-    return dict(filter_kv_ms=round(e0.elapsed_time(e1) / steps, 4), filter_kv_rows=rows * Hkv,
-                block_efficiency_synthetic=round(block_eff, 3))
+    out = dict(filter_kv_ms=round(e0.elapsed_time(e1) / steps, 4), filter_kv_rows=rows * Hkv,
+               block_efficiency_synthetic=round(block_eff, 3))
+    if cfg["name"] in DRAFT_TO_TARGET:
+        # memory-bound speed-up (App. C, performance metrics): block efficiency / (depth * r + 1)
+        depth = cfg["depth"] if cfg["sampler"] == "sbs" else len(cfg["branching"])
+        out["mbsu_synthetic"] = round(block_eff / (depth * DRAFT_TO_TARGET[cfg["name"]] + 1.0), 3)
+    return out
 
 
 def filter_logits_pass(case, torch, binding, steps=5):
