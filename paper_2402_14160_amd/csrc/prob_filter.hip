@@ -1,16 +1,20 @@
 // Top-k / nucleus (top-p) filtering of logit rows (Sec. 4, experiment setup: nucleus sampling
 // with p = 0.95; last step of Alg. 4 and Alg. 9: candidates filtered to -inf are dropped).
 //
-// One 1024-thread workgroup owns one row and keeps its unnormalised probabilities
+// One workgroup owns one row and keeps its unnormalised probabilities
 // e_x = exp((z_x - max) / T) in registers.  Both filters ask for the largest threshold t with
 // F(t) >= target, where F(t) = sum over {x : e_x >= t} of a weight (1 for top-k, e_x for top-p)
-// is a non-increasing step function: the threshold is found by bisection on the bit pattern of
-// t (positive floats order like their bit patterns): workgroup-wide sums over the registers
-// until few entries are left between the bounds, then one wave finishes on those alone.  The
-// summation order is fixed, so a row always gives the same result.  No sort; entries equal to
-// the threshold are all kept.
+// is a non-increasing step function.  The threshold is found by bisection on the bit pattern of
+// t (positive floats order like their bit patterns), starting between the row's smallest
+// positive entry (whose F, the total, comes out of the exponential pass) and 1: workgroup-wide
+// sums over the registers until few entries are left between the bounds; those are compacted
+// into LDS and every wave then probes its own threshold on them (a 17-way split per round)
+// until one entry is left.  The summation order is fixed, so a row always gives the same
+// result.  No sort; entries equal to the threshold are all kept.
 #include <hip/hip_runtime.h>
 #include <math.h>
+
+#include <type_traits>
 
 #include "../../include/rsd.h"
 #include "rsd_device.hpp"
@@ -32,28 +36,44 @@ struct FilterLogitsArgs {
 constexpr int kFilterThreads = 1024;
 constexpr float kMinNormal = 1.17549435e-38f;
 constexpr uint32_t kMinNormalBits = 0x00800000u;
-constexpr int kFilterCand = 1024;  // entries between the bounds when one wave takes over the search
+constexpr uint32_t kAboveOneBits = 0x3F800001u;  // e <= 1, so nothing is >= this
+constexpr int kFilterCand = 1024;  // entries between the bounds when the per-wave probes take over
 
-template <int CH>
-__global__ __launch_bounds__(kFilterThreads) void prob_filter_kernel(FilterLogitsArgs a) {
-    __shared__ double s_sum[kFilterThreads / kWave];
-    __shared__ __align__(16) float s_part[2 * kFilterThreads / kWave];  // wave partials: masses, then counts
-    __shared__ float s_max[kFilterThreads / kWave];
-    __shared__ int s_woff[kFilterThreads / kWave];
+// sum of lanes 0..15 of a wave (one DPP row), the same in every lane; fixed order
+__device__ __forceinline__ float row0_sum(float v) {
+    v += dpp_move<0xB1>(v);
+    v += dpp_move<0x4E>(v);
+    v += dpp_move<0x124>(v);
+    v += dpp_move<0x128>(v);
+    return read_lane(v, 0);
+}
+
+// CH: float4 chunks per thread; RAGGED: V is not a multiple of 4 (the last chunk is then read
+// and written entry by entry).  Up to 8 chunks per thread the kernel fits 64 registers, so two
+// workgroups share a CU and one row's loads and stores overlap the other's arithmetic.
+template <int CH, bool RAGGED>
+__global__ __launch_bounds__(kFilterThreads, CH <= 8 ? 8 : 4) void prob_filter_kernel(FilterLogitsArgs a) {
+    constexpr int kWaves = kFilterThreads / kWave;
+    static_assert(kWaves <= 16, "the wave partials are combined inside one row of 16 lanes");
+    __shared__ float s_part[2][2 * kWaves];  // wave partials (masses, then counts), double-buffered
+    __shared__ float s_max[kWaves];
+    __shared__ uint32_t s_min[kWaves];
+    __shared__ int s_woff[kWaves];
     __shared__ float s_cand[kFilterCand];
-    __shared__ uint32_t s_cut;
     const int row = blockIdx.x, tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const float *zrow = a.logits + (int64_t)row * a.ld;
     const float4 *z4 = reinterpret_cast<const float4 *>(zrow);
     const int V = a.V, nfull = V >> 2;
+    int flip = 0;  // which half of s_part the next workgroup-wide sum uses
 
     // entry (j, q) of this thread is vocabulary index 4 * (j * 1024 + tid) + q; a chunk that
     // straddles the end of the row is read entry by entry
-    auto load_chunk = [&](int c) -> float4 {
+    auto load_chunk = [&](int j, int th) -> float4 {
+        const int c = j * kFilterThreads + th;
         float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
         if (c < nfull) {
-            t = z4[c];
-        } else if (c == nfull) {
+            t = (z4 + j * kFilterThreads)[th];  // uniform base, one lane offset for every j
+        } else if (RAGGED && c == nfull) {
             if (4 * c + 0 < V) t.x = zrow[4 * c + 0];
             if (4 * c + 1 < V) t.y = zrow[4 * c + 1];
             if (4 * c + 2 < V) t.z = zrow[4 * c + 2];
@@ -64,7 +84,7 @@ __global__ __launch_bounds__(kFilterThreads) void prob_filter_kernel(FilterLogit
     float mx = -INFINITY;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-        const float4 t = load_chunk(j * kFilterThreads + tid);
+        const float4 t = load_chunk(j, tid);
         e[4 * j + 0] = t.x; e[4 * j + 1] = t.y; e[4 * j + 2] = t.z; e[4 * j + 3] = t.w;
         mx = fmaxf(mx, fmaxf(fmaxf(t.x, t.y), fmaxf(t.z, t.w)));
     }
@@ -74,66 +94,88 @@ __global__ __launch_bounds__(kFilterThreads) void prob_filter_kernel(FilterLogit
     __syncthreads();
     mx = s_max[0];
 #pragma unroll
-    for (int w = 1; w < kFilterThreads / kWave; ++w) mx = fmaxf(mx, s_max[w]);
-    __syncthreads();
+    for (int w = 1; w < kWaves; ++w) mx = fmaxf(mx, s_max[w]);
     const float mref = (mx == -INFINITY || mx == INFINITY) ? 0.f : mx * a.c2;
+
+    // wave partials (mass, count) -> workgroup totals in every thread: one barrier, then lanes
+    // 0..15 of each wave fetch one partial each and add them inside their DPP row (fp32, fixed
+    // order).  The two halves of s_part alternate, so the next call's writes cannot overtake
+    // this call's reads.
+    auto combine = [&](float pm, float pc, float &mass, float &cnt) {
+        if (lane == 0) {
+            s_part[flip][wave] = pm;
+            s_part[flip][kWaves + wave] = pc;
+        }
+        __syncthreads();
+        const float m = lane < kWaves ? s_part[flip][lane] : 0.f;
+        const float c = lane < kWaves ? s_part[flip][kWaves + lane] : 0.f;
+        mass = row0_sum(m);
+        cnt = row0_sum(c);
+        flip ^= 1;
+    };
+
+    // exponentials; their total, the number of positive ones and the smallest positive one
+    // come out of the same pass
+    float total, npos;
+    uint32_t min_bits;
+    {
+        float pm = 0.f;
+        int wc = 0;
+        uint32_t mb = 0xFFFFFFFFu;
 #pragma unroll
-    for (int i = 0; i < CH * 4; ++i) {
-        const float p = __builtin_amdgcn_exp2f(fmaf(e[i], a.c2, -mref));
-        // -inf and NaN never count; neither do probabilities below the smallest normal number
-        // (1e-38 of the row maximum), so that every threshold tried is a normal number
-        // (the rounded reference can leave the maximum a hair above 1: clamp, the search assumes e <= 1)
-        e[i] = (e[i] > -INFINITY && p >= kMinNormal) ? fminf(p, 1.f) : 0.f;
+        for (int i = 0; i < CH * 4; ++i) {
+            const float p = __builtin_amdgcn_exp2f(fmaf(e[i], a.c2, -mref));
+            // -inf and NaN never count (their p is 0 or NaN); neither do probabilities below the
+            // smallest normal number (1e-38 of the row maximum), so that every threshold tried is
+            // a normal number.  The rounded reference can leave the maximum a hair above 1:
+            // clamp, the search assumes e <= 1.
+            const bool pos = p >= kMinNormal;
+            e[i] = pos ? __builtin_amdgcn_fmed3f(p, 0.f, 1.f) : 0.f;
+            pm += e[i];
+            wc += __builtin_popcountll(__builtin_amdgcn_ballot_w64(pos));
+            mb = min(mb, __float_as_uint(e[i]) - 1u);  // zero wraps to the largest value
+        }
+        pm = wave_sum(pm);
+#pragma unroll
+        for (int o = 32; o >= 1; o >>= 1) mb = min(mb, (uint32_t)__shfl_xor((int)mb, o, kWave));
+        if (lane == 0) s_min[wave] = mb;
+        combine(pm, (float)wc, total, npos);
+        mb = s_min[0];
+#pragma unroll
+        for (int w = 1; w < kWaves; ++w) mb = min(mb, s_min[w]);
+        min_bits = mb + 1u;  // meaningful when npos > 0
     }
 
     // (mass, count) of the entries with e >= t; every thread gets the workgroup's values.
-    // fp32 inside a thread and a wave (fixed order), fp64 across the waves.
-    auto tail_sums = [&](uint32_t t_bits, double &mass, double &cnt) {
+    // The count is a population count of the compare mask (scalar unit, whole wave at once);
+    // only the mass costs vector adds, and a search by count skips it.
+    auto tail_sums = [&](uint32_t t_bits, auto by_count, float &mass, float &cnt) {
         const float t = __uint_as_float(t_bits);
-        // the count is a population count of the compare mask (scalar unit, whole wave at once);
-        // only the mass costs vector adds
         float pm = 0.f;
         int wc = 0;
 #pragma unroll
         for (int i = 0; i < CH * 4; ++i) {
             const bool ge = e[i] >= t;
-            wc += __builtin_popcountll(__ballot(ge));
-            pm += ge ? e[i] : 0.f;
+            wc += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ge));
+            if (!decltype(by_count)::value) pm += ge ? e[i] : 0.f;
         }
-        pm = wave_sum(pm);
-        const float pc = (float)wc;
-        if (lane == 0) {
-            s_part[wave] = pm;
-            s_part[kFilterThreads / kWave + wave] = pc;
-        }
-        __syncthreads();
-        // 16 wave partials each, fetched as 16-byte broadcast reads and added in fp64 in wave order
-        mass = 0.0;
-        cnt = 0.0;
-#pragma unroll
-        for (int w4 = 0; w4 < kFilterThreads / kWave / 4; ++w4) {
-            const float4 pm4 = reinterpret_cast<const float4 *>(s_part)[w4];
-            const float4 pc4 = reinterpret_cast<const float4 *>(s_part)[kFilterThreads / kWave / 4 + w4];
-            mass += (double)pm4.x; mass += (double)pm4.y; mass += (double)pm4.z; mass += (double)pm4.w;
-            cnt += (double)pc4.x; cnt += (double)pc4.y; cnt += (double)pc4.z; cnt += (double)pc4.w;
-        }
-        __syncthreads();
+        if (!decltype(by_count)::value) pm = wave_sum(pm);
+        combine(pm, (float)wc, mass, cnt);
     };
-    // Largest bit pattern t in [smallest normal, 0x3F800000] with F(t) >= target (F = count or mass of the entries
-    // >= t), or 0 when even the smallest pattern falls short.  Bisection over the whole row until at
-    // most kFilterCand entries lie between the two bounds; those are then compacted into LDS in index
-    // order and one wave finishes the bisection on them alone.
-    auto threshold = [&](double target, bool by_count) -> uint32_t {
-        uint32_t lo = kMinNormalBits, hi = 0x3F800001u;  // e <= 1, so F(hi) = 0; invariant F(lo) >= target > F(hi)
-        double f_lo, c_lo, f_hi = 0.0, c_hi = 0.0, m, c;
-        tail_sums(lo, m, c);
-        f_lo = by_count ? c : m;
-        c_lo = c;
-        if (f_lo < target) return 0u;
-        while (hi - lo > 1u && c_lo - c_hi > (double)kFilterCand) {
+
+    // Largest bit pattern t in [lo, 1] with F(t) >= target, given F(lo) = f_lo >= target and the
+    // count c_lo of the entries >= lo.  Bisection over the whole row until at most kFilterCand
+    // entries lie between the two bounds; those are compacted into LDS in index order and every
+    // wave then evaluates F at its own threshold inside the bounds (kWaves + 1 intervals per
+    // round) until one entry is left between them: that entry is the threshold.
+    auto search = [&](float target, auto by_count, uint32_t lo, float f_lo, float c_lo) -> uint32_t {
+        constexpr bool kByCount = decltype(by_count)::value;
+        uint32_t hi = kAboveOneBits;  // invariant F(lo) >= target > F(hi)
+        float f_hi = 0.f, c_hi = 0.f, m, c;
+        while (hi - lo > 1u && c_lo - c_hi > (float)kFilterCand) {
             const uint32_t mid = lo + ((hi - lo) >> 1);
-            tail_sums(mid, m, c);
-            const double f = by_count ? c : m;
+            tail_sums(mid, by_count, m, c);
+            const float f = kByCount ? c : m;
             if (f >= target) { lo = mid; f_lo = f; c_lo = c; } else { hi = mid; f_hi = f; c_hi = c; }
         }
         if (hi - lo <= 1u) return lo;
@@ -157,82 +199,115 @@ __global__ __launch_bounds__(kFilterThreads) void prob_filter_kernel(FilterLogit
         for (int i = 0; i < CH * 4; ++i)
             if (e[i] >= flo && e[i] < fhi && pos < kFilterCand) s_cand[pos++] = e[i];
         __syncthreads();
-        if (wave == 0) {
-            const int ncand = (int)(c_lo - c_hi + 0.5);
-            float cv[kFilterCand / kWave];
+        const int ncand = (int)(c_lo - c_hi + 0.5f);
+        float cv[kFilterCand / kWave];
+#pragma unroll
+        for (int q = 0; q < kFilterCand / kWave; ++q) {
+            const int idx = q * kWave + lane;
+            cv[q] = idx < ncand ? s_cand[idx] : 0.f;  // 0 < every threshold tried: never counted
+        }
+        // F(t) = f_hi + the candidates >= t.  The candidates hold a small part of the row's mass
+        // (or a count below 2^24), so fp32 is ample.
+        float n_lo = (float)ncand, n_hi = 0.f;  // candidates >= lo, >= hi
+        while (hi - lo > 1u && n_lo - n_hi > 1.5f) {
+            const uint32_t span = hi - lo;
+            auto probe = [&](int w) -> uint32_t {  // lo <= probe(w) < hi, non-decreasing in w
+                return lo + (uint32_t)(((uint64_t)(w + 1) * span) / (uint32_t)(kWaves + 1));
+            };
+            const float t = __uint_as_float(probe(wave));
+            float part = 0.f;
+            int wc = 0;
 #pragma unroll
             for (int q = 0; q < kFilterCand / kWave; ++q) {
-                const int idx = q * kWave + lane;
-                cv[q] = idx < ncand ? s_cand[idx] : 0.f;   // 0 < every threshold tried: never counted
+                const bool ge = cv[q] >= t;
+                wc += __builtin_popcountll(__builtin_amdgcn_ballot_w64(ge));
+                if (!kByCount) part += ge ? cv[q] : 0.f;
             }
-            uint32_t l2 = lo, h2 = hi;
-            while (h2 - l2 > 1u) {
-                const uint32_t mid = l2 + ((h2 - l2) >> 1);
-                const float t = __uint_as_float(mid);
-                // the candidates together hold a small part of the row's mass (or a count below
-                // 2^24), so fp32 is ample here; lane-permute reduction, fixed order
-                float part = 0.f;
-#pragma unroll
-                for (int q = 0; q < kFilterCand / kWave; ++q)
-                    part += (cv[q] >= t) ? (by_count ? 1.f : cv[q]) : 0.f;
-                part = wave_sum(part);
-                if (f_hi + (double)part >= target) l2 = mid; else h2 = mid;
+            part = kByCount ? (float)wc : wave_sum(part);
+            if (lane == 0) {
+                s_part[flip][wave] = f_hi + part;
+                s_part[flip][kWaves + wave] = (float)wc;
             }
-            if (lane == 0) s_cut = l2;
+            __syncthreads();
+            // F does not increase with t: the probes that still reach the target are the first n_ok
+            const bool ok = lane < kWaves && s_part[flip][lane < kWaves ? lane : 0] >= target;
+            const int n_ok = __builtin_popcountll(__ballot(ok));
+            const uint32_t new_lo = n_ok > 0 ? probe(n_ok - 1) : lo;
+            const uint32_t new_hi = n_ok < kWaves ? probe(n_ok) : hi;
+            if (n_ok > 0) n_lo = s_part[flip][kWaves + n_ok - 1];
+            if (n_ok < kWaves) n_hi = s_part[flip][kWaves + n_ok];
+            lo = new_lo;
+            hi = new_hi;
+            flip ^= 1;
         }
-        __syncthreads();
-        const uint32_t r = s_cut;
-        __syncthreads();
-        return r;
-    };
-    auto mass_at_least = [&](uint32_t t_bits, bool by_count) -> double {
-        double m, c;
-        tail_sums(t_bits, m, c);
-        return by_count ? c : m;
+        if (hi - lo > 1u && n_lo - n_hi > 0.5f) {
+            // one candidate c in [lo, hi): F(c) = F(lo) >= target > F(hi) = F(c + 1 ulp)
+            const float flo2 = __uint_as_float(lo), fhi2 = __uint_as_float(hi);
+            float best = 0.f;
+#pragma unroll
+            for (int q = 0; q < kFilterCand / kWave; ++q)
+                best = fmaxf(best, (cv[q] >= flo2 && cv[q] < fhi2) ? cv[q] : 0.f);
+            best = wave_max(best);
+            if (best > 0.f) lo = __float_as_uint(best);
+        }
+        return lo;
     };
 
     uint32_t cut = kMinNormalBits;  // keep every entry with e >= cut (bit pattern): all positive ones so far
-    if (a.top_k > 0) {
-        const uint32_t t = threshold((double)a.top_k, true);
-        if (t != 0u) cut = t;  // fewer than k positive entries: keep them all
+    if (npos > 0.5f) {
+        if (a.top_k > 0 && npos > (float)a.top_k) {  // no more than k positive entries: keep them all
+            cut = search((float)a.top_k, std::true_type{}, min_bits, npos, npos);
 #pragma unroll
-        for (int i = 0; i < CH * 4; ++i) e[i] = (e[i] >= __uint_as_float(cut)) ? e[i] : 0.f;
-    }
-    if (a.top_p < 1.f) {
-        const double total = mass_at_least(kMinNormalBits, false);
-        // a target that rounding could push above the total would empty the row: cap it
-        const double target = fmin((double)a.top_p * total, total);
-        const uint32_t t = threshold(target, false);
-        if (t > cut) cut = t;
+            for (int i = 0; i < CH * 4; ++i) e[i] = (e[i] >= __uint_as_float(cut)) ? e[i] : 0.f;
+            if (a.top_p < 1.f) {
+                min_bits = cut;  // every surviving entry is >= cut
+                tail_sums(cut, std::false_type{}, total, npos);
+            }
+        }
+        if (a.top_p < 1.f) {
+            // a target that rounding could push above the total would empty the row: cap it
+            const float target = fminf(a.top_p * total, total);
+            const uint32_t t = search(target, std::false_type{}, min_bits, total, npos);
+            if (t > cut) cut = t;
+        }
     }
     const float cutf = __uint_as_float(cut);
-    float nkept = 0.f;
+    int wkept = 0;
     float *orow = a.out + (int64_t)row * a.out_ld;
     float4 *o4 = reinterpret_cast<float4 *>(orow);
     // the logits are read a second time (they were not kept in registers; the row is still in
     // L2) just before the same thread overwrites them, so `out` may be `logits` itself
+    // (a lane index the compiler takes for a new value, so that the first pass's addresses and
+    // bounds are recomputed here instead of being held in registers through the search)
+    int tid_w = tid;
+    asm volatile("" : "+v"(tid_w));
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-        const int c = j * kFilterThreads + tid;
-        const float4 t = load_chunk(c);
+        const int c = j * kFilterThreads + tid_w;
+        const float4 t = load_chunk(j, tid_w);
         const float zq[4] = {t.x, t.y, t.z, t.w};
         float r[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const bool keep = e[4 * j + q] >= cutf && e[4 * j + q] > 0.f;
+            const bool keep = e[4 * j + q] >= cutf;  // cutf > 0: the dropped entries (e = 0) fail
             r[q] = keep ? zq[q] : -INFINITY;
-            nkept += keep ? 1.f : 0.f;
+            wkept += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keep));
         }
         if (c < nfull) {
-            o4[c] = make_float4(r[0], r[1], r[2], r[3]);
-        } else if (c == nfull) {
+            (o4 + j * kFilterThreads)[tid_w] = make_float4(r[0], r[1], r[2], r[3]);
+        } else if (RAGGED && c == nfull) {
             for (int q = 0; q < 3; ++q)
                 if (4 * c + q < V) orow[4 * c + q] = r[q];
         }
     }
     if (a.kept) {
-        const double n = block_sum<kFilterThreads>(nkept, s_sum);
-        if (tid == 0) a.kept[row] = (int)(n + 0.5);
+        if (lane == 0) s_woff[wave] = wkept;
+        __syncthreads();
+        if (tid == 0) {
+            int n = 0;
+            for (int w = 0; w < kWaves; ++w) n += s_woff[w];
+            a.kept[row] = n;
+        }
     }
 }
 
@@ -256,13 +331,22 @@ extern "C" int32_t rsd_filter_logits(const float *logits, int64_t ld, int32_t R,
     hipStream_t st = static_cast<hipStream_t>(stream);
     const int need = (V >> 2) + ((V & 3) ? 1 : 0);  // float4 chunks of a row, a ragged tail included
     const int chunks = (need + kFilterThreads - 1) / kFilterThreads;
+    const bool ragged = (V & 3) != 0;
+#define RSD_LAUNCH_FILTER(CH)                                                                          \
+    do {                                                                                               \
+        if (ragged)                                                                                    \
+            hipLaunchKernelGGL((prob_filter_kernel<CH, true>), dim3(R), dim3(kFilterThreads), 0, st, a);  \
+        else                                                                                           \
+            hipLaunchKernelGGL((prob_filter_kernel<CH, false>), dim3(R), dim3(kFilterThreads), 0, st, a); \
+    } while (0)
     if (chunks <= 2)
-        hipLaunchKernelGGL(prob_filter_kernel<2>, dim3(R), dim3(kFilterThreads), 0, st, a);
+        RSD_LAUNCH_FILTER(2);
     else if (chunks <= 8)
-        hipLaunchKernelGGL(prob_filter_kernel<8>, dim3(R), dim3(kFilterThreads), 0, st, a);
+        RSD_LAUNCH_FILTER(8);
     else if (chunks <= 13)
-        hipLaunchKernelGGL(prob_filter_kernel<13>, dim3(R), dim3(kFilterThreads), 0, st, a);
+        RSD_LAUNCH_FILTER(13);
     else
-        hipLaunchKernelGGL(prob_filter_kernel<16>, dim3(R), dim3(kFilterThreads), 0, st, a);
+        RSD_LAUNCH_FILTER(16);
+#undef RSD_LAUNCH_FILTER
     return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
 }

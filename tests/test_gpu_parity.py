@@ -318,7 +318,7 @@ FILTER_TOL = 1e-6   # probability mass: fp32 exponentials and sums on the GPU ag
 def _check_filtered(got, z, ref, margin, inv_t, top_k, top_p):
     """Every row: the kept set is a top set, keeps the logits unchanged, and is a valid answer up to
     FILTER_TOL of probability mass (reaches the target, and would fall short without its least probable
-    entry).  Rows that the oracle decided by a margin above FILTER_TOL must match it exactly."""
+    entries, which stay or go together when they are equally probable).  Rows that the oracle decided by a margin above FILTER_TOL must match it exactly."""
     near = 0
     for r in range(z.shape[0]):
         kept = np.isfinite(got[r])
@@ -340,7 +340,9 @@ def _check_filtered(got, z, ref, margin, inv_t, top_k, top_p):
         prob /= prob.sum()
         if top_p < 1.0:
             mass = prob[kept].sum()
-            assert mass >= top_p - FILTER_TOL and mass - prob[kept].min() < top_p + FILTER_TOL
+            least = prob[kept].min()                        # entries as probable as it stay together
+            assert mass >= top_p - FILTER_TOL
+            assert mass - prob[kept & (prob <= least * (1 + 1e-6))].sum() < top_p + FILTER_TOL
     return near
 
 
@@ -373,6 +375,40 @@ def test_filter_logits(kind, R, V, inv_t, top_k, top_p):
     # in place
     binding.filter_logits(d_in, inv_t, top_k, top_p, out=d_in)
     assert torch.equal(d_in, out)
+
+
+@pytest.mark.parametrize("V,top_k,top_p", [
+    (32000, 0, 0.9),
+    (32000, 100, 1.0),
+    (4099, 2000, 0.7),        # ragged row, both filters
+    (50272, 3000, 0.95),
+])
+def test_filter_logits_hard_rows(V, top_k, top_p):
+    """Rows that stress the threshold search: sorted values (every wave holds one value range), one
+    value repeated through the row and coarsely quantised values (tie groups larger than the candidate
+    buffer), a dominant peak, a handful of finite entries, none at all."""
+    say(f"filter_logits hard rows V={V} top_k={top_k} top_p={top_p}")
+    rng = np.random.default_rng(V + top_k)
+    base = (rng.standard_normal(V) * 3).astype(np.float32)
+    rows = [np.sort(base), np.sort(base)[::-1].copy(), np.full(V, 0.5, np.float32),
+            np.round(base * 2) / 2, base.copy(), np.full(V, -np.inf, np.float32), base.copy(),
+            np.where(np.arange(V) % 2 == 0, np.float32(1.0), np.float32(-2.0)).astype(np.float32),
+            np.full(V, -np.inf, np.float32)]
+    rows[4][:] = -np.inf
+    rows[4][[3, V // 2, V - 1]] = [0.1, 0.2, 0.1]
+    rows[6][V // 3] += 30.0
+    rows[8][V - 2] = 7.0                                           # a single finite entry
+    z = np.stack(rows).astype(np.float32)
+    ld = (V + 3) // 4 * 4
+    buf = torch.zeros((z.shape[0], ld), dtype=torch.float32)
+    buf[:, :V] = torch.from_numpy(z)
+    out, kept = binding.filter_logits(buf.to(dev())[:, :V], 1.0, top_k, top_p, return_kept=True)
+    ref, kept_ref, margin = o_pfilter.filter_logits(z, 1.0, top_k, top_p)
+    near = _check_filtered(to_np(out), z, ref, margin, 1.0, top_k, top_p)
+    say(f"  kept per row {kept_ref.tolist()}, rows decided within {FILTER_TOL} of mass: {near}")
+    assert np.array_equal(to_np(kept), np.isfinite(to_np(out)).sum(1))
+    ok = margin >= FILTER_TOL
+    assert np.array_equal(to_np(kept)[ok], kept_ref[ok])
 
 
 def test_filtered_logits_through_drafting_and_verification():
