@@ -267,20 +267,30 @@ __device__ double child_theta(const float *zt, const float *zd, float c2, int k,
     return fmin(1.0, q / p);
 }
 
-// Verify one sibling group: fills sh.g (children, scalars, thresholds).
-// All threads of the workgroup must call this.  Returns with sh.g visible to all.
-// Children of `node` in stored order: the first RSD_NODES_MAX threads test one node each,
-// wave ballots give every match its rank.  Ends with a barrier.
-__device__ __forceinline__ void scan_children(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
+// Children of `node` in stored order, into sh.g (kid, tok, K): the first RSD_NODES_MAX threads
+// test one node each, wave ballots give every match its rank.  All threads of the workgroup
+// take part; ends with a barrier.  The two halves can be called apart: fetch_candidate only
+// issues this thread's loads (its parent and token), rank_children consumes them.
+struct ChildCandidate {
+    int parent, token;
+};
+
+__device__ __forceinline__ ChildCandidate fetch_candidate(const RrsArgs &a, int b, int node, int n) {
     const int *par = a.parent + (int64_t)b * a.N;
     const int *tok = a.tokens + (int64_t)b * a.N;
-    const int j = threadIdx.x, lane = j & (kWave - 1), wave = j / kWave;
-    bool match = false;
-    int t = 0;
+    const int j = threadIdx.x;
+    ChildCandidate c{-2, 0};  // -2: not a node of this tree (a parent is >= -1)
     if (j > node && j < n) {
-        match = par[j] == node;
-        t = tok[j];
+        c.parent = par[j];
+        c.token = tok[j];
     }
+    return c;
+}
+
+__device__ __forceinline__ void rank_children(const RrsArgs &a, int node, ChildCandidate cand, GroupShared &sh) {
+    const int j = threadIdx.x, lane = j & (kWave - 1), wave = j / kWave;
+    const bool match = cand.parent == node;
+    const int t = cand.token;
     const unsigned long long mask = __ballot(match);
     if (wave < RSD_NODES_MAX / kWave && lane == 0) sh.cmask[wave] = mask;
     __syncthreads();
@@ -299,6 +309,10 @@ __device__ __forceinline__ void scan_children(const RrsArgs &a, int b, int node,
         sh.g.flags = 0;
     }
     __syncthreads();
+}
+
+__device__ __forceinline__ void scan_children(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
+    rank_children(a, node, fetch_candidate(a, b, node, n), sh);
 }
 
 template <int THREADS>
@@ -339,9 +353,6 @@ template <int CH>
 __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
     constexpr int T = kRegThreads;
     constexpr int NW = T / kWave;
-    scan_children(a, b, node, n, sh);
-    const int K = sh.g.K;
-    if (K == 0) return;
     const int tid = threadIdx.x, wave = tid / kWave;
     const bool lane0 = (tid & (kWave - 1)) == 0;
     const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
@@ -350,6 +361,26 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
     const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
     const int nchunk = a.V >> 2;
     const float c2 = a.c2;
+    // The children's lookup is requested first and both rows right after it, before the lookup
+    // is used: its dependent steps (two barriers, the children's own logits) then run under
+    // the rows' memory latency.  A node without children (the end of a path) costs one row
+    // pair that is not used.
+    const ChildCandidate cand = fetch_candidate(a, b, node, n);
+    float ut[CH * 4], ed[CH * 4];
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const int c = j * T + tid;
+        float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY), d = t;
+        if (c < nchunk) {
+            t = zt4[c];
+            d = zd4[c];
+        }
+        ut[4 * j + 0] = t.x; ut[4 * j + 1] = t.y; ut[4 * j + 2] = t.z; ut[4 * j + 3] = t.w;
+        ed[4 * j + 0] = d.x; ed[4 * j + 1] = d.y; ed[4 * j + 2] = d.z; ed[4 * j + 3] = d.w;
+    }
+    rank_children(a, node, cand, sh);
+    const int K = sh.g.K;
+    if (K == 0) return;
     // bit (4 j + e) set: this thread's register entry (j, e) is a child token
     static_assert(CH * 4 <= 128, "element mask holds 128 entries");
     uint64_t elmask[2] = {0, 0};
@@ -360,23 +391,13 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
             if (bit < 64) elmask[0] |= 1ull << bit; else elmask[1] |= 1ull << (bit - 64);
         }
     }
-
-    float ut[CH * 4], ed[CH * 4];
     float mt = -INFINITY, md = -INFINITY;
 #pragma unroll
-    for (int j = 0; j < CH; ++j) {
-        const int c = j * T + tid;
-        if (c < nchunk) {
-            const float4 t = zt4[c];
-            const float4 d = zd4[c];
-            ut[4 * j + 0] = t.x * c2; ut[4 * j + 1] = t.y * c2; ut[4 * j + 2] = t.z * c2; ut[4 * j + 3] = t.w * c2;
-            ed[4 * j + 0] = d.x * c2; ed[4 * j + 1] = d.y * c2; ed[4 * j + 2] = d.z * c2; ed[4 * j + 3] = d.w * c2;
-        } else {
-#pragma unroll
-            for (int e = 0; e < 4; ++e) { ut[4 * j + e] = -INFINITY; ed[4 * j + e] = -INFINITY; }
-        }
-#pragma unroll
-        for (int e = 0; e < 4; ++e) { mt = fmaxf(mt, ut[4 * j + e]); md = fmaxf(md, ed[4 * j + e]); }
+    for (int i = 0; i < CH * 4; ++i) {
+        ut[i] *= c2;
+        ed[i] *= c2;
+        mt = fmaxf(mt, ut[i]);
+        md = fmaxf(md, ed[i]);
     }
     // children: lane t < K reads its token's two logits (fp64 follow-up of the child tokens)
     double cu = 0.0, ce = 0.0;
@@ -629,13 +650,17 @@ __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
 template <int THREADS, int CH>
 __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
-    __shared__ int s_item;
+    __shared__ int s_item[2];
     const int count = a.wq[0];
-    for (;;) {
-        if (threadIdx.x == 0) s_item = atomicAdd(&a.wq[1], 1);
-        __syncthreads();
-        const int item = s_item;
+    if (threadIdx.x == 0) s_item[0] = atomicAdd(&a.wq[1], 1);
+    __syncthreads();
+    for (int cur = 0;; cur ^= 1) {
+        const int item = s_item[cur];
         if (item >= count) break;
+        // the item after this one is claimed now and handed over at the end of the pass, so the
+        // counter's round trip runs under this group's work
+        int next = 0;
+        if (threadIdx.x == 0) next = atomicAdd(&a.wq[1], 1);
         const int i = a.work[item];
         const int b = i / a.N, node = i - b * a.N;
         const int n = min(max(a.n_nodes[b], 1), a.N);
@@ -654,7 +679,8 @@ __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
             if ((int)threadIdx.x < sh.g.K)
                 a.theta[(int64_t)b * a.N + sh.g.kid[threadIdx.x]] = sh.g.theta[threadIdx.x];
         }
-        __syncthreads();  // sh and s_item are reused by the next item
+        if (threadIdx.x == 0) s_item[cur ^ 1] = next;
+        __syncthreads();  // sh is reused by the next item, which s_item[cur ^ 1] names
     }
 }
 
