@@ -22,7 +22,12 @@ namespace rsd {
 
 constexpr int kGroupThreads = 512;   // streaming variant (any vocabulary size)
 constexpr int kRegThreads = 512;     // register-resident variant: 2 waves per SIMD, 256 VGPRs each
-constexpr int kGroupWaves = kRegThreads / kWave;
+// resident variant with most of the draft row in LDS (larger vocabularies): 12 waves, three per
+// SIMD, so that a thread has 168 registers and nothing spills
+constexpr int kLdsThreads = 768;
+constexpr int kLdsChunks = 17;       // float4 chunks per thread: 52224 entries
+constexpr int kLdsChunksInLds = 12;  // of which in LDS: 12 * 768 * 16 B = 144 KB
+constexpr int kGroupWavesMax = 16;
 constexpr int kFinalThreads = 512;
 constexpr int kFinalSplitsMax = 8;
 
@@ -149,9 +154,9 @@ __device__ __forceinline__ uint64_t child_chunk_mask(const GroupRec &g, int c_lo
 
 struct GroupShared {
     GroupRec g;
-    MaxSum ms[kGroupWaves];
-    double red[kGroupWaves];
-    double red2[kGroupWaves];
+    MaxSum ms[kGroupWavesMax];
+    double red[kGroupWavesMax];
+    double red2[kGroupWavesMax];
     double ce[RSD_K_MAX];   // draft exponentials of the child tokens (fp64)
     double isk[RSD_K_MAX];  // 1 / s_k in fp64
     unsigned long long cmask[RSD_NODES_MAX / kWave];  // per-wave ballots of the child scan
@@ -343,16 +348,20 @@ __device__ void process_group(const RrsArgs &a, int b, int node, int n, GroupSha
 }
 
 
-// Register-resident variant for vocabularies up to kRegThreads * 4 * CH entries: both logit
-// rows are read from memory once; each thread keeps its share of the target-side value
-// u(x) (q^(k) = u / A_k) and of the draft exponentials e_d(x) in registers, so a stage is
+// Resident variant for vocabularies up to T * 4 * CH entries: both logit rows are read from
+// memory once; each thread keeps its share of the target-side value u(x) (q^(k) = u / A_k) in
+// registers and its share of the draft exponentials e_d(x) in registers (chunks CL..CH-1) and,
+// for the larger vocabularies, in LDS (chunks 0..CL-1, a slot of its own per thread and chunk,
+// so no barrier guards them).  A stage is
 //     S = sum_x max(u - gamma_k * e_d, 0);   u <- max(u - gamma_k * e_d, 0);   A_{k+1} = S
 // with gamma_k = A_k / s_k: three to five ALU operations per entry, one wave reduction and a
 // single barrier.  Every thread carries the scalars; lane t < K follows child token t in fp64.
-template <int CH>
+template <int T, int CH, int CL>
 __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
-    constexpr int T = kRegThreads;
     constexpr int NW = T / kWave;
+    constexpr int CR = CH - CL;  // chunks of e_d held in registers
+    static_assert(NW <= kGroupWavesMax && CL >= 0 && CL < CH, "");
+    __shared__ float4 s_ed[CL > 0 ? CL * T : 1];
     const int tid = threadIdx.x, wave = tid / kWave;
     const bool lane0 = (tid & (kWave - 1)) == 0;
     const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
@@ -361,27 +370,44 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
     const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
     const int nchunk = a.V >> 2;
     const float c2 = a.c2;
-    // The children's lookup is requested first and both rows right after it, before the lookup
+    const float4 ninf4 = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    // The children's lookup is requested first and the rows right after it, before the lookup
     // is used: its dependent steps (two barriers, the children's own logits) then run under
     // the rows' memory latency.  A node without children (the end of a path) costs one row
     // pair that is not used.
     const ChildCandidate cand = fetch_candidate(a, b, node, n);
-    float ut[CH * 4], ed[CH * 4];
+    float ut[CH * 4], edr[CR * 4];
+    // chunk j of e_d, wherever it lives (j is a constant once the loops are unrolled)
+    auto ed_get = [&](int j) -> float4 {
+        if (j < CL) return s_ed[j * T + tid];
+        const int r = j < CL ? 0 : 4 * (j - CL);
+        return make_float4(edr[r], edr[r + 1], edr[r + 2], edr[r + 3]);
+    };
+    auto ed_put = [&](int j, float4 v) {
+        if (j < CL) {
+            s_ed[j * T + tid] = v;
+        } else {
+            const int r = j < CL ? 0 : 4 * (j - CL);
+            edr[r] = v.x; edr[r + 1] = v.y; edr[r + 2] = v.z; edr[r + 3] = v.w;
+        }
+    };
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
         const int c = j * T + tid;
-        float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY), d = t;
+        // (a uniform base per chunk and one lane offset for all of them; the loads stay inside
+        // an `if`, which keeps them 16 bytes wide)
+        float4 t = ninf4, d = ninf4;
         if (c < nchunk) {
-            t = zt4[c];
-            d = zd4[c];
+            t = (zt4 + j * T)[tid];
+            if (j >= CL) d = (zd4 + j * T)[tid];
         }
         ut[4 * j + 0] = t.x; ut[4 * j + 1] = t.y; ut[4 * j + 2] = t.z; ut[4 * j + 3] = t.w;
-        ed[4 * j + 0] = d.x; ed[4 * j + 1] = d.y; ed[4 * j + 2] = d.z; ed[4 * j + 3] = d.w;
+        if (j >= CL) ed_put(j, d);
     }
     rank_children(a, node, cand, sh);
     const int K = sh.g.K;
     if (K == 0) return;
-    // bit (4 j + e) set: this thread's register entry (j, e) is a child token
+    // bit (4 j + e) set: this thread's entry (j, e) is a child token
     static_assert(CH * 4 <= 128, "element mask holds 128 entries");
     uint64_t elmask[2] = {0, 0};
     for (int i = 0; i < K; ++i) {
@@ -392,12 +418,26 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
         }
     }
     float mt = -INFINITY, md = -INFINITY;
+    // the LDS part of the draft row goes from memory to its slots now (scaled), six chunks in
+    // flight at a time: the registers are full of the target row
+#pragma unroll 6
+    for (int j = 0; j < CL; ++j) {
+        const int c = j * T + tid;
+        float4 d = ninf4;
+        if (c < nchunk) d = (zd4 + j * T)[tid];
+        d.x *= c2; d.y *= c2; d.z *= c2; d.w *= c2;
+        md = fmaxf(md, fmaxf(fmaxf(d.x, d.y), fmaxf(d.z, d.w)));
+        s_ed[j * T + tid] = d;
+    }
 #pragma unroll
     for (int i = 0; i < CH * 4; ++i) {
         ut[i] *= c2;
-        ed[i] *= c2;
         mt = fmaxf(mt, ut[i]);
-        md = fmaxf(md, ed[i]);
+    }
+#pragma unroll
+    for (int i = 0; i < CR * 4; ++i) {
+        edr[i] *= c2;
+        md = fmaxf(md, edr[i]);
     }
     // children: lane t < K reads its token's two logits (fp64 follow-up of the child tokens)
     double cu = 0.0, ce = 0.0;
@@ -417,16 +457,20 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
     float st = 0.f, sd = 0.f;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
+        float4 d = ed_get(j);
+        d.x = __builtin_amdgcn_exp2f(d.x - md_use);
+        d.y = __builtin_amdgcn_exp2f(d.y - md_use);
+        d.z = __builtin_amdgcn_exp2f(d.z - md_use);
+        d.w = __builtin_amdgcn_exp2f(d.w - md_use);
+        ed_put(j, d);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            ut[4 * j + e] = __builtin_amdgcn_exp2f(ut[4 * j + e] - mt_use);
-            ed[4 * j + e] = __builtin_amdgcn_exp2f(ed[4 * j + e] - md_use);
-        }
+        for (int e = 0; e < 4; ++e) ut[4 * j + e] = __builtin_amdgcn_exp2f(ut[4 * j + e] - mt_use);
         st += (ut[4 * j] + ut[4 * j + 1]) + (ut[4 * j + 2] + ut[4 * j + 3]);
+        const float dv[4] = {d.x, d.y, d.z, d.w};
         float dsum[4];
 #pragma unroll
         for (int e = 0; e < 4; ++e)
-            dsum[e] = ((elmask[(4 * j + e) >> 6] >> ((4 * j + e) & 63)) & 1ull) ? 0.f : ed[4 * j + e];
+            dsum[e] = ((elmask[(4 * j + e) >> 6] >> ((4 * j + e) & 63)) & 1ull) ? 0.f : dv[e];
         sd += (dsum[0] + dsum[1]) + (dsum[2] + dsum[3]);
     }
     st = wave_sum(st);
@@ -471,7 +515,13 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
         const float gamma = (float)(inv_sk * A);
         float part = 0.f;
 #pragma unroll
-        for (int i = 0; i < CH * 4; ++i) part += fmaxf(fmaf(-gamma, ed[i], ut[i]), 0.f);
+        for (int j = 0; j < CH; ++j) {
+            const float4 d = ed_get(j);
+            part += fmaxf(fmaf(-gamma, d.x, ut[4 * j + 0]), 0.f);
+            part += fmaxf(fmaf(-gamma, d.y, ut[4 * j + 1]), 0.f);
+            part += fmaxf(fmaf(-gamma, d.z, ut[4 * j + 2]), 0.f);
+            part += fmaxf(fmaf(-gamma, d.w, ut[4 * j + 3]), 0.f);
+        }
         part = wave_sum(part);
         double *red = (k & 1) ? sh.red2 : sh.red;
         if (lane0) red[wave] = (double)part;
@@ -482,7 +532,13 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
         const bool ok = S > 0.0 && isfinite(S);
         if (ok) {
 #pragma unroll
-            for (int i = 0; i < CH * 4; ++i) ut[i] = fmaxf(fmaf(-gamma, ed[i], ut[i]), 0.f);
+            for (int j = 0; j < CH; ++j) {
+                const float4 d = ed_get(j);
+                ut[4 * j + 0] = fmaxf(fmaf(-gamma, d.x, ut[4 * j + 0]), 0.f);
+                ut[4 * j + 1] = fmaxf(fmaf(-gamma, d.y, ut[4 * j + 1]), 0.f);
+                ut[4 * j + 2] = fmaxf(fmaf(-gamma, d.z, ut[4 * j + 2]), 0.f);
+                ut[4 * j + 3] = fmaxf(fmaf(-gamma, d.w, ut[4 * j + 3]), 0.f);
+            }
             if (tid < K) cu = fmax(cu - (double)gamma * ce, 0.0);
             if (tid == 0) sh.g.inv_S[k] = (float)(A / S);
             A = S;
@@ -496,18 +552,29 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
         if ((elmask[0] | elmask[1]) != 0ull) {
             const int xk = sh.g.tok[k], ck = xk >> 2;
             const int target = (ck % T == tid) ? (((ck / T) << 2) | (xk & 3)) : -1;
+            if (target >= 0) {
 #pragma unroll
-            for (int i = 0; i < CH * 4; ++i)
-                if (i == target) ed[i] = 0.f;
+                for (int j = 0; j < CH; ++j) {
+                    if ((target >> 2) == j) {
+                        float4 d = ed_get(j);
+                        if ((target & 3) == 0) d.x = 0.f;
+                        if ((target & 3) == 1) d.y = 0.f;
+                        if ((target & 3) == 2) d.z = 0.f;
+                        if ((target & 3) == 3) d.w = 0.f;
+                        ed_put(j, d);
+                    }
+                }
+            }
         }
     }
     __syncthreads();
 }
 
-template <int THREADS, int CH>
+// CH == 0: streaming variant; else the resident variant with CH chunks per thread, CL of them in LDS
+template <int THREADS, int CH, int CL>
 __device__ __forceinline__ void verify_group(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
     if constexpr (CH > 0)
-        process_group_reg<CH>(a, b, node, n, sh);
+        process_group_reg<THREADS, CH, CL>(a, b, node, n, sh);
     else
         process_group<THREADS>(a, b, node, n, sh);
 }
@@ -647,7 +714,7 @@ __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
 // until it is empty (every workgroup leaves the loop once the shared counter passes the
 // item count).
 // ---------------------------------------------------------------------------
-template <int THREADS, int CH>
+template <int THREADS, int CH, int CL>
 __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
     __shared__ int s_item[2];
@@ -664,7 +731,7 @@ __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
         const int i = a.work[item];
         const int b = i / a.N, node = i - b * a.N;
         const int n = min(max(a.n_nodes[b], 1), a.N);
-        verify_group<THREADS, CH>(a, b, node, n, sh);
+        verify_group<THREADS, CH, CL>(a, b, node, n, sh);
         GroupRec *out = a.rec + i;
         const int words = sizeof(GroupRec) / 4;
         const uint32_t *src = reinterpret_cast<const uint32_t *>(&sh.g);
@@ -809,7 +876,7 @@ __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
 // PATH mode: one persistent workgroup per sequence verifies only the groups on
 // the accepted path, then draws the last token.
 // ---------------------------------------------------------------------------
-template <int THREADS, int CH>
+template <int THREADS, int CH, int CL>
 __global__ __launch_bounds__(THREADS) void rrs_path_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
     __shared__ float s_v[THREADS / kWave];
@@ -836,7 +903,7 @@ __global__ __launch_bounds__(THREADS) void rrs_path_kernel(RrsArgs a) {
     __syncthreads();
     for (int guard = 0; guard < a.N; ++guard) {
         const int cur = sh.cur;
-        verify_group<THREADS, CH>(a, b, cur, n, sh);
+        verify_group<THREADS, CH, CL>(a, b, cur, n, sh);
         const int K = sh.g.K;
         if (K == 0) break;
         if (tid == 0) {
@@ -947,14 +1014,19 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
     a.work = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * N_max * 4, 256);
     a.wq = reinterpret_cast<int *>(ws + off);
     hipStream_t st = (hipStream_t)stream;
-    // rows of up to 32768 entries fit the register-resident variant (128 data registers per
-    // thread); a 25-chunk variant for 50k vocabularies spills and is slower than streaming
+    // Rows of up to 32768 entries fit the register-resident variant (128 data registers per
+    // thread); up to 52224 entries (the 50k vocabularies) the variant that keeps most of the
+    // draft row in LDS; beyond that the rows are streamed from memory at every stage.
     const bool reg16 = V <= kRegThreads * 4 * 16;
+    const bool lds13 = !reg16 && V <= kLdsThreads * 4 * kLdsChunks;
     if (mode == RSD_MODE_PATH) {
         if (reg16)
-            hipLaunchKernelGGL((rrs_path_kernel<kRegThreads, 16>), dim3(B), dim3(kRegThreads), 0, st, a);
+            hipLaunchKernelGGL((rrs_path_kernel<kRegThreads, 16, 0>), dim3(B), dim3(kRegThreads), 0, st, a);
+        else if (lds13)
+            hipLaunchKernelGGL((rrs_path_kernel<kLdsThreads, kLdsChunks, kLdsChunksInLds>), dim3(B),
+                               dim3(kLdsThreads), 0, st, a);
         else
-            hipLaunchKernelGGL((rrs_path_kernel<kGroupThreads, 0>), dim3(B), dim3(kGroupThreads), 0, st, a);
+            hipLaunchKernelGGL((rrs_path_kernel<kGroupThreads, 0, 0>), dim3(B), dim3(kGroupThreads), 0, st, a);
     } else {
         static int n_cu = 0;
         if (n_cu == 0) {
@@ -968,9 +1040,12 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
         const int grid = (int)(items_max < n_cu ? items_max : n_cu);
         hipLaunchKernelGGL(rrs_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a);
         if (reg16)
-            hipLaunchKernelGGL((rrs_group_kernel<kRegThreads, 16>), dim3(grid), dim3(kRegThreads), 0, st, a);
+            hipLaunchKernelGGL((rrs_group_kernel<kRegThreads, 16, 0>), dim3(grid), dim3(kRegThreads), 0, st, a);
+        else if (lds13)
+            hipLaunchKernelGGL((rrs_group_kernel<kLdsThreads, kLdsChunks, kLdsChunksInLds>), dim3(grid),
+                               dim3(kLdsThreads), 0, st, a);
         else
-            hipLaunchKernelGGL((rrs_group_kernel<kGroupThreads, 0>), dim3(2 * grid), dim3(kGroupThreads), 0, st, a);
+            hipLaunchKernelGGL((rrs_group_kernel<kGroupThreads, 0, 0>), dim3(2 * grid), dim3(kGroupThreads), 0, st, a);
         hipLaunchKernelGGL(rrs_walk_kernel, dim3(B), dim3(kWave), 0, st, a);
         // enough workgroups to fill the chip, but no more: every split costs two device-wide fences
         int fsplits = 256 / (B > 0 ? B : 1);
