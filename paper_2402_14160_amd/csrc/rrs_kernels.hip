@@ -20,6 +20,9 @@
 
 namespace rsd {
 
+typedef __attribute__((address_space(3))) void lds_void;
+typedef __attribute__((address_space(1))) const void global_void;
+
 constexpr int kGroupThreads = 512;   // streaming variant (any vocabulary size)
 constexpr int kRegThreads = 512;     // register-resident variant: 2 waves per SIMD, 256 VGPRs each
 // resident variant with most of the draft row in LDS (larger vocabularies): 12 waves, three per
@@ -74,8 +77,8 @@ struct RrsArgs {
     int *fnode;                 // [B]
     uint32_t *fflags;           // [B]
     int *kcount;                // [B, N] number of children of every node
-    int *work;                  // [B, N] non-leaf nodes (b * N + node), most children first
-    int *wq;                    // [0] number of work items, [1] next item to take
+    int2 *work;                 // [B, N] non-leaf nodes {b * N + node, nodes of the tree}, most children first
+    int *wq;                    // [0] number of work items
 };
 
 __device__ __forceinline__ int removal_stage(int x, const int *tok, int K) {
@@ -157,8 +160,10 @@ struct GroupShared {
     MaxSum ms[kGroupWavesMax];
     double red[kGroupWavesMax];
     double red2[kGroupWavesMax];
+    float czt[RSD_K_MAX];   // raw target / draft logits of the child tokens (resident variant)
+    float czd[RSD_K_MAX];
     double ce[RSD_K_MAX];   // draft exponentials of the child tokens (fp64)
-    double isk[RSD_K_MAX];  // 1 / s_k in fp64
+    double sred[2][kGroupWavesMax];  // stage sums of the resident variant, alternating
     unsigned long long cmask[RSD_NODES_MAX / kWave];  // per-wave ballots of the child scan
     int cur;
     int done;
@@ -274,17 +279,18 @@ __device__ double child_theta(const float *zt, const float *zd, float c2, int k,
 
 // Children of `node` in stored order, into sh.g (kid, tok, K): the first RSD_NODES_MAX threads
 // test one node each, wave ballots give every match its rank.  All threads of the workgroup
-// take part; ends with a barrier.  The two halves can be called apart: fetch_candidate only
-// issues this thread's loads (its parent and token), rank_children consumes them.
+// take part; ends with a barrier.  The halves can be called apart: fetch_candidate only issues
+// this thread's loads (its parent and token), fetch_child_logits the two logits of its token
+// when it is a child (sh.czt / sh.czd then hold them by rank), rank_children consumes them.
 struct ChildCandidate {
     int parent, token;
+    float zt, zd;
 };
 
-__device__ __forceinline__ ChildCandidate fetch_candidate(const RrsArgs &a, int b, int node, int n) {
+__device__ __forceinline__ ChildCandidate fetch_candidate(const RrsArgs &a, int b, int node, int n, int j) {
     const int *par = a.parent + (int64_t)b * a.N;
     const int *tok = a.tokens + (int64_t)b * a.N;
-    const int j = threadIdx.x;
-    ChildCandidate c{-2, 0};  // -2: not a node of this tree (a parent is >= -1)
+    ChildCandidate c{-2, 0, 0.f, 0.f};  // -2: not a node of this tree (a parent is >= -1)
     if (j > node && j < n) {
         c.parent = par[j];
         c.token = tok[j];
@@ -292,8 +298,19 @@ __device__ __forceinline__ ChildCandidate fetch_candidate(const RrsArgs &a, int 
     return c;
 }
 
-__device__ __forceinline__ void rank_children(const RrsArgs &a, int node, ChildCandidate cand, GroupShared &sh) {
-    const int j = threadIdx.x, lane = j & (kWave - 1), wave = j / kWave;
+// (the first use of the candidate: clamps its token so that it never indexes outside the row)
+__device__ __forceinline__ void fetch_child_logits(const float *zt, const float *zd, int V, int node,
+                                                   ChildCandidate &c) {
+    c.token = min(max(c.token, 0), V - 1);
+    if (c.parent == node) {
+        c.zt = zt[c.token];
+        c.zd = zd[c.token];
+    }
+}
+
+__device__ __forceinline__ void rank_children(const RrsArgs &a, int node, ChildCandidate cand, GroupShared &sh,
+                                              int j) {
+    const int lane = j & (kWave - 1), wave = j / kWave;
     const bool match = cand.parent == node;
     const int t = cand.token;
     const unsigned long long mask = __ballot(match);
@@ -304,7 +321,9 @@ __device__ __forceinline__ void rank_children(const RrsArgs &a, int node, ChildC
         for (int w = 0; w < wave; ++w) rank += __popcll(sh.cmask[w]);
         if (rank < RSD_K_MAX) {
             sh.g.kid[rank] = j;
-            sh.g.tok[rank] = min(max(t, 0), a.V - 1);  // never index outside the row
+            sh.g.tok[rank] = t;
+            sh.czt[rank] = cand.zt;
+            sh.czd[rank] = cand.zd;
         }
     }
     if (j == 0) {
@@ -317,7 +336,9 @@ __device__ __forceinline__ void rank_children(const RrsArgs &a, int node, ChildC
 }
 
 __device__ __forceinline__ void scan_children(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
-    rank_children(a, node, fetch_candidate(a, b, node, n), sh);
+    ChildCandidate c = fetch_candidate(a, b, node, n, threadIdx.x);
+    c.token = min(max(c.token, 0), a.V - 1);
+    rank_children(a, node, c, sh, threadIdx.x);
 }
 
 template <int THREADS>
@@ -362,7 +383,12 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
     constexpr int CR = CH - CL;  // chunks of e_d held in registers
     static_assert(NW <= kGroupWavesMax && CL >= 0 && CL < CH, "");
     __shared__ float4 s_ed[CL > 0 ? CL * T : 1];
-    const int tid = threadIdx.x, wave = tid / kWave;
+    // (a copy of the thread index that the compiler takes for a new value in every call: what
+    // derives from it -- chunk addresses, LDS slots, lane masks -- is then worked out here, next
+    // to its use, instead of being kept in registers from one group to the next)
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int wave = tid / kWave;
     const bool lane0 = (tid & (kWave - 1)) == 0;
     const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
     const float *zd = a.zd + ((int64_t)b * a.N + node) * a.V;
@@ -370,12 +396,14 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
     const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
     const int nchunk = a.V >> 2;
     const float c2 = a.c2;
-    const float4 ninf4 = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
+    const int last = nchunk - 1;  // the caller checks V >= 4
     // The children's lookup is requested first and the rows right after it, before the lookup
-    // is used: its dependent steps (two barriers, the children's own logits) then run under
-    // the rows' memory latency.  A node without children (the end of a path) costs one row
-    // pair that is not used.
-    const ChildCandidate cand = fetch_candidate(a, b, node, n);
+    // is used: its dependent steps (the children's own logits, two barriers) then run under
+    // the rows' memory latency.  Every row load is unconditional (a chunk past the end of the
+    // row reads the row's last chunk instead and is set to -inf when it is scaled), so that
+    // the loads form one straight line and a wait can name exactly the loads it needs.  A node
+    // without children (the end of a path) costs one row pair that is not used.
+    ChildCandidate cand = fetch_candidate(a, b, node, n, tid);
     float ut[CH * 4], edr[CR * 4];
     // chunk j of e_d, wherever it lives (j is a constant once the loops are unrolled)
     auto ed_get = [&](int j) -> float4 {
@@ -393,18 +421,74 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
     };
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-        const int c = j * T + tid;
-        // (a uniform base per chunk and one lane offset for all of them; the loads stay inside
-        // an `if`, which keeps them 16 bytes wide)
-        float4 t = ninf4, d = ninf4;
-        if (c < nchunk) {
-            t = (zt4 + j * T)[tid];
-            if (j >= CL) d = (zd4 + j * T)[tid];
-        }
+        const int c = min(j * T + tid, last);
+        const float4 t = zt4[c];
         ut[4 * j + 0] = t.x; ut[4 * j + 1] = t.y; ut[4 * j + 2] = t.z; ut[4 * j + 3] = t.w;
-        if (j >= CL) ed_put(j, d);
+        if (j >= CL) ed_put(j, zd4[c]);
     }
-    rank_children(a, node, cand, sh);
+    // (the candidate is consumed from here on: its wait and the children's own logit loads come
+    // after every row load has been issued)
+    asm volatile("" : "+v"(cand.parent), "+v"(cand.token));
+    fetch_child_logits(zt, zd, a.V, node, cand);
+    // chunks 0..CL-1 of the draft row go from memory straight into this thread's LDS slots (no
+    // registers, raw logits; 64 lanes x 16 bytes land contiguously, which is the slot layout;
+    // issued last, so that the wait above counts register loads only)
+    if constexpr (CL > 0) {
+#pragma unroll
+        for (int j = 0; j < CL; ++j)
+            __builtin_amdgcn_global_load_lds((global_void *)(zd4 + min(j * T + tid, last)),
+                                             (lds_void *)(s_ed + j * T + wave * kWave), 16, 0, 0);
+    }
+    // The row maxima and the children's ranks share their barriers: every wave first reduces
+    // its part of the two rows (scaled in place) and takes the ballot of its candidates, then
+    // one barrier publishes both, and the ranks are written while the maxima are combined.
+    float mt = -INFINITY, md = -INFINITY;
+    // the LDS part of the draft row: wait for this wave's memory-to-LDS loads (the slots are the
+    // wave's own, so no barrier)
+    if constexpr (CL > 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    // scaling: x * c2 + 0 for a chunk of the row, x * c2 - inf = -inf for a chunk past its end
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const float bias = (j * T + tid <= last) ? 0.f : -INFINITY;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            ut[4 * j + e] = fmaf(ut[4 * j + e], c2, bias);
+            mt = fmaxf(mt, ut[4 * j + e]);
+        }
+        float4 d = ed_get(j);
+        d.x = fmaf(d.x, c2, bias); d.y = fmaf(d.y, c2, bias); d.z = fmaf(d.z, c2, bias); d.w = fmaf(d.w, c2, bias);
+        md = fmaxf(md, fmaxf(fmaxf(d.x, d.y), fmaxf(d.z, d.w)));
+        ed_put(j, d);
+    }
+    mt = wave_max(mt);
+    md = wave_max(md);
+    const int lane = tid & (kWave - 1);
+    const bool match = cand.parent == node;
+    const unsigned long long cmask = __ballot(match);
+    if (lane0) {
+        sh.ms[wave] = MaxSum{mt, md};
+        if (wave < RSD_NODES_MAX / kWave) sh.cmask[wave] = cmask;
+    }
+    __syncthreads();
+    if (match) {
+        int rank = __popcll(cmask & ((1ull << lane) - 1ull));
+        for (int w = 0; w < wave; ++w) rank += __popcll(sh.cmask[w]);
+        if (rank < RSD_K_MAX) {
+            sh.g.kid[rank] = tid;
+            sh.g.tok[rank] = cand.token;
+            sh.czt[rank] = cand.zt;
+            sh.czd[rank] = cand.zd;
+        }
+    }
+    if (tid == 0) {
+        int total = 0;
+        for (int w = 0; w < RSD_NODES_MAX / kWave; ++w) total += __popcll(sh.cmask[w]);
+        sh.g.K = min(total, RSD_K_MAX);
+        sh.g.flags = 0;
+    }
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { mt = fmaxf(mt, sh.ms[w].m); md = fmaxf(md, sh.ms[w].s); }
+    __syncthreads();
     const int K = sh.g.K;
     if (K == 0) return;
     // bit (4 j + e) set: this thread's entry (j, e) is a child token
@@ -417,41 +501,12 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
             if (bit < 64) elmask[0] |= 1ull << bit; else elmask[1] |= 1ull << (bit - 64);
         }
     }
-    float mt = -INFINITY, md = -INFINITY;
-    // the LDS part of the draft row goes from memory to its slots now (scaled), six chunks in
-    // flight at a time: the registers are full of the target row
-#pragma unroll 6
-    for (int j = 0; j < CL; ++j) {
-        const int c = j * T + tid;
-        float4 d = ninf4;
-        if (c < nchunk) d = (zd4 + j * T)[tid];
-        d.x *= c2; d.y *= c2; d.z *= c2; d.w *= c2;
-        md = fmaxf(md, fmaxf(fmaxf(d.x, d.y), fmaxf(d.z, d.w)));
-        s_ed[j * T + tid] = d;
-    }
-#pragma unroll
-    for (int i = 0; i < CH * 4; ++i) {
-        ut[i] *= c2;
-        mt = fmaxf(mt, ut[i]);
-    }
-#pragma unroll
-    for (int i = 0; i < CR * 4; ++i) {
-        edr[i] *= c2;
-        md = fmaxf(md, edr[i]);
-    }
-    // children: lane t < K reads its token's two logits (fp64 follow-up of the child tokens)
+    // children: lane t < K follows its token's two logits in fp64
     double cu = 0.0, ce = 0.0;
     if (tid < K) {
-        cu = (double)zt[sh.g.tok[tid]] * (double)c2;
-        ce = (double)zd[sh.g.tok[tid]] * (double)c2;
+        cu = (double)sh.czt[tid] * (double)c2;
+        ce = (double)sh.czd[tid] * (double)c2;
     }
-    // row maxima
-    mt = wave_max(mt);
-    md = wave_max(md);
-    if (lane0) sh.ms[wave] = MaxSum{mt, md};
-    __syncthreads();
-#pragma unroll
-    for (int w = 0; w < NW; ++w) { mt = fmaxf(mt, sh.ms[w].m); md = fmaxf(md, sh.ms[w].s); }
     const float mt_use = (mt == -INFINITY) ? 0.f : mt, md_use = (md == -INFINITY) ? 0.f : md;
     // exponentials in place; the draft sum leaves out every child token
     float st = 0.f, sd = 0.f;
@@ -488,12 +543,13 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
     double St = 0.0, Sd = 0.0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) { St += sh.red[w]; Sd += sh.red2[w]; }
-    // draft mass still available at stage k: the rest plus the children not yet removed
+    // draft mass still available at stage k: the rest plus the children not yet removed.  Lane
+    // k writes 1 / s_k into the record; the stage loop below works the same number out in every
+    // thread (same order of additions), so no barrier stands between the two.
     if (tid < RSD_K_MAX) {
         double s = Sd;
         for (int i = K - 1; i >= tid; --i) s += sh.ce[i];
         const double inv = (tid < K) ? 1.0 / s : 0.0;
-        sh.isk[tid] = inv;
         sh.g.inv_s[tid] = (float)inv;
         sh.g.inv_S[tid] = 1.f;
         if (tid == 0) {
@@ -503,10 +559,11 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
             if (!(St > 0.0) || !isfinite(St) || !(s > 0.0) || !isfinite(s)) sh.g.flags |= RSD_FLAG_NONFINITE;
         }
     }
-    __syncthreads();
     double A = St;  // q^(k) = u / A
     for (int k = 0; k < K; ++k) {
-        const double inv_sk = sh.isk[k];
+        double s_k = Sd;
+        for (int i = K - 1; i >= k; --i) s_k += sh.ce[i];
+        const double inv_sk = 1.0 / s_k;
         if (tid == k) {  // threshold of child k (Eq. (3))
             const double p = ce * inv_sk;
             sh.g.theta[k] = (p > 0.0) ? (float)fmin(1.0, cu / (A * p)) : 1.f;
@@ -523,7 +580,7 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
             part += fmaxf(fmaf(-gamma, d.w, ut[4 * j + 3]), 0.f);
         }
         part = wave_sum(part);
-        double *red = (k & 1) ? sh.red2 : sh.red;
+        double *red = sh.sred[k & 1];
         if (lane0) red[wave] = (double)part;
         __syncthreads();
         double S = 0.0;
@@ -673,10 +730,6 @@ __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
     int *cnt = in_lds ? s_k : a.kcount;
     for (int i = tid; i < total; i += kPlanThreads) cnt[i] = 0;
     if (tid <= RSD_K_MAX) hist[tid] = 0;
-    if (tid == 0) {
-        a.wq[0] = 0;
-        a.wq[1] = 0;
-    }
     __syncthreads();
     for (int i = tid; i < total; i += kPlanThreads) {
         const int b = i / a.N, j = i - b * a.N;
@@ -705,32 +758,39 @@ __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
     __syncthreads();
     for (int i = tid; i < total; i += kPlanThreads) {
         const int k = min(cnt[i], RSD_K_MAX);
-        if (k > 0) a.work[atomicAdd(&offs[k], 1)] = i;
+        if (k > 0) {
+            const int b = i / a.N;
+            a.work[atomicAdd(&offs[k], 1)] = make_int2(i, min(max(a.n_nodes[b], 1), a.N));
+        }
     }
 }
 
 // ---------------------------------------------------------------------------
-// ALL_GROUPS, kernel 1: persistent workgroups take sibling groups from the work list
-// until it is empty (every workgroup leaves the loop once the shared counter passes the
-// item count).
+// ALL_GROUPS, kernel 1: persistent workgroups go through the work list (largest groups
+// first) in rounds of gridDim.x items, forwards in even rounds and backwards in odd ones, so
+// that a workgroup that drew a large group in one round draws a small one in the next.  The
+// assignment is static: the next item's entry is read while the current group is verified.
 // ---------------------------------------------------------------------------
 template <int THREADS, int CH, int CL>
 __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
-    __shared__ int s_item[2];
     const int count = a.wq[0];
-    if (threadIdx.x == 0) s_item[0] = atomicAdd(&a.wq[1], 1);
-    __syncthreads();
-    for (int cur = 0;; cur ^= 1) {
-        const int item = s_item[cur];
-        if (item >= count) break;
-        // the item after this one is claimed now and handed over at the end of the pass, so the
-        // counter's round trip runs under this group's work
-        int next = 0;
-        if (threadIdx.x == 0) next = atomicAdd(&a.wq[1], 1);
-        const int i = a.work[item];
+    const int G = gridDim.x, g = blockIdx.x;
+    auto item_of_round = [&](int r) { return r * G + ((r & 1) ? G - 1 - g : g); };
+    // (every lane reads the same entry through an offset the compiler cannot see is zero: the
+    // value then stays in a vector register, and its wait at the first use, one round later)
+    int lane_zero = 0;
+    asm volatile("" : "+v"(lane_zero));
+    int idx = item_of_round(0);
+    int2 ent = make_int2(0, 1);
+    if (idx < count) ent = a.work[idx + lane_zero];
+    for (int r = 0; idx < count; ++r) {
+        const int i = __builtin_amdgcn_readfirstlane(ent.x), n = __builtin_amdgcn_readfirstlane(ent.y);
+        const int nidx = item_of_round(r + 1);
+        // (an entry past the end of the list is never used: any entry will do, and the load
+        // stays unconditional)
+        int2 nent = a.work[min(nidx, count - 1) + lane_zero];
         const int b = i / a.N, node = i - b * a.N;
-        const int n = min(max(a.n_nodes[b], 1), a.N);
         verify_group<THREADS, CH, CL>(a, b, node, n, sh);
         GroupRec *out = a.rec + i;
         const int words = sizeof(GroupRec) / 4;
@@ -746,8 +806,9 @@ __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
             if ((int)threadIdx.x < sh.g.K)
                 a.theta[(int64_t)b * a.N + sh.g.kid[threadIdx.x]] = sh.g.theta[threadIdx.x];
         }
-        if (threadIdx.x == 0) s_item[cur ^ 1] = next;
-        __syncthreads();  // sh is reused by the next item, which s_item[cur ^ 1] names
+        __syncthreads();  // sh is reused by the next item
+        ent = nent;
+        idx = nidx;
     }
 }
 
@@ -972,7 +1033,7 @@ using namespace rsd;
 extern "C" size_t rsd_recursive_reject_workspace_bytes(int32_t B, int32_t N_max, int32_t) {
     if (B <= 0 || N_max <= 0) return 0;
     return align_up((size_t)B * N_max * sizeof(GroupRec), 256) + align_up((size_t)B * 16, 256) +
-           3 * align_up((size_t)B * 4, 256) + 2 * align_up((size_t)B * N_max * 4, 256) + 256;
+           3 * align_up((size_t)B * 4, 256) + 3 * align_up((size_t)B * N_max * 4, 256) + 256;
 }
 
 extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *target_logits,
@@ -1011,7 +1072,7 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
     a.fnode = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * 4, 256);
     a.fflags = reinterpret_cast<uint32_t *>(ws + off); off += align_up((size_t)B * 4, 256);
     a.kcount = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * N_max * 4, 256);
-    a.work = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * N_max * 4, 256);
+    a.work = reinterpret_cast<int2 *>(ws + off); off += 2 * align_up((size_t)B * N_max * 4, 256);
     a.wq = reinterpret_cast<int *>(ws + off);
     hipStream_t st = (hipStream_t)stream;
     // Rows of up to 32768 entries fit the register-resident variant (128 data registers per
