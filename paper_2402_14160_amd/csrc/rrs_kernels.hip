@@ -74,8 +74,6 @@ struct RrsArgs {
     GroupRec *rec;              // [B, N]
     unsigned long long *fkey;   // [B, 2] packed (score, token) maxima: residual / fallback
     int *fdone;                 // [B]
-    int *fnode;                 // [B]
-    uint32_t *fflags;           // [B]
     int *kcount;                // [B, N] number of children of every node
     int2 *work;                 // [B, N] non-leaf nodes {b * N + node, nodes of the tree}, most children first
     int *wq;                    // [0] number of work items
@@ -648,6 +646,15 @@ __device__ __forceinline__ unsigned long long pack_key(float v, int idx) {
     return ((unsigned long long)bits << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)idx);
 }
 
+// Hardware exp2 / log2 (one instruction each).  The logarithm's operand is scaled out of the
+// denormal range first, which the instruction would read as zero.
+__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+__device__ __forceinline__ float fast_ln(float x) {
+    const bool tiny = x < 0x1p-100f;
+    const float l2 = __builtin_amdgcn_logf(tiny ? x * 0x1p100f : x) - (tiny ? 100.f : 0.f);
+    return l2 * kLn2;
+}
+
 template <int THREADS>
 __device__ void final_sample_range(const RrsArgs &a, int b, int node, const GroupRec &g, int c_lo,
                                    int c_hi, float &best_v, int &best_i, float &alt_v, int &alt_i) {
@@ -683,10 +690,10 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
         const float4 d = zd4[c];
         const uint4 rnd = philox4x32_10((uint32_t)c, (uint32_t)node, seq, c3, key);
         const uint32_t wd[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
-        const float et[4] = {exp2f(fmaf(t.x, a.c2, -cr.mt2)), exp2f(fmaf(t.y, a.c2, -cr.mt2)),
-                             exp2f(fmaf(t.z, a.c2, -cr.mt2)), exp2f(fmaf(t.w, a.c2, -cr.mt2))};
-        const float ed[4] = {exp2f(fmaf(d.x, a.c2, -cr.md2)), exp2f(fmaf(d.y, a.c2, -cr.md2)),
-                             exp2f(fmaf(d.z, a.c2, -cr.md2)), exp2f(fmaf(d.w, a.c2, -cr.md2))};
+        const float et[4] = {fast_exp2(fmaf(t.x, a.c2, -cr.mt2)), fast_exp2(fmaf(t.y, a.c2, -cr.mt2)),
+                             fast_exp2(fmaf(t.z, a.c2, -cr.mt2)), fast_exp2(fmaf(t.w, a.c2, -cr.mt2))};
+        const float ed[4] = {fast_exp2(fmaf(d.x, a.c2, -cr.md2)), fast_exp2(fmaf(d.y, a.c2, -cr.md2)),
+                             fast_exp2(fmaf(d.z, a.c2, -cr.md2)), fast_exp2(fmaf(d.w, a.c2, -cr.md2))};
         float q[4], r[4];
         if (!((hits >> it) & 1ull)) {
             chain4(et, ed, cr, K - 1, q);                                      // q^(K)
@@ -703,8 +710,8 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
             const float gum = gumbel_from_word(wd[i]);
-            const float s = logf(r[i]) + gum;
-            const float s2 = logf(q[i]) + gum;
+            const float s = fast_ln(r[i]) + gum;
+            const float s2 = fast_ln(q[i]) + gum;
             if (better(s, (c << 2) + i, best_v, best_i)) { best_v = s; best_i = (c << 2) + i; }
             if (better(s2, (c << 2) + i, alt_v, alt_i)) { alt_v = s2; alt_i = (c << 2) + i; }
         }
@@ -730,6 +737,12 @@ __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
     int *cnt = in_lds ? s_k : a.kcount;
     for (int i = tid; i < total; i += kPlanThreads) cnt[i] = 0;
     if (tid <= RSD_K_MAX) hist[tid] = 0;
+    // the last kernel's per-sequence maxima and arrival counters start at zero
+    for (int i = tid; i < a.B; i += kPlanThreads) {
+        a.fkey[2 * i] = 0ull;
+        a.fkey[2 * i + 1] = 0ull;
+        a.fdone[i] = 0;
+    }
     __syncthreads();
     for (int i = tid; i < total; i += kPlanThreads) {
         const int b = i / a.N, j = i - b * a.N;
@@ -812,8 +825,7 @@ __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
     }
 }
 
-// The walk itself (one lane), shared by both modes.  `rec_of(node)` must return the
-// verified record of `node`.
+// The uniform that decides child `node` of sequence b (Alg. 6: U ~ Uniform(0, 1) per tested token).
 __device__ __forceinline__ float accept_uniform(const RrsArgs &a, int b, int node) {
     const uint32_t seq = a.seq_id ? (uint32_t)a.seq_id[b] : (uint32_t)b;
     const uint4 r = philox4x32_10(0u, (uint32_t)node, seq, counter_word3(kTagAcceptUniform, a.step),
@@ -821,79 +833,118 @@ __device__ __forceinline__ float accept_uniform(const RrsArgs &a, int b, int nod
     return uniform_from_word(r.x);
 }
 
-// ALL_GROUPS, kernel 2: one wave per sequence walks the tree.
-__global__ __launch_bounds__(kWave) void rrs_walk_kernel(RrsArgs a) {
-    const int b = blockIdx.x;
-    const int lane = threadIdx.x;
-    const int n = min(max(a.n_nodes[b], 1), a.N);
-    for (int j = lane; j < a.N; j += kWave) {
-        if (a.uniforms) a.uniforms[(int64_t)b * a.N + j] = (j < n) ? accept_uniform(a, b, j) : 0.f;
-        if (a.theta && (j == 0 || j >= n)) a.theta[(int64_t)b * a.N + j] = NAN;
-    }
-    for (int j = lane; j < a.depth_max; j += kWave) {
-        a.accepted_nodes[(int64_t)b * a.depth_max + j] = -1;
-        if (a.accepted_tokens) a.accepted_tokens[(int64_t)b * a.depth_max + j] = -1;
-    }
-    __syncthreads();
-    if (lane != 0) return;
+// The walk of one sequence by one wave (ALL_GROUPS): at every node the wave reads the node's
+// verified record with all its lanes at once, lane k draws the uniform of child k, and a ballot
+// names the first accepted child -- one memory round trip per level.  Returns the node the walk
+// ends at; `g` receives that node's record (K = 0 for a leaf).  With `write` set (one workgroup per
+// sequence) the accepted path goes to the outputs.
+struct WalkResult {
+    int node, nacc;
+    uint32_t flags;
+};
+
+__device__ __forceinline__ WalkResult walk_tree(const RrsArgs &a, int b, int lane, bool write, GroupRec &g) {
+    constexpr int W_K = offsetof(GroupRec, K) / 4, W_FLAGS = offsetof(GroupRec, flags) / 4;
+    constexpr int W_KID = offsetof(GroupRec, kid) / 4, W_TOK = offsetof(GroupRec, tok) / 4;
+    constexpr int W_INVS = offsetof(GroupRec, inv_s) / 4, W_THETA = offsetof(GroupRec, theta) / 4;
+    constexpr int kWords = sizeof(GroupRec) / 4;
+    static_assert(kWords <= 2 * kWave && RSD_K_MAX <= kWave, "a record is two words per lane at most");
+    // word w of the record sits in lane w % 64, register w / 64
+    auto word = [&](uint32_t r0, uint32_t r1, int w) -> uint32_t {
+        const uint32_t lo = (uint32_t)__shfl((int)r0, w & (kWave - 1), kWave);
+        const uint32_t hi = (uint32_t)__shfl((int)r1, w & (kWave - 1), kWave);
+        return w < kWave ? lo : hi;
+    };
     int cur = 0, nacc = 0;
-    uint32_t flags = 0;
+    uint32_t flags = 0, r0 = 0, r1 = 0;
+    bool leaf = true;
     for (int guard = 0; guard < a.N; ++guard) {
-        if (a.kcount[(int64_t)b * a.N + cur] == 0) break;  // leaf: no record was written
-        const GroupRec &g = a.rec[(int64_t)b * a.N + cur];
-        const int K = g.K;
-        if (K == 0) break;
-        flags |= g.flags & RSD_FLAG_NONFINITE;
-        int took = -1;
-        for (int k = 0; k < K; ++k) {
-            const float u = accept_uniform(a, b, g.kid[k]);
-            if (u < g.theta[k]) {
-                took = k;
-                break;
-            }
-        }
+        const int64_t i = (int64_t)b * a.N + cur;
+        const int kc = a.kcount[i];
+        const uint32_t *src = reinterpret_cast<const uint32_t *>(a.rec + i);
+        // (the record of a leaf was never written: what is read is not used)
+        r0 = src[lane];
+        r1 = (lane + kWave < kWords) ? src[lane + kWave] : 0u;
+        leaf = kc == 0;
+        if (leaf) break;
+        const int K = (int)word(r0, r1, W_K);
+        if (K == 0) { leaf = true; break; }
+        const uint32_t gflags = word(r0, r1, W_FLAGS);
+        flags |= gflags & RSD_FLAG_NONFINITE;
+        const int kid = (int)word(r0, r1, W_KID + min(lane, RSD_K_MAX - 1));
+        const float theta = __uint_as_float(word(r0, r1, W_THETA + min(lane, RSD_K_MAX - 1)));
+        const float inv_s = __uint_as_float(word(r0, r1, W_INVS + min(lane, RSD_K_MAX - 1)));
+        const bool ok = lane < K && accept_uniform(a, b, kid) < theta;
+        const unsigned long long acc = __ballot(ok);
+        const int took = acc ? __ffsll((long long)acc) - 1 : -1;
         // degenerate stages matter only if their residual was used
-        if (g.flags & RSD_FLAG_DEGENERATE_RESIDUAL) {
+        if (gflags & RSD_FLAG_DEGENERATE_RESIDUAL) {
             const int used = took < 0 ? K - 1 : took;
-            for (int j = 0; j < used; ++j)
-                if (g.inv_s[j] == 0.f) flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
+            if (__ballot(lane < used && inv_s == 0.f)) flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
         }
         if (took < 0) break;
-        if (nacc < a.depth_max) {
-            a.accepted_nodes[(int64_t)b * a.depth_max + nacc] = g.kid[took];
-            if (a.accepted_tokens) a.accepted_tokens[(int64_t)b * a.depth_max + nacc] = g.tok[took];
+        const int next = __shfl(kid, took, kWave);
+        const int next_tok = (int)word(r0, r1, W_TOK + took);  // (lane exchanges stay outside divergent code)
+        if (write && lane == 0 && nacc < a.depth_max) {
+            a.accepted_nodes[(int64_t)b * a.depth_max + nacc] = next;
+            if (a.accepted_tokens) a.accepted_tokens[(int64_t)b * a.depth_max + nacc] = next_tok;
         }
         ++nacc;
-        cur = g.kid[took];
+        cur = next;
     }
-    a.n_accepted[b] = nacc;
-    if (a.final_node) a.final_node[b] = cur;
-    a.fnode[b] = cur;
-    a.fflags[b] = flags;
-    a.fkey[2 * b] = 0ull;
-    a.fkey[2 * b + 1] = 0ull;
-    a.fdone[b] = 0;
+    uint32_t *dst = reinterpret_cast<uint32_t *>(&g);
+    if (leaf) {
+        if (lane == 0) g.K = 0;  // sample from the target row itself
+    } else {
+        dst[lane] = r0;
+        if (lane + kWave < kWords) dst[lane + kWave] = r1;
+    }
+    return WalkResult{cur, nacc, flags};
 }
 
-// ALL_GROUPS, kernel 3: last token; the vocabulary is split over gridDim.x workgroups (more of them
-// for small batches; one per sequence, with no atomics at all, once the batch fills the chip).
+// ALL_GROUPS, kernel 2: the walk and the last token.  The vocabulary of a sequence is split over
+// gridDim.x workgroups (more of them for small batches; one per sequence, with no atomics at all,
+// once the batch fills the chip); every one of them walks the tree itself (the walk is a few
+// dependent reads of records that the previous kernel wrote), workgroup 0 of the sequence writes
+// the path.
 __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
     __shared__ GroupRec g;
     __shared__ float s_v[kFinalThreads / kWave];
     __shared__ int s_i[kFinalThreads / kWave];
     __shared__ int s_last;
+    __shared__ int s_node;
+    __shared__ uint32_t s_flags;
     const int b = blockIdx.y;
     const int split = blockIdx.x;
-    const int node = a.fnode[b];
-    if (a.kcount[(int64_t)b * a.N + node] > 0) {
-        const int words = sizeof(GroupRec) / 4;
-        const uint32_t *src = reinterpret_cast<const uint32_t *>(a.rec + (int64_t)b * a.N + node);
-        uint32_t *dst = reinterpret_cast<uint32_t *>(&g);
-        for (int i = threadIdx.x; i < words; i += kFinalThreads) dst[i] = src[i];
-    } else if (threadIdx.x == 0) {
-        g.K = 0;  // leaf: sample from the target row itself
+    const int tid = threadIdx.x;
+    const bool writer = split == 0;
+    const int n = min(max(a.n_nodes[b], 1), a.N);
+    if (writer) {
+        for (int j = tid; j < a.N; j += kFinalThreads) {
+            if (a.uniforms) a.uniforms[(int64_t)b * a.N + j] = (j < n) ? accept_uniform(a, b, j) : 0.f;
+            if (a.theta && (j == 0 || j >= n)) a.theta[(int64_t)b * a.N + j] = NAN;
+        }
+    }
+    if (tid < kWave) {
+        const WalkResult w = walk_tree(a, b, tid, writer, g);
+        if (writer) {
+            // slots of the path that the walk did not reach
+            for (int j = w.nacc + tid; j < a.depth_max; j += kWave) {
+                a.accepted_nodes[(int64_t)b * a.depth_max + j] = -1;
+                if (a.accepted_tokens) a.accepted_tokens[(int64_t)b * a.depth_max + j] = -1;
+            }
+        }
+        if (tid == 0) {
+            s_node = w.node;
+            s_flags = w.flags;
+            if (writer) {
+                a.n_accepted[b] = w.nacc;
+                if (a.final_node) a.final_node[b] = w.node;
+            }
+        }
     }
     __syncthreads();
+    const int node = s_node;
     const int nchunk = a.V >> 2;
     const int nsplit = gridDim.x;
     const int per = (nchunk + nsplit - 1) / nsplit;
@@ -921,7 +972,7 @@ __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
             k0 = atomicMax(&a.fkey[2 * b], 0ull);
             k1 = atomicMax(&a.fkey[2 * b + 1], 0ull);
         }
-        uint32_t flags = a.fflags[b];
+        uint32_t flags = s_flags;
         const unsigned long long ninf = pack_key(-INFINITY, 0) >> 32;
         unsigned long long use = k0;
         if ((k0 >> 32) <= ninf) {  // empty last residual: fall back to q^(K)
@@ -1069,8 +1120,7 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
     a.rec = reinterpret_cast<GroupRec *>(ws + off); off += align_up((size_t)B * N_max * sizeof(GroupRec), 256);
     a.fkey = reinterpret_cast<unsigned long long *>(ws + off); off += align_up((size_t)B * 16, 256);
     a.fdone = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * 4, 256);
-    a.fnode = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * 4, 256);
-    a.fflags = reinterpret_cast<uint32_t *>(ws + off); off += align_up((size_t)B * 4, 256);
+    off += 2 * align_up((size_t)B * 4, 256);  // (two per-sequence arrays of an earlier layout)
     a.kcount = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * N_max * 4, 256);
     a.work = reinterpret_cast<int2 *>(ws + off); off += 2 * align_up((size_t)B * N_max * 4, 256);
     a.wq = reinterpret_cast<int *>(ws + off);
@@ -1107,7 +1157,6 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
                                dim3(kLdsThreads), 0, st, a);
         else
             hipLaunchKernelGGL((rrs_group_kernel<kGroupThreads, 0, 0>), dim3(2 * grid), dim3(kGroupThreads), 0, st, a);
-        hipLaunchKernelGGL(rrs_walk_kernel, dim3(B), dim3(kWave), 0, st, a);
         // enough workgroups to fill the chip, but no more: every split costs two device-wide fences
         int fsplits = 256 / (B > 0 ? B : 1);
         fsplits = fsplits < 1 ? 1 : (fsplits > kFinalSplitsMax ? kFinalSplitsMax : fsplits);
