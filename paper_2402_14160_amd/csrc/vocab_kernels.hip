@@ -86,8 +86,11 @@ constexpr int kTopkThreads = 1024;
 constexpr int kTopkWaves = kTopkThreads / kWave;
 constexpr int kCandMax = 1024;
 
+// Without the normaliser and up to 8 chunks per thread the kernel is held to 64 registers: two
+// workgroups then share a CU, and one row's load, reduction and selection phases run under the
+// other's Philox arithmetic (with the normaliser the same limit spills too much to pay).
 template <int CH, bool WANT_LSE>
-__global__ __launch_bounds__(kTopkThreads) void gumbel_topk_kernel(TopkArgs a) {
+__global__ __launch_bounds__(kTopkThreads, (CH <= 8 && !WANT_LSE) ? 8 : 4) void gumbel_topk_kernel(TopkArgs a) {
     __shared__ MaxSum s_ms[kTopkWaves];
     __shared__ float s_wmax[kTopkWaves];
     __shared__ float s_tau;
