@@ -1084,7 +1084,7 @@ using namespace rsd;
 extern "C" size_t rsd_recursive_reject_workspace_bytes(int32_t B, int32_t N_max, int32_t) {
     if (B <= 0 || N_max <= 0) return 0;
     return align_up((size_t)B * N_max * sizeof(GroupRec), 256) + align_up((size_t)B * 16, 256) +
-           3 * align_up((size_t)B * 4, 256) + 3 * align_up((size_t)B * N_max * 4, 256) + 256;
+           align_up((size_t)B * 4, 256) + 3 * align_up((size_t)B * N_max * 4, 256) + 256;
 }
 
 extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *target_logits,
@@ -1120,7 +1120,6 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
     a.rec = reinterpret_cast<GroupRec *>(ws + off); off += align_up((size_t)B * N_max * sizeof(GroupRec), 256);
     a.fkey = reinterpret_cast<unsigned long long *>(ws + off); off += align_up((size_t)B * 16, 256);
     a.fdone = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * 4, 256);
-    off += 2 * align_up((size_t)B * 4, 256);  // (two per-sequence arrays of an earlier layout)
     a.kcount = reinterpret_cast<int *>(ws + off); off += align_up((size_t)B * N_max * 4, 256);
     a.work = reinterpret_cast<int2 *>(ws + off); off += 2 * align_up((size_t)B * N_max * 4, 256);
     a.wq = reinterpret_cast<int *>(ws + off);
