@@ -529,7 +529,9 @@ def _rrs_case(kind, B, V, counts, n_cap, seed, inv_t, mode, sbs=None):
     ("normal", 4, 64, (2, 2), 1.0),
     ("zipf", 3, 32000, (3, 2, 2, 1), 1.0),
     ("zipf", 2, 32000, (8, 4, 2), 1.0 / 0.3),
-    ("zipf", 2, 50272, (4, 3), 1.0),
+    ("zipf", 2, 50272, (4, 3), 1.0),         # resident variant with the draft row partly in LDS
+    ("zipf", 2, 40004, (5, 2), 1.0),         # the same, chunks that end inside a wave
+    ("zipf", 2, 65536, (3, 2), 1.0),         # largest row: the streaming variant
 ])
 def test_recursive_reject_matches_oracle(mode, kind, B, V, branching, inv_t):
     say(f"rrs mode={mode} {kind} B={B} V={V} b={branching} invT={inv_t:.2f}")
