@@ -6,11 +6,17 @@
 //   q^(1)(x)   = e_t(x) / s_t
 //   p^(k)(x)   = e_d(x) / s_k          for x not in {x_1..x_{k-1}}, else 0
 //   q^(k+1)(x) = max(q^(k)(x) - p^(k)(x), 0) / S_k,   S_k = sum_x max(q^(k) - p^(k), 0)
-// so every stage is one read-only pass over the two logit rows that evaluates a
-// short per-entry chain from the scalars (s_t, s_1.., S_1..) found so far.
+// The resident variants keep u(x) = q^(k)(x) * A_k and e_d(x) on chip (registers, and LDS
+// for the larger vocabularies) and update u in place at every stage; the streaming variant
+// (largest vocabularies) re-reads the two rows at every stage and evaluates the short
+// per-entry chain from the scalars (s_t, s_1.., S_1..) found so far.  Either way only the
+// scalars go to memory, and the last-token pass re-evaluates the chain from them.
 // s_k sums the draft row without the removed tokens directly (no 1 - p
-// cancellation).  Sums are accumulated per lane in fp32, across lanes in fp64
+// cancellation).  Sums are accumulated per lane in fp32, across waves in fp64
 // in a fixed order, so results do not depend on scheduling.
+//
+// ALL_GROUPS runs three kernels (plan, groups, walk + last token), PATH one persistent
+// workgroup per sequence.
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <math.h>
@@ -26,7 +32,7 @@ typedef __attribute__((address_space(1))) const void global_void;
 constexpr int kGroupThreads = 512;   // streaming variant (any vocabulary size)
 constexpr int kRegThreads = 512;     // register-resident variant: 2 waves per SIMD, 256 VGPRs each
 // resident variant with most of the draft row in LDS (larger vocabularies): 12 waves, three per
-// SIMD, so that a thread has 168 registers and nothing spills
+// SIMD, so that a thread has 168 registers
 constexpr int kLdsThreads = 768;
 constexpr int kLdsChunks = 17;       // float4 chunks per thread: 52224 entries
 constexpr int kLdsChunksInLds = 12;  // of which in LDS: 12 * 768 * 16 B = 144 KB
