@@ -854,11 +854,25 @@ static int plan_segments(int dtype, int B, int Hq, int Hkv, int N, int P_max, in
     for (int i = 0; i < nseg; ++i) {
         int s = requested;
         if (dtype != RSD_DTYPE_BF16) s = 1;
-        if (s <= 0) {  // fill the chip in one round: one or two workgroups per CU
+        if (s <= 0) {
+            // The number of splits that minimises (rounds of workgroups over the chip's slots, one
+            // or two per CU) x (tiles per split + about two tiles' worth of set-up), plus about two
+            // tiles for the merge launch once there is more than one split.  A split of fewer than
+            // four tiles costs more in set-up and merging than it gains.
             const long blocks = (long)seg[i].row_blocks * Hkv * B;
-            s = (int)((seg[i].variant == kV32x8 ? 256 : 512) / (blocks > 0 ? blocks : 1));
-            // a split of fewer than four tiles costs more in set-up and merging than it gains
-            if (s > tiles / 4) s = tiles / 4;
+            const long slots = seg[i].variant == kV32x8 ? 256 : 512;
+            int smax = tiles / 4 < kMaxSplits ? tiles / 4 : kMaxSplits;
+            if (smax < 1) smax = 1;
+            double best = 0.0;
+            s = 1;
+            for (int c = 1; c <= smax; ++c) {
+                const long rounds = (blocks * c + slots - 1) / slots;
+                const double cost = (double)rounds * ((double)tiles / c + 2.0) + (c > 1 ? 2.0 : 0.0);
+                if (c == 1 || cost < best) {
+                    best = cost;
+                    s = c;
+                }
+            }
         }
         if (s > kMaxSplits) s = kMaxSplits;  // the merge holds one split per lane
         if (s > tiles) s = tiles;
