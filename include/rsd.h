@@ -268,6 +268,13 @@ int32_t rsd_filter_kv_cache(void *k_cache, void *v_cache, const void *k_tree, co
  *          kept   [R] number of kept entries, or NULL
  * Limits: 1 <= V <= RSD_VOCAB_MAX; inv_temperature > 0; top_k >= 0 (0 = off);
  *   top_p > 0 (>= 1 = off).  -inf / NaN entries are never kept.  No workspace.
+ * Precision: probabilities are ranked as 2^y with y = (logit - row max) *
+ *   inv_temperature * log2(e) held in fp32, so two entries whose probabilities
+ *   differ by less than about |y| * 2^-22 * ln 2 (relative) may count as equally
+ *   probable, and sums of probabilities are fp32 (about 1e-6 of mass).  With top_p
+ *   given, entries below 2^-126 of the row maximum carry no mass and are dropped;
+ *   top_k alone ranks them too, down to 2^-2142 of the maximum, below which an
+ *   entry is never kept.
  * ------------------------------------------------------------------------- */
 int32_t rsd_filter_logits(const float *logits, int64_t ld, int32_t R, int32_t V,
                           float inv_temperature, int32_t top_k, float top_p, float *out,

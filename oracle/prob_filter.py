@@ -32,9 +32,12 @@ def _softmax64(z):
 def filter_row(z, inv_temperature=1.0, top_k=0, top_p=1.0):
     """One row of logits -> (filtered logits, margin).
 
-    `margin` is how far the deciding comparison was from flipping: the smaller of the gap
+    `margin` is how far the deciding comparisons were from flipping: the smallest of the gap
     between the top-p target and the cumulative masses on either side of the cut, and the
-    relative gap between the k-th and (k+1)-th probability (inf when a filter is off).
+    relative gap between the least probable kept entry and the most probable dropped one
+    (for either filter; inf when a filter is off or nothing is dropped).  A reader that works
+    in lower precision may see such a pair as equally probable and, by the rule above, keep
+    both.
     """
     z = np.asarray(z)
     x = z.astype(np.float64) * np.float64(np.float32(inv_temperature))
@@ -58,6 +61,9 @@ def filter_row(z, inv_temperature=1.0, top_k=0, top_p=1.0):
         thr = srt[i]
         below = cum[i - 1] if i > 0 else 0.0
         margin = min(margin, cum[i] - top_p, top_p - below)
+        dropped = srt[srt < thr]
+        if dropped.size:
+            margin = min(margin, (thr - dropped[0]) / thr)
         keep &= prob >= thr
     out = np.where(keep, z, np.asarray(-np.inf, dtype=z.dtype))
     return out.astype(z.dtype), float(margin)

@@ -38,6 +38,10 @@ constexpr float kMinNormal = 1.17549435e-38f;
 constexpr uint32_t kMinNormalBits = 0x00800000u;
 constexpr uint32_t kAboveOneBits = 0x3F800001u;  // e <= 1, so nothing is >= this
 constexpr int kFilterCand = 1024;  // entries between the bounds when the per-wave probes take over
+// A top-k larger than the number of entries that fp32 tells apart from zero goes on below the
+// fp32 range, 126 binary orders of magnitude at a time, at most this many times (entries more
+// than 126 * 17 = 2142 log2 units below the row maximum are never kept).
+constexpr int kUnderflowBands = 16;
 
 // sum of lanes 0..15 of a wave (one DPP row), the same in every lane; fixed order
 __device__ __forceinline__ float row0_sum(float v) {
@@ -51,7 +55,9 @@ __device__ __forceinline__ float row0_sum(float v) {
 // CH: float4 chunks per thread; RAGGED: V is not a multiple of 4 (the last chunk is then read
 // and written entry by entry).  Up to 8 chunks per thread the kernel fits 64 registers, so two
 // workgroups share a CU and one row's loads and stores overlap the other's arithmetic.
-template <int CH, bool RAGGED>
+// BANDS: top-k without top-p, the one case that may have to rank entries below the fp32 range
+// (kept out of the other instantiations, whose register budget it would strain).
+template <int CH, bool RAGGED, bool BANDS>
 __global__ __launch_bounds__(kFilterThreads, CH <= 8 ? 8 : 4) void prob_filter_kernel(FilterLogitsArgs a) {
     constexpr int kWaves = kFilterThreads / kWave;
     static_assert(kWaves <= 16, "the wave partials are combined inside one row of 16 lanes");
@@ -82,9 +88,14 @@ __global__ __launch_bounds__(kFilterThreads, CH <= 8 ? 8 : 4) void prob_filter_k
     };
     float e[CH * 4];  // raw logits first, then exp((z - max) / T)
     float mx = -INFINITY;
+    // (with the bands the lane index is live through the whole kernel and the register allocator
+    // would reload it from scratch before every load below, which drains the loads one by one: a
+    // copy it takes for a new value keeps the reloads out of this loop)
+    int tid_a = tid;
+    if constexpr (BANDS) asm volatile("" : "+v"(tid_a));
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-        const float4 t = load_chunk(j, tid);
+        const float4 t = load_chunk(j, tid_a);
         e[4 * j + 0] = t.x; e[4 * j + 1] = t.y; e[4 * j + 2] = t.z; e[4 * j + 3] = t.w;
         mx = fmaxf(mx, fmaxf(fmaxf(t.x, t.y), fmaxf(t.z, t.w)));
     }
@@ -145,6 +156,11 @@ __global__ __launch_bounds__(kFilterThreads, CH <= 8 ? 8 : 4) void prob_filter_k
         for (int w = 1; w < kWaves; ++w) mb = min(mb, s_min[w]);
         min_bits = mb + 1u;  // meaningful when npos > 0
     }
+    // (a lane index the compiler takes for a new value wherever the row is read again, so that
+    // the first pass's addresses and bounds are recomputed there instead of being held in
+    // registers through the search)
+    int tid_w = tid;
+    if constexpr (BANDS) asm volatile("" : "+v"(tid_w));  // (the bands read the row inside the search)
 
     // (mass, count) of the entries with e >= t; every thread gets the workgroup's values.
     // The count is a population count of the compare mask (scalar unit, whole wave at once);
@@ -254,14 +270,69 @@ __global__ __launch_bounds__(kFilterThreads, CH <= 8 ? 8 : 4) void prob_filter_k
     };
 
     uint32_t cut = kMinNormalBits;  // keep every entry with e >= cut (bit pattern): all positive ones so far
+    // The cut lies this many log2 units below the fp32 range: an entry is kept when
+    // 2^(log2 of its relative probability + shift) >= cut.  Once a band below the range has been
+    // looked at (top-k alone, see below) the registers no longer hold band 0, and the decision
+    // is worked out again from the logits when the row is written.
+    float shift = 0.f;
+    bool stale = false;
     if (npos > 0.5f) {
-        if (a.top_k > 0 && npos > (float)a.top_k) {  // no more than k positive entries: keep them all
-            cut = search((float)a.top_k, std::true_type{}, min_bits, npos, npos);
+        if (a.top_k > 0) {
+            // The row is ranked band by band: band 0 is what fp32 tells apart from zero (the
+            // values in the registers); when top-k alone wants more entries than that, the
+            // relative probabilities in [2^-126 (s+1), 2^-126 s) are worked out again from the
+            // logits, scaled up by 2^(126 s).  A band that fits is taken whole, the one that
+            // does not is searched.
+            const bool deeper = BANDS && !(a.top_p < 1.f);  // with top-p the bands below carry no mass and go anyway
+            float have = 0.f, cnt = npos, base = 0.f;
+            uint32_t band_min = min_bits;
+            for (int band = 0;; ++band) {
+                if (have + cnt > (float)a.top_k) {  // the cut falls inside this band
+                    cut = search((float)a.top_k - have, std::true_type{}, band_min, cnt, cnt);
+                    shift = base;
+                    break;
+                }
+                if (cnt > 0.5f) {  // the whole band is kept
+                    have += cnt;
+                    cut = kMinNormalBits;
+                    shift = base;
+                }
+                if (!BANDS || !deeper || band == kUnderflowBands || have >= (float)a.top_k) break;
+                base += 126.f;
+                stale = true;
+                int wc = 0;
+                uint32_t mb = 0xFFFFFFFFu;
 #pragma unroll
-            for (int i = 0; i < CH * 4; ++i) e[i] = (e[i] >= __uint_as_float(cut)) ? e[i] : 0.f;
-            if (a.top_p < 1.f) {
-                min_bits = cut;  // every surviving entry is >= cut
-                tail_sums(cut, std::false_type{}, total, npos);
+                for (int j = 0; j < CH; ++j) {
+                    const float4 t = load_chunk(j, tid_w);
+                    const float zq[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                    for (int q = 0; q < 4; ++q) {
+                        const float pb = __builtin_amdgcn_exp2f(fmaf(zq[q], a.c2, -mref) + base);
+                        const bool in_band = pb >= kMinNormal && pb < 1.f;
+                        e[4 * j + q] = in_band ? pb : 0.f;
+                        wc += __builtin_popcountll(__builtin_amdgcn_ballot_w64(in_band));
+                        mb = min(mb, __float_as_uint(e[4 * j + q]) - 1u);
+                    }
+                }
+#pragma unroll
+                for (int o = 32; o >= 1; o >>= 1) mb = min(mb, (uint32_t)__shfl_xor((int)mb, o, kWave));
+                __syncthreads();  // the previous round's s_min has been read
+                if (lane == 0) s_min[wave] = mb;
+                float unused;
+                combine(0.f, (float)wc, unused, cnt);
+                mb = s_min[0];
+#pragma unroll
+                for (int w = 1; w < kWaves; ++w) mb = min(mb, s_min[w]);
+                band_min = mb + 1u;
+            }
+            if (a.top_p < 1.f) {  // (then the cut lies in band 0)
+#pragma unroll
+                for (int i = 0; i < CH * 4; ++i) e[i] = (e[i] >= __uint_as_float(cut)) ? e[i] : 0.f;
+                if (cut != kMinNormalBits) {
+                    min_bits = cut;  // every surviving entry is >= cut
+                    tail_sums(cut, std::false_type{}, total, npos);
+                }
             }
         }
         if (a.top_p < 1.f) {
@@ -277,9 +348,7 @@ __global__ __launch_bounds__(kFilterThreads, CH <= 8 ? 8 : 4) void prob_filter_k
     float4 *o4 = reinterpret_cast<float4 *>(orow);
     // the logits are read a second time (they were not kept in registers; the row is still in
     // L2) just before the same thread overwrites them, so `out` may be `logits` itself
-    // (a lane index the compiler takes for a new value, so that the first pass's addresses and
-    // bounds are recomputed here instead of being held in registers through the search)
-    int tid_w = tid;
+    const bool below_range = BANDS && stale;  // uniform
     asm volatile("" : "+v"(tid_w));
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
@@ -289,7 +358,11 @@ __global__ __launch_bounds__(kFilterThreads, CH <= 8 ? 8 : 4) void prob_filter_k
         float r[4];
 #pragma unroll
         for (int q = 0; q < 4; ++q) {
-            const bool keep = e[4 * j + q] >= cutf;  // cutf > 0: the dropped entries (e = 0) fail
+            // cutf > 0: the dropped entries (e = 0) fail.  After a look below the fp32 range the
+            // entry's scaled probability is worked out again (infinite for the bands above the
+            // cut's, zero or NaN for what is never kept).
+            bool keep = e[4 * j + q] >= cutf;
+            if (below_range) keep = __builtin_amdgcn_exp2f(fmaf(zq[q], a.c2, -mref) + shift) >= cutf;
             r[q] = keep ? zq[q] : -INFINITY;
             wkept += __builtin_popcountll(__builtin_amdgcn_ballot_w64(keep));
         }
@@ -332,12 +405,17 @@ extern "C" int32_t rsd_filter_logits(const float *logits, int64_t ld, int32_t R,
     const int need = (V >> 2) + ((V & 3) ? 1 : 0);  // float4 chunks of a row, a ragged tail included
     const int chunks = (need + kFilterThreads - 1) / kFilterThreads;
     const bool ragged = (V & 3) != 0;
-#define RSD_LAUNCH_FILTER(CH)                                                                          \
-    do {                                                                                               \
-        if (ragged)                                                                                    \
-            hipLaunchKernelGGL((prob_filter_kernel<CH, true>), dim3(R), dim3(kFilterThreads), 0, st, a);  \
-        else                                                                                           \
-            hipLaunchKernelGGL((prob_filter_kernel<CH, false>), dim3(R), dim3(kFilterThreads), 0, st, a); \
+    const bool bands = top_k > 0 && !(top_p < 1.f);
+#define RSD_LAUNCH_FILTER(CH)                                                                                 \
+    do {                                                                                                      \
+        if (bands && ragged)                                                                                  \
+            hipLaunchKernelGGL((prob_filter_kernel<CH, true, true>), dim3(R), dim3(kFilterThreads), 0, st, a);   \
+        else if (bands)                                                                                       \
+            hipLaunchKernelGGL((prob_filter_kernel<CH, false, true>), dim3(R), dim3(kFilterThreads), 0, st, a);  \
+        else if (ragged)                                                                                      \
+            hipLaunchKernelGGL((prob_filter_kernel<CH, true, false>), dim3(R), dim3(kFilterThreads), 0, st, a);  \
+        else                                                                                                  \
+            hipLaunchKernelGGL((prob_filter_kernel<CH, false, false>), dim3(R), dim3(kFilterThreads), 0, st, a); \
     } while (0)
     if (chunks <= 2)
         RSD_LAUNCH_FILTER(2);

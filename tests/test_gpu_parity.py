@@ -315,15 +315,29 @@ def test_tree_attention_strided_prefix_and_bad_arguments():
 FILTER_TOL = 1e-6   # probability mass: fp32 exponentials and sums on the GPU against the fp64 oracle
 
 
+def _filter_tol(z_row, ref_row, inv_t):
+    """Relative tolerance of one row's decision.  The kernel raises 2 to y = (z - max)/T * log2(e) held
+    in fp32, whose spacing at the cut is |y| * 2^-23: one rounding in the scale and one in the fused
+    multiply-add move an entry by up to |y| * 2^-22 * ln 2 of its probability, so neighbours closer
+    than that cannot be told apart.  Never below FILTER_TOL, which covers the sums."""
+    keep = np.isfinite(ref_row)
+    if not keep.any():                                                      # a row with no finite logit
+        return FILTER_TOL
+    y_cut = (float(z_row[keep].min()) - float(z_row[keep].max())) * inv_t * np.log2(np.e)
+    return max(FILTER_TOL, abs(y_cut) * 2.0 ** -22 * np.log(2.0))
+
+
 def _check_filtered(got, z, ref, margin, inv_t, top_k, top_p):
-    """Every row: the kept set is a top set, keeps the logits unchanged, and is a valid answer up to
-    FILTER_TOL of probability mass (reaches the target, and would fall short without its least probable
-    entries, which stay or go together when they are equally probable).  Rows that the oracle decided by a margin above FILTER_TOL must match it exactly."""
+    """Every row: the kept set is a top set, keeps the logits unchanged, and is a valid answer up to the
+    row's tolerance (reaches the target, and would fall short without its least probable entries, which
+    stay or go together when they are equally probable).  Rows that the oracle decided by a margin above
+    the tolerance must match it exactly."""
     near = 0
     for r in range(z.shape[0]):
         kept = np.isfinite(got[r])
         assert np.array_equal(got[r][kept], z[r][kept])
-        if margin[r] >= FILTER_TOL:
+        tol = _filter_tol(z[r], ref[r], inv_t)
+        if margin[r] >= tol:
             assert np.array_equal(got[r], ref[r]), r
             continue
         near += 1
@@ -332,17 +346,26 @@ def _check_filtered(got, z, ref, margin, inv_t, top_k, top_p):
         assert z[r][kept].min() >= z[r][fin & ~kept].max(initial=-np.inf)         # a top set
         x = z[r].astype(np.float64) * np.float64(np.float32(inv_t))
         prob = np.where(fin, np.exp(x - x[fin].max()), 0.0)
+        sizes = [int(fin.sum())]                            # candidate sizes of the set top-p acts on
         if top_k:                                                               # top-k acts first
-            kth = np.sort(prob)[::-1][min(top_k, int(fin.sum())) - 1]
-            in_k = prob >= kth * (1 - 1e-6)
+            srt = np.sort(prob)[::-1]
+            kth = srt[min(top_k, int(fin.sum())) - 1]
+            in_k = prob >= kth * (1 - tol)
             assert not (kept & ~in_k).any()
-            prob = np.where(in_k, prob, 0.0)
-        prob /= prob.sum()
+            # entries within the tolerance of the k-th may or may not have been taken as tied with it
+            sizes = list(range(int((prob >= kth).sum()), int(in_k.sum()) + 1))
         if top_p < 1.0:
-            mass = prob[kept].sum()
-            least = prob[kept].min()                        # entries as probable as it stay together
-            assert mass >= top_p - FILTER_TOL
-            assert mass - prob[kept & (prob <= least * (1 + 1e-6))].sum() < top_p + FILTER_TOL
+            order = np.argsort(-prob, kind="stable")
+            ok = False
+            for m in sizes:                                 # top-p on the distribution over the top m
+                pm = np.zeros_like(prob)
+                pm[order[:m]] = prob[order[:m]]
+                pm /= pm.sum()
+                mass = pm[kept].sum()
+                least = pm[kept].min()                      # entries as probable as it stay together
+                ok |= (mass >= top_p - tol and
+                       mass - pm[kept & (pm <= least * (1 + tol))].sum() < top_p + tol)
+            assert ok
     return near
 
 
@@ -367,9 +390,9 @@ def test_filter_logits(kind, R, V, inv_t, top_k, top_p):
     out, kept = binding.filter_logits(d_in, inv_t, top_k, top_p, return_kept=True)
     ref, kept_ref, margin = o_pfilter.filter_logits(z.numpy(), inv_t, top_k, top_p)
     near = _check_filtered(to_np(out), z.numpy(), ref, margin, inv_t, top_k, top_p)
-    say(f"  kept per row {kept_ref.tolist()}, rows decided within {FILTER_TOL} of mass: {near}")
+    say(f"  kept per row {kept_ref.tolist()}, rows decided within the tolerance: {near}")
     assert np.array_equal(to_np(kept), np.isfinite(to_np(out)).sum(1))
-    ok = margin >= FILTER_TOL
+    ok = margin >= np.array([_filter_tol(z.numpy()[r], ref[r], inv_t) for r in range(R)])
     assert np.array_equal(to_np(kept)[ok], kept_ref[ok])
     assert np.abs(to_np(kept) - kept_ref).max() <= 2
     # in place
@@ -405,9 +428,37 @@ def test_filter_logits_hard_rows(V, top_k, top_p):
     out, kept = binding.filter_logits(buf.to(dev())[:, :V], 1.0, top_k, top_p, return_kept=True)
     ref, kept_ref, margin = o_pfilter.filter_logits(z, 1.0, top_k, top_p)
     near = _check_filtered(to_np(out), z, ref, margin, 1.0, top_k, top_p)
-    say(f"  kept per row {kept_ref.tolist()}, rows decided within {FILTER_TOL} of mass: {near}")
+    say(f"  kept per row {kept_ref.tolist()}, rows decided within the tolerance: {near}")
     assert np.array_equal(to_np(kept), np.isfinite(to_np(out)).sum(1))
-    ok = margin >= FILTER_TOL
+    ok = margin >= np.array([_filter_tol(z[r], ref[r], 1.0) for r in range(z.shape[0])])
+    assert np.array_equal(to_np(kept)[ok], kept_ref[ok])
+
+
+@pytest.mark.parametrize("V,top_k,top_p", [
+    (32000, 4000, 1.0),       # the k-th entry lies below what fp32 tells apart from zero
+    (32000, 31000, 1.0),      # several such bands
+    (4099, 4099, 1.0),        # everything finite is kept
+    (32000, 4000, 0.999),     # with top-p those entries carry no mass and go
+])
+def test_filter_logits_wide_rows(V, top_k, top_p):
+    """Sharp rows (1/T = 10/3 on logits spread over +-40): the relative probabilities span more than the
+    fp32 exponent range, so top-k alone has to rank entries whose fp32 exponential is zero."""
+    say(f"filter_logits wide rows V={V} top_k={top_k} top_p={top_p}")
+    rng = np.random.default_rng(V + top_k)
+    z = (rng.standard_normal((4, V)) * 10).astype(np.float32)
+    z[1] = np.sort(z[1])
+    z[2, ::7] = -np.inf
+    z[3] = np.round(z[3])                                          # ties inside every band
+    inv_t = 1.0 / 0.3
+    ld = (V + 3) // 4 * 4
+    buf = torch.zeros((z.shape[0], ld), dtype=torch.float32)
+    buf[:, :V] = torch.from_numpy(z)
+    out, kept = binding.filter_logits(buf.to(dev())[:, :V], inv_t, top_k, top_p, return_kept=True)
+    ref, kept_ref, margin = o_pfilter.filter_logits(z, inv_t, top_k, top_p)
+    near = _check_filtered(to_np(out), z, ref, margin, inv_t, top_k, top_p)
+    say(f"  kept per row {kept_ref.tolist()}, rows decided within the tolerance: {near}")
+    assert np.array_equal(to_np(kept), np.isfinite(to_np(out)).sum(1))
+    ok = margin >= np.array([_filter_tol(z[r], ref[r], inv_t) for r in range(z.shape[0])])
     assert np.array_equal(to_np(kept)[ok], kept_ref[ok])
 
 
