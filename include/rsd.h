@@ -160,7 +160,9 @@ int32_t rsd_sbs_step(const float *logits, const float *sum_logprob, const float 
  *                      values above 32 are taken as 32
  * Outputs
  *   out     [B, H_q, N_max, D] fp32; rows i >= n_nodes[b] are not written
- *   lse_out [B, H_q, N_max] natural-log softmax normaliser, or NULL
+ *   lse_out [B, H_q, N_max] natural-log softmax normaliser, or NULL.  On the bf16 path it
+ *           is the log of the sum of the bf16-rounded weights that multiply V (the sum
+ *           `out` is normalised by), within 2^-8 relative of the exact sum.
  * Limits: bf16: D in {64, 128}; f32: D <= 256; N_max <= RSD_NODES_MAX;
  *   H_q % H_kv == 0; all tensors 16-byte aligned, prefix strides multiples of 8 (bf16)
  *   or 4 (f32).  Invalid parent values are clamped on the device (no fault).

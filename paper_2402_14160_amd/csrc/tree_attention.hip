@@ -32,6 +32,7 @@ namespace rsd {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 typedef __attribute__((address_space(3))) bf16x4 lds_bf16x4;
 
@@ -183,6 +184,22 @@ __device__ __forceinline__ bf16x4 lds_read_tr(const __bf16 *p) {
     return __builtin_amdgcn_ds_read_tr16_b64_v4bf16((lds_bf16x4 *)(p));
 }
 
+// Sum of 16 probabilities as the matrix instruction will see them (after rounding to bf16), so
+// that the row sum normalises exactly the weights that multiply V: with the unrounded sum a row
+// dominated by one key is off by that key's rounding error (up to 2^-8 relative) whenever its
+// exponential is not a power of two.  v_dot2_f32_bf16 adds two entries per instruction.
+__device__ __forceinline__ float rounded_sum(const bf16x8 &p0, const bf16x8 &p1) {
+    const bf16x2 ones = {(__bf16)1.f, (__bf16)1.f};
+    float s0 = 0.f, s1 = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+        const bf16x2 a = {p0[2 * e], p0[2 * e + 1]}, b = {p1[2 * e], p1[2 * e + 1]};
+        s0 = __builtin_amdgcn_fdot2_f32_bf16(a, ones, s0, false);
+        s1 = __builtin_amdgcn_fdot2_f32_bf16(b, ones, s1, false);
+    }
+    return s0 + s1;
+}
+
 template <int D>
 __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArgs a) {
     constexpr int KS = D / 32;        // k-steps of the first product
@@ -296,17 +313,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
         const float m_new = fmaxf(m, mx);
         const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
         const float alpha = exp2f(m - m_use);
-        float psum = 0.f;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const float p = exp2f(s[t][r] - m_use);
-                s[t][r] = p;
-                psum += p;
-            }
+            for (int r = 0; r < 4; ++r) s[t][r] = exp2f(s[t][r] - m_use);
         }
-        l = l * alpha + psum;
         m = m_new;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
@@ -318,6 +329,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
 #pragma unroll
             for (int e = 0; e < 8; ++e) pf[j][e] = (__bf16)s[2 * j + (e >> 2)][e & 3];
         }
+        l = l * alpha + rounded_sum(pf[0], pf[1]);
         // lane (c16, g) of the A operand needs V[key][16 dt + c16] for the keys
         // 32 j + 16 a + 4 g + r (a = 0,1; r = 0..3): two transposing reads, in which this
         // lane loads row 32 j + 16 a + 4 g + c16 / 4, columns 16 dt + 4 (c16 % 4) .. + 3.
@@ -585,13 +597,8 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
             };
             auto half_exp = [&](floatx16 &sv, bf16x8 &p0, bf16x8 &p1) {
                 const float mu = (m == -INFINITY) ? 0.f : m;
-                float ps = 0.f;
 #pragma unroll
-                for (int r = 0; r < 16; ++r) {
-                    sv[r] = __builtin_amdgcn_exp2f(fmaf(sv[r], a.scale_log2, -mu));
-                    ps += sv[r];
-                }
-                l += ps;
+                for (int r = 0; r < 16; ++r) sv[r] = __builtin_amdgcn_exp2f(fmaf(sv[r], a.scale_log2, -mu));
 #pragma unroll
                 for (int e = 0; e < 8; ++e) {
                     p0[e] = (__bf16)sv[e];
@@ -635,9 +642,11 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
             qk_half(s1, 1);
             half_exp(s0, pf[0], pf[1]);
             if (EXACT) raise_max(half_max(s1), true);
+            l += rounded_sum(pf[0], pf[1]);  // (after the rescale, which forms this half's P again)
             pv_step(0, pf[0]);
             pv_step(1, pf[1]);
             half_exp(s1, pf[2], pf[3]);
+            l += rounded_sum(pf[2], pf[3]);
             pv_step(2, pf[2]);
             pv_step(3, pf[3]);
         }

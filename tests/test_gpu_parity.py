@@ -267,6 +267,17 @@ def test_tree_attention_bf16(B, Hq, Hkv, N, D, P, splits, n_nodes, plens):
     assert err < 1e-2
 
 
+def test_tree_attention_one_key_prefix_wide_rows():
+    """A one-key prefix under 272 stacked rows: few visible keys per row, so single keys dominate, and the
+    fixed softmax reference of the 32-row kernel (taken from the first tile, here that one key) makes the
+    dominant exponential something other than 1.  The row sum has to be the sum of the bf16-rounded
+    probabilities that multiply V, or the dominant key's rounding error (2^-8 relative) reaches the output."""
+    say("attention bf16, one-key prefix, 16 query heads per KV head")
+    err = _attention_case(3, 48, 3, 17, 64, 1, "bf16", 617961752, n_nodes=[17, 3, 3], plens=[1, 1, 1])
+    say(f"  max abs err {err:.2e}")
+    assert err < 1e-2
+
+
 def test_tree_attention_rising_scores():
     """Scores that climb far above those of the first tile (by more than 64 in log2 units): blocks of
     the 256-row kernel leave their fixed-reference pass and repeat with the running-maximum pass."""
