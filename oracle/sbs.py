@@ -48,7 +48,9 @@ def sbs_step_from_noise(logits, sum_logprob, trunc_gumbel, gumbel, width,
     """Alg. 9 for one sequence with the Gumbel matrix passed in.
 
     logits [n,V] (one row per live beam entry), sum_logprob [n], trunc_gumbel [n],
-    gumbel [n,V].  Returns dict(tokens, parent, sum_logprob, trunc_gumbel, lse, psi_all).
+    gumbel [n,V].  Returns dict(tokens, parent, sum_logprob, trunc_gumbel, perturbed, lse,
+    psi_all); perturbed = Phi_tilde of the selected pairs (Eq. (11) turns an error e in it into
+    e * exp(psi - Phi_tilde) in psi, which a comparison in lower precision has to allow for).
     """
     logits = np.atleast_2d(np.asarray(logits))
     n, V = logits.shape
@@ -69,7 +71,8 @@ def sbs_step_from_noise(logits, sum_logprob, trunc_gumbel, gumbel, width,
     tokens = sel % V
     return dict(tokens=tokens.astype(np.int64), parent=parent.astype(np.int64),
                 sum_logprob=phi[parent, tokens],                 # step 7
-                trunc_gumbel=psi[parent, tokens], lse=lse, psi_all=psi)
+                trunc_gumbel=psi[parent, tokens], perturbed=phi_tilde[parent, tokens],
+                lse=lse, psi_all=psi)
 
 
 def sbs_step(logits, sum_logprob, trunc_gumbel, n_in, width, inv_temperature=1.0,
@@ -90,6 +93,7 @@ def sbs_step(logits, sum_logprob, trunc_gumbel, n_in, width, inv_temperature=1.0
     parent = np.full((B, width), -1, dtype=np.int64)
     s_out = np.full((B, width), -np.inf)
     g_out = np.full((B, width), -np.inf)
+    p_out = np.full((B, width), -np.inf)
     lse = np.zeros((B, W_in))
     n_out = np.zeros(B, dtype=np.int64)
     for b in range(B):
@@ -104,7 +108,8 @@ def sbs_step(logits, sum_logprob, trunc_gumbel, n_in, width, inv_temperature=1.0
         m = len(r["tokens"])
         tokens[b, :m], parent[b, :m] = r["tokens"], r["parent"]
         s_out[b, :m], g_out[b, :m] = r["sum_logprob"], r["trunc_gumbel"]
+        p_out[b, :m] = r["perturbed"]
         lse[b, :n] = r["lse"]
         n_out[b] = m
     return dict(tokens=tokens, parent=parent, sum_logprob=s_out,
-                trunc_gumbel=g_out, n_out=n_out, lse=lse)
+                trunc_gumbel=g_out, perturbed=p_out, n_out=n_out, lse=lse)

@@ -10,7 +10,7 @@ from oracle import sbs as o_sbs
 from oracle import tree_attention as o_attn
 from paper_2402_14160_amd import binding, draft_tree, workloads
 from tests.gpu_util import (LOGP_TOL, NEAR_TIE, check_topk_against_oracle, dev, oracle_tree_const,
-                            say, to_np)
+                            psi_tolerance, say, sbs_near_tie, to_np)
 
 pytestmark = pytest.mark.gpu
 
@@ -119,14 +119,13 @@ def test_sbs_step_matches_oracle(B, W_in, V, W, inv_t):
     near = 0
     for b in range(B):
         n = int(ref["n_out"][b])
-        gaps = -np.diff(ref["trunc_gumbel"][b, :n])
-        if np.any(gaps < NEAR_TIE):
+        if sbs_near_tie(ref, b, n, gamma):
             near += 1
             continue
         assert np.array_equal(to_np(g["tokens"])[b, :n], ref["tokens"][b, :n])
         assert np.array_equal(to_np(g["parent"])[b, :n], ref["parent"][b, :n])
         assert np.allclose(to_np(g["sum_logprob"])[b, :n], ref["sum_logprob"][b, :n], rtol=1e-6, atol=LOGP_TOL)
-        assert np.allclose(to_np(g["trunc_gumbel"])[b, :n], ref["trunc_gumbel"][b, :n], rtol=1e-6, atol=2e-5)
+        assert np.all(np.abs(to_np(g["trunc_gumbel"])[b, :n] - ref["trunc_gumbel"][b, :n]) <= psi_tolerance(ref, b, n, gamma))
         assert np.all(to_np(g["tokens"])[b, n:] == -1)
         live = int(n_in[b])
         assert np.allclose(to_np(g["lse"])[b, :live], ref["lse"][b, :live], rtol=0, atol=LOGP_TOL)
@@ -158,12 +157,12 @@ def test_sbs_step_split_rows_with_sparse_and_dead_rows():
         assert np.array_equal(to_np(g["n_out"]), ref["n_out"])
         for b in range(B):
             n = int(ref["n_out"][b])
-            if np.any(-np.diff(ref["trunc_gumbel"][b, :n]) < NEAR_TIE):
+            if sbs_near_tie(ref, b, n, gamma):
                 continue
             assert np.array_equal(to_np(g["tokens"])[b, :n], ref["tokens"][b, :n])
             assert np.array_equal(to_np(g["parent"])[b, :n], ref["parent"][b, :n])
             assert np.allclose(to_np(g["sum_logprob"])[b, :n], ref["sum_logprob"][b, :n], rtol=1e-6, atol=LOGP_TOL)
-            assert np.allclose(to_np(g["trunc_gumbel"])[b, :n], ref["trunc_gumbel"][b, :n], rtol=1e-6, atol=2e-5)
+            assert np.all(np.abs(to_np(g["trunc_gumbel"])[b, :n] - ref["trunc_gumbel"][b, :n]) <= psi_tolerance(ref, b, n, gamma))
             assert np.all(to_np(g["tokens"])[b, n:] == -1)
             live = int(n_in[b])
             assert np.allclose(to_np(g["lse"])[b, :live], ref["lse"][b, :live], rtol=0, atol=LOGP_TOL)
