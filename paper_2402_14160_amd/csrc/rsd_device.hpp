@@ -141,6 +141,14 @@ __device__ __forceinline__ MaxSum wave_merge(MaxSum v) {
     return v;
 }
 
+// The same merge without LDS traffic: the maximum and the rescaled sums go through the DPP
+// reductions (one exponential per lane).  All lanes receive the result; fixed order.
+__device__ __forceinline__ MaxSum wave_merge_dpp(MaxSum v) {
+    const float m = wave_max(v.m);
+    if (m == -INFINITY) return MaxSum{-INFINITY, 0.f};  // (uniform)
+    return MaxSum{m, wave_sum(v.s * __builtin_amdgcn_exp2f(v.m - m))};
+}
+
 // Workgroup-wide merge of (max,sum) pairs.  `scratch` holds one pair per wave.
 // Every thread returns the merged pair.  Contains two barriers.
 template <int THREADS>

@@ -93,7 +93,6 @@ template <int CH, bool WANT_LSE>
 __global__ __launch_bounds__(kTopkThreads, (CH <= 8 && !WANT_LSE) ? 8 : 4) void gumbel_topk_kernel(TopkArgs a) {
     __shared__ MaxSum s_ms[kTopkWaves];
     __shared__ float s_wmax[kTopkWaves];
-    __shared__ float s_tau;
     __shared__ int s_cnt;
     __shared__ float s_cval[kCandMax];
     __shared__ int s_cidx[kCandMax];
@@ -126,7 +125,10 @@ __global__ __launch_bounds__(kTopkThreads, (CH <= 8 && !WANT_LSE) ? 8 : 4) void 
     const float *zrow = a.logits + (int64_t)row * a.ld;
     const float4 *z4 = reinterpret_cast<const float4 *>(zrow);
     const int V = a.V;
-    const int nfull = dead ? 0 : (V >> 2);  // chunks of four entries that lie fully inside the row
+    // chunks of four entries that lie fully inside the row (a dead row is read like any other --
+    // it is memory of the same tensor -- so that the loads below do not wait for n_live; its k = 0
+    // keeps it out of every output)
+    const int nfull = V >> 2;
     const float inv_t = a.inv_t;
     // this workgroup's chunk range [c0, c1) of the row; the ragged tail goes with the last segment
     const int per = (nfull + nseg - 1) / nseg;
@@ -194,36 +196,37 @@ __global__ __launch_bounds__(kTopkThreads, (CH <= 8 && !WANT_LSE) ? 8 : 4) void 
     // vocabulary index of register slot i
     auto slot_index = [&](int i) { return i < CH * 4 ? (((c0 + (i >> 2) * kTopkThreads + tid) << 2) | (i & 3)) : (nfull << 2) + tid; };
 
-    // ---- row normaliser -------------------------------------------------
-    float lse_nat = 0.f;
-    if (WANT_LSE) {
-        acc = block_merge<kTopkThreads>(acc, s_ms);
-        lse_nat = (acc.m + log2f(acc.s)) * kLn2;
-    }
-
+    // ---- per-wave partials, one barrier, then every wave finishes both reductions itself ----
     float tmax = -INFINITY;
 #pragma unroll
     for (int e = 0; e < CH * 4 + 1; ++e) tmax = fmaxf(tmax, val[e]);
-    // ---- threshold: k-th largest wave maximum ----------------------------
     const float wmax = wave_max(tmax);
-    if (lane == 0) s_wmax[wave] = wmax;
+    if (WANT_LSE) acc = wave_merge_dpp(acc);
+    if (lane == 0) {
+        s_wmax[wave] = wmax;
+        if (WANT_LSE) s_ms[wave] = acc;
+    }
     if (tid == 0) {
         s_cnt = 0;
         s_nout = 0;
     }
     __syncthreads();
-    if (tid < kTopkWaves) {
-        // rank of this wave's maximum among the 16 (ties by wave index)
-        const float mine = s_wmax[tid];
-        int rank = 0;
-        for (int o = 0; o < kTopkWaves; ++o) {
-            const float ov = s_wmax[o];
-            rank += (ov > mine) || (ov == mine && o < tid);
-        }
-        if (rank == max(k, 1) - 1) s_tau = mine;
+    // row normaliser
+    float lse_nat = 0.f;
+    if (WANT_LSE) {
+        acc = wave_merge_dpp(lane < kTopkWaves ? s_ms[lane] : MaxSum{-INFINITY, 0.f});
+        lse_nat = (acc.m + log2f(acc.s)) * kLn2;
     }
-    __syncthreads();
-    const float tau = s_tau;
+    // threshold: the k-th largest wave maximum (ranks of the 16 maxima, ties by wave index)
+    const float mine = lane < kTopkWaves ? s_wmax[lane] : -INFINITY;
+    int mrank = 0;
+#pragma unroll
+    for (int o = 0; o < kTopkWaves; ++o) {
+        const float ov = read_lane(mine, o);
+        mrank += (ov > mine) || (ov == mine && o < lane);
+    }
+    const uint64_t hit = __builtin_amdgcn_ballot_w64(lane < kTopkWaves && mrank == max(k, 1) - 1);
+    const float tau = read_lane(mine, hit ? __builtin_ctzll(hit) : 0);
 
     // ---- gather everything at or above the threshold ---------------------
     if (k > 0 && tmax >= tau && tmax > -INFINITY) {
@@ -244,7 +247,19 @@ __global__ __launch_bounds__(kTopkThreads, (CH <= 8 && !WANT_LSE) ? 8 : 4) void 
 
     if (ncand <= kCandMax) {
         // ---- wave 0 picks the k best candidates in order -----------------
-        if (wave == 0) {
+        if (wave == 0 && ncand <= kWave) {
+            // one candidate per lane: its rank among them is its place in the output
+            const float v = lane < ncand ? s_cval[lane] : -INFINITY;
+            const int i = lane < ncand ? s_cidx[lane] : INT_MAX;
+            int rank = 0;
+            for (int t = 0; t < ncand; ++t)
+                rank += better(read_lane(v, t), __builtin_amdgcn_readlane(i, t), v, i);
+            if (lane < ncand && rank < k) {
+                s_outv[rank] = v;
+                s_outi[rank] = i;
+            }
+            if (lane == 0) s_nout = min(k, ncand);  // (every candidate is finite)
+        } else if (wave == 0) {
             for (int r = 0; r < k; ++r) {
                 float bv = -INFINITY;
                 int bi = INT_MAX, bslot = -1;
@@ -355,6 +370,8 @@ struct SbsSelectArgs {
 __global__ __launch_bounds__(256) void sbs_select_kernel(SbsSelectArgs a) {
     __shared__ __align__(16) double s_psi[256];
     __shared__ __align__(16) int s_key[256];
+    __shared__ __align__(16) int s_key2[256];
+    __shared__ float s_rpert[256];
     __shared__ float s_lse[RSD_K_MAX];   // per row (0 when the lists are already normalised)
     __shared__ float s_top[RSD_K_MAX];   // per row: largest perturbed score (same offset as the lists)
     __shared__ MaxSum s_sms[RSD_K_MAX * 8];
@@ -384,7 +401,34 @@ __global__ __launch_bounds__(256) void sbs_select_kernel(SbsSelectArgs a) {
         s_sms[w * nseg + sg] = row_live ? ms_in : MaxSum{-INFINITY, 0.f};
         s_stop[w * nseg + sg] = (row_live && cnt > 0) ? pert_in : -INFINITY;
     }
+    const int slots = a.W_in * a.W;  // entries of the table that the last ranking runs over
+    if (t < ((slots + 3) & ~3)) {
+        s_psi[t] = -INFINITY;
+        s_key2[t] = INT_MAX;
+    }
+    bool live = row_live && j < cnt;
+    if (nseg > 1) {  // (token array of the row ranking below)
+        s_rpert[t] = live ? pert_in : -INFINITY;
+        s_key[t] = live ? tok_in : INT_MAX;
+    }
     __syncthreads();
+    // With segments a row has nseg * W candidates, of which only its W best by perturbed score
+    // can be selected: rank inside the row first (fp32), so that the fp64 part below and the
+    // ranking over all rows handle W_in * W entries, as without segments.
+    int place = j;  // position inside the row's list of (at most) W
+    if (nseg > 1) {
+        const int base = w * per_row;
+        int rr = 0;
+        if (live) {
+            for (int o = 0; o < per_row; ++o) {
+                const float op = s_rpert[base + o];
+                const int ot = s_key[base + o];
+                rr += (int)((op > pert_in) | ((op == pert_in) & (ot < tok_in)));
+            }
+        }
+        live = live && rr < a.W;
+        place = rr;
+    }
     if (t < a.W_in) {
         float lse = 0.f, top = -INFINITY;
         MaxSum ms{-INFINITY, 0.f};
@@ -400,7 +444,6 @@ __global__ __launch_bounds__(256) void sbs_select_kernel(SbsSelectArgs a) {
     __syncthreads();
     double psi = -INFINITY, phi = -INFINITY;
     int tok = -1;
-    const bool live = row_live && j < cnt;
     if (live) {
         tok = tok_in;
         const double sigma = (double)sigma_in;
@@ -418,18 +461,20 @@ __global__ __launch_bounds__(256) void sbs_select_kernel(SbsSelectArgs a) {
             psi = gamma - (fmax(v, 0.0) + log1p(exp(-fabs(v))));
         }
     }
-    s_psi[t] = live ? psi : -INFINITY;
-    s_key[t] = live ? (w * a.V + tok) : INT_MAX;
+    // compact table of W_in * W entries: entry w * W + place (the others were initialised dead)
+    const int mykey = live ? (w * a.V + tok) : INT_MAX;
+    if (live) {
+        s_psi[w * a.W + place] = psi;
+        s_key2[w * a.W + place] = mykey;
+    }
     __syncthreads();
-    // rank of this slot among all slots (all 256 entries of the two arrays are initialised, so
-    // the loop may run past the last used slot in steps of four: 16-byte LDS reads)
+    // rank of this candidate among all (the table is padded to a multiple of four entries:
+    // 16-byte LDS reads)
     int total = 0, rank = 0;
-    const int slots = a.W_in * per_row;  // thread slots that can hold a candidate
-    const int mykey = s_key[t];
     for (int o = 0; o < slots; o += 4) {
         const double2 p01 = *reinterpret_cast<const double2 *>(&s_psi[o]);
         const double2 p23 = *reinterpret_cast<const double2 *>(&s_psi[o + 2]);
-        const int4 k4 = *reinterpret_cast<const int4 *>(&s_key[o]);
+        const int4 k4 = *reinterpret_cast<const int4 *>(&s_key2[o]);
         const double op[4] = {p01.x, p01.y, p23.x, p23.y};
         const int ok[4] = {k4.x, k4.y, k4.z, k4.w};
 #pragma unroll
