@@ -915,8 +915,8 @@ __device__ __forceinline__ WalkResult walk_tree(const RrsArgs &a, int b, int lan
 // the path.
 __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
     __shared__ GroupRec g;
-    __shared__ float s_v[kFinalThreads / kWave];
-    __shared__ int s_i[kFinalThreads / kWave];
+    __shared__ float s_v[2 * kFinalThreads / kWave];
+    __shared__ int s_i[2 * kFinalThreads / kWave];
     __shared__ int s_last;
     __shared__ int s_node;
     __shared__ uint32_t s_flags;
@@ -958,8 +958,7 @@ __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
     float bv, av;
     int bi, ai;
     final_sample_range<kFinalThreads>(a, b, node, g, c_lo, c_hi, bv, bi, av, ai);
-    block_argmax<kFinalThreads>(bv, bi, s_v, s_i);
-    block_argmax<kFinalThreads>(av, ai, s_v, s_i);
+    block_argmax_pair<kFinalThreads>(bv, bi, av, ai, s_v, s_i);
     if (nsplit > 1) {
         if (threadIdx.x == 0) {
             if (bi != INT_MAX) atomicMax(&a.fkey[2 * b], pack_key(bv, bi));
@@ -997,8 +996,8 @@ __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
 template <int THREADS, int CH, int CL>
 __global__ __launch_bounds__(THREADS) void rrs_path_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
-    __shared__ float s_v[THREADS / kWave];
-    __shared__ int s_i[THREADS / kWave];
+    __shared__ float s_v[2 * THREADS / kWave];
+    __shared__ int s_i[2 * THREADS / kWave];
     __shared__ int s_nacc;
     __shared__ uint32_t s_flags;
     const int b = blockIdx.x;
@@ -1061,8 +1060,7 @@ __global__ __launch_bounds__(THREADS) void rrs_path_kernel(RrsArgs a) {
     float bv, av;
     int bi, ai;
     final_sample_range<THREADS>(a, b, node, sh.g, 0, a.V >> 2, bv, bi, av, ai);
-    block_argmax<THREADS>(bv, bi, s_v, s_i);
-    block_argmax<THREADS>(av, ai, s_v, s_i);
+    block_argmax_pair<THREADS>(bv, bi, av, ai, s_v, s_i);
     if (tid == 0) {
         uint32_t flags = s_flags;
         int tokn = bi;

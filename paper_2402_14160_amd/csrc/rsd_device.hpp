@@ -211,4 +211,48 @@ __device__ __forceinline__ void block_argmax(float &v, int &i, float *sv, int *s
     i = bi;
 }
 
+// Wave-wide arg-max with the `better` ordering through DPP reductions (no LDS traffic): the
+// maximum first, then the lowest index among the lanes that hold it.
+template <int CTRL>
+__device__ __forceinline__ int dpp_move_i(int v) {
+    return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, false);
+}
+__device__ __forceinline__ int wave_min_int(int v) {
+    v = min(v, dpp_move_i<0xB1>(v));
+    v = min(v, dpp_move_i<0x4E>(v));
+    v = min(v, dpp_move_i<0x124>(v));
+    v = min(v, dpp_move_i<0x128>(v));
+    return min(min(__builtin_amdgcn_readlane(v, 0), __builtin_amdgcn_readlane(v, 16)),
+               min(__builtin_amdgcn_readlane(v, 32), __builtin_amdgcn_readlane(v, 48)));
+}
+__device__ __forceinline__ void wave_argmax_dpp(float &v, int &i) {
+    const float m = wave_max(v);
+    i = wave_min_int(v == m ? i : INT_MAX);
+    v = m;
+}
+
+// Two workgroup-wide arg-maxima at once (one barrier; the scratch arrays are written once per
+// call, so a kernel that calls this again has to put a barrier of its own in between).
+template <int THREADS>
+__device__ __forceinline__ void block_argmax_pair(float &v0, int &i0, float &v1, int &i1, float *sv, int *si) {
+    constexpr int NW = THREADS / kWave;
+    static_assert(NW <= kWave, "one lane per wave");
+    wave_argmax_dpp(v0, i0);
+    wave_argmax_dpp(v1, i1);
+    const int wave = threadIdx.x / kWave, lane = threadIdx.x & (kWave - 1);
+    if (lane == 0) {
+        sv[wave] = v0;
+        si[wave] = i0;
+        sv[NW + wave] = v1;
+        si[NW + wave] = i1;
+    }
+    __syncthreads();
+    v0 = lane < NW ? sv[lane] : -INFINITY;
+    i0 = lane < NW ? si[lane] : INT_MAX;
+    v1 = lane < NW ? sv[NW + lane] : -INFINITY;
+    i1 = lane < NW ? si[NW + lane] : INT_MAX;
+    wave_argmax_dpp(v0, i0);
+    wave_argmax_dpp(v1, i1);
+}
+
 }  // namespace rsd

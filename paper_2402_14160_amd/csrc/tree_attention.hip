@@ -723,15 +723,33 @@ __global__ __launch_bounds__(kWave) void tree_attn_merge_kernel(AttnArgs a) {
     const int lane = threadIdx.x;
     const float wm = lane < splits ? a.ws_m[orow * a.ws_splits + lane] : -INFINITY;
     const float wl = lane < splits ? a.ws_l[orow * a.ws_splits + lane] : 0.f;
+    // the partial outputs do not depend on the weights: the first four splits' values of this
+    // lane's (at most two: D <= 128 on this path) columns are asked for in the same round trip
+    const float *po = a.ws_o + orow * a.ws_splits * a.D;
+    constexpr int kEarly = 4;
+    float early[kEarly][2];
+#pragma unroll
+    for (int s = 0; s < kEarly; ++s) {
+#pragma unroll
+        for (int c = 0; c < 2; ++c) {
+            const int d = lane + c * kWave;
+            early[s][c] = (s < splits && d < a.D) ? po[(int64_t)s * a.D + d] : 0.f;
+        }
+    }
     const float m = wave_max(wm);
     const float w = (wm == -INFINITY) ? 0.f : exp2f(wm - m);  // weight of this lane's split
     const float lsum = wave_sum(w * wl);
     const float inv = lsum > 0.f ? 1.f / lsum : 0.f;
-    const float *po = a.ws_o + orow * a.ws_splits * a.D;
-    for (int d = lane; d < a.D; d += kWave) {
+#pragma unroll
+    for (int c = 0; c < 2; ++c) {
+        const int d = lane + c * kWave;
         float acc = 0.f;
-        for (int s = 0; s < splits; ++s) acc += __shfl(w, s, kWave) * po[(int64_t)s * a.D + d];
-        a.out[orow * a.D + d] = acc * inv;
+#pragma unroll
+        for (int s = 0; s < kEarly; ++s) acc += read_lane(w, s) * early[s][c];  // (w = 0 beyond the last split)
+        if (d < a.D) {
+            for (int s = kEarly; s < splits; ++s) acc += __shfl(w, s, kWave) * po[(int64_t)s * a.D + d];
+            a.out[orow * a.D + d] = acc * inv;
+        }
     }
     if (a.lse_out && lane == 0) a.lse_out[orow] = (m + log2f(lsum)) * kLn2;
 }
