@@ -8,7 +8,8 @@
  *    never allocates, frees or keeps any of them.  Scratch memory comes from the
  *    caller through (workspace, workspace_bytes); the matching
  *    rsd_*_workspace_bytes() call gives the size needed (it may be 0, then
- *    workspace may be NULL).  Workspace contents need not be initialised.
+ *    workspace may be NULL).  Workspace contents need not be initialised; the
+ *    pointer must be 16-byte aligned (RSD_ERR_WORKSPACE otherwise).
  *  - `stream` is a hipStream_t passed as void*.  Calls only enqueue work on it
  *    and never synchronise; outputs are valid once the stream has drained.
  *  - Return value: RSD_OK or a negative rsd_status.  On an error nothing is
@@ -45,7 +46,7 @@ typedef enum rsd_status {
     RSD_ERR_NULL = -1,        /* a required pointer is NULL                              */
     RSD_ERR_SHAPE = -2,       /* a size is out of range or a pointer/stride is misaligned */
     RSD_ERR_TREE = -3,        /* host-checked tree violates the layout contract          */
-    RSD_ERR_WORKSPACE = -4,   /* workspace missing or too small                          */
+    RSD_ERR_WORKSPACE = -4,   /* workspace missing, too small or not 16-byte aligned      */
     RSD_ERR_LAUNCH = -5,      /* the HIP runtime refused a launch                        */
     RSD_ERR_UNSUPPORTED = -6  /* valid request outside what the kernels implement        */
 } rsd_status;

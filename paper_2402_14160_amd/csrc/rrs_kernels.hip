@@ -1109,7 +1109,7 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
     if (mode != RSD_MODE_PATH && mode != RSD_MODE_ALL_GROUPS) return RSD_ERR_UNSUPPORTED;
     if (B == 0) return RSD_OK;
     const size_t need = rsd_recursive_reject_workspace_bytes(B, N_max, V);
-    if (!workspace || workspace_bytes < need) return RSD_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return RSD_ERR_WORKSPACE;
     char *ws = static_cast<char *>(workspace);
     RrsArgs a{};
     a.zd = draft_logits; a.zt = target_logits; a.B = B; a.N = N_max; a.V = V;

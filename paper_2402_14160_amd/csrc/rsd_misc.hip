@@ -9,7 +9,7 @@ extern "C" const char *rsd_status_string(int32_t status) {
         case RSD_ERR_NULL: return "a required pointer is NULL";
         case RSD_ERR_SHAPE: return "a size is out of range or a pointer/stride is misaligned";
         case RSD_ERR_TREE: return "tree violates the layout contract (root first, parent[i] < i)";
-        case RSD_ERR_WORKSPACE: return "workspace missing or too small";
+        case RSD_ERR_WORKSPACE: return "workspace missing, too small or not 16-byte aligned";
         case RSD_ERR_LAUNCH: return "the HIP runtime refused a launch";
         case RSD_ERR_UNSUPPORTED: return "request outside what the kernels implement";
         default: return "unknown status";

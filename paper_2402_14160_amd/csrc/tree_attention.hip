@@ -1015,7 +1015,7 @@ extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const
     for (int i = 0; i < nseg; ++i) a.ws_splits = seg[i].splits > a.ws_splits ? seg[i].splits : a.ws_splits;
     if (a.ws_splits > 1) {
         const size_t need = rsd_tree_attention_workspace_bytes(dtype, B, H_q, H_kv, N_max, D, P_max, num_splits);
-        if (!workspace || workspace_bytes < need) return RSD_ERR_WORKSPACE;
+        if (!workspace || workspace_bytes < need || !aligned16(workspace)) return RSD_ERR_WORKSPACE;
         const size_t rows = (size_t)B * H_q * N_max;
         char *ws = static_cast<char *>(workspace);
         a.ws_o = reinterpret_cast<float *>(ws);

@@ -602,7 +602,7 @@ extern "C" int32_t rsd_sbs_step(const float *logits, const float *sum_logprob,
         return RSD_ERR_SHAPE;
     if (B == 0) return RSD_OK;
     const size_t need = rsd_sbs_step_workspace_bytes(B, W_in, V, W);
-    if (!workspace || workspace_bytes < need) return RSD_ERR_WORKSPACE;
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return RSD_ERR_WORKSPACE;
     const size_t rows = (size_t)B * W_in;
     const int nseg = sbs_segments(B, W_in, V, W);
     const size_t lists = rows * nseg;

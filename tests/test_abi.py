@@ -94,6 +94,11 @@ def test_argument_errors_are_returned_before_any_launch():
     assert lib.rsd_recursive_reject(fake, fake, 1, 8, 64, 1.0, fake, fake, fake, null, 0, 0, 0,
                                     fake, null, 8, fake, fake, null, null, null, null, null, 0,
                                     null) == -4
+    assert lib.rsd_recursive_reject(fake, fake, 1, 8, 64, 1.0, fake, fake, fake, null, 0, 0, 0,
+                                    fake, null, 8, fake, fake, null, null, null, null, ctypes.c_void_p(4104),
+                                    1 << 20, null) == -4                           # misaligned workspace
+    assert lib.rsd_sbs_step(fake, fake, fake, fake, null, null, 2, 4, 64, 2, 1.0, 0, 0,
+                            fake, fake, fake, fake, fake, null, ctypes.c_void_p(4104), 1 << 20, null) == -4
 
 
 def test_workspace_sizes_are_consistent():
