@@ -79,7 +79,13 @@ __device__ __forceinline__ void decode_block(const AttnArgs &a, int &b, int &kvh
 
 // Ancestor-or-self bit-sets of all nodes of one tree into `anc` ([n][kAncWords]).
 // Parent values are clamped into [0, j-1], so the walk always terminates.
-__device__ __forceinline__ void build_ancestors(const int *par, int n, uint64_t *anc, int threads) {
+// The parent array goes to LDS first (one round trip): the walk up the tree is then a chain of
+// LDS reads instead of one dependent global load per level.  Contains a barrier: every thread of
+// the workgroup must call it.
+__device__ __forceinline__ void build_ancestors(const int *gpar, int n, uint64_t *anc, int threads) {
+    __shared__ int par[RSD_NODES_MAX];
+    for (int i = threadIdx.x; i < n; i += threads) par[i] = gpar[i];
+    __syncthreads();
     for (int i = threadIdx.x; i < n; i += threads) {
         uint64_t w[kAncWords];
 #pragma unroll
@@ -220,7 +226,6 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int c16 = lane & 15, g = lane >> 4;
     const bool do_tree = (sp == a.splits - 1);
-    if (do_tree) build_ancestors(a.par + (int64_t)b * a.N, n, anc, kAttnThreads);
 
     // ---- this lane's query ------------------------------------------------
     const int R = a.row_base + rb * kRowsPerBlock + wave * 16 + c16;
@@ -264,6 +269,8 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     float m = -INFINITY, l = 0.f;
 
     if (ntiles > 0) stage(0);
+    // (after the first tile and the query rows have been asked for: one round trip for all three)
+    if (do_tree) build_ancestors(a.par + (int64_t)b * a.N, n, anc, kAttnThreads);
     wait_tile_loads<0>();
     __syncthreads();
 
@@ -427,7 +434,6 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int q32 = lane & 31, h = lane >> 5;
     const bool do_tree = (sp == a.splits - 1);
-    if (do_tree) build_ancestors(a.par + (int64_t)b * a.N, n, anc, THREADS);
 
     const int R = a.row_base + rb * RPB + wave * 32 + q32;
     const bool qvalid = R < rows;
@@ -490,6 +496,7 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
 #pragma unroll
     for (int u = 0; u < STAGES - 1; ++u)
         if (u < ntiles) stage(u);
+    if (do_tree) build_ancestors(a.par + (int64_t)b * a.N, n, anc, THREADS);
     if (ntiles > STAGES - 2 && STAGES > 2) {
         if (ntiles > 1) wait_tile_loads<(STAGES - 2) * LOADS>(); else wait_tile_loads<0>();
     } else {
