@@ -48,7 +48,8 @@ typedef enum rsd_status {
     RSD_ERR_TREE = -3,        /* host-checked tree violates the layout contract          */
     RSD_ERR_WORKSPACE = -4,   /* workspace missing, too small or not 16-byte aligned      */
     RSD_ERR_LAUNCH = -5,      /* the HIP runtime refused a launch                        */
-    RSD_ERR_UNSUPPORTED = -6  /* valid request outside what the kernels implement        */
+    RSD_ERR_UNSUPPORTED = -6, /* valid request outside what the kernels implement        */
+    RSD_ERR_TOO_LARGE = -7    /* request needs more scratch than a fixed-size buffer holds  */
 } rsd_status;
 
 /* Compile-time limits. */
@@ -142,6 +143,30 @@ int32_t rsd_sbs_step(const float *logits, const float *sum_logprob, const float 
                      int32_t *tokens, int32_t *parent, float *sum_logprob_out,
                      float *trunc_gumbel_out, int32_t *n_out, float *lse,
                      void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * rsd_sbs_step for callers that cannot allocate device memory or bring a
+ * workspace: code under HIP graph capture, tight serving loops, harnesses that
+ * forbid hipMalloc.  Same arguments (without the workspace pair), same kernels and
+ * bit-identical outputs as rsd_sbs_step; the per-row candidate lists live in a
+ * device array of RSD_SBS_STATIC_SCRATCH_BYTES bytes inside the library (one copy
+ * per GPU, held until the process ends).  The call allocates and frees nothing.
+ * Limit: rsd_sbs_step_workspace_bytes(B, W_in, V, W) <= RSD_SBS_STATIC_SCRATCH_BYTES,
+ *   else RSD_ERR_TOO_LARGE and nothing is launched (e.g. B * W_in up to 1024 rows
+ *   at W = 16 fit).
+ * All calls on one GPU share that GPU's array: two calls whose kernels may overlap
+ * (different streams, no ordering between them) race; calls on one stream do not.
+ * The array keeps the previous call's contents; nothing in it needs clearing, every
+ * slot a call reads was written by that call.  The first call on a device looks the
+ * array's address up (no allocation); make that call outside stream capture.
+ * ------------------------------------------------------------------------- */
+#define RSD_SBS_STATIC_SCRATCH_BYTES 524288
+int32_t rsd_sbs_step_static(const float *logits, const float *sum_logprob,
+                            const float *trunc_gumbel, const int32_t *n_in, const int32_t *seq_id,
+                            const int32_t *node_id, int32_t B, int32_t W_in, int32_t V, int32_t W,
+                            float inv_temperature, uint64_t seed, uint32_t step,
+                            int32_t *tokens, int32_t *parent, float *sum_logprob_out,
+                            float *trunc_gumbel_out, int32_t *n_out, float *lse, void *stream);
 
 /* ---------------------------------------------------------------------------
  * Tree-masked attention of the draft-tree tokens (Sec. 3.2.2, tree evaluation

@@ -37,6 +37,8 @@ _SIGNATURES = {
     "rsd_sbs_step_workspace_bytes": (_sz, [_i32, _i32, _i32, _i32]),
     "rsd_sbs_step": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _f32, _u64, _u32,
                             _vp, _vp, _vp, _vp, _vp, _vp, _vp, _sz, _vp]),
+    "rsd_sbs_step_static": (_i32, [_vp, _vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _f32, _u64, _u32,
+                                   _vp, _vp, _vp, _vp, _vp, _vp, _vp]),
     "rsd_tree_attention_workspace_bytes": (_sz, [_i32] * 8),
     "rsd_tree_attention": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32,
                                   _i64, _i64, _i64, _vp, _vp, _vp, _f32, _i32, _vp, _vp, _vp, _sz, _vp]),
@@ -145,20 +147,39 @@ def gumbel_topk(logits, k_max, k_per_row=None, inv_temperature=1.0, seq_id=None,
 
 
 def sbs_step(logits, sum_logprob, trunc_gumbel, n_in, width, inv_temperature=1.0, seq_id=None,
-             node_id=None, seed=0, step=0):
-    """rsd_sbs_step; returns dict(tokens, parent, sum_logprob, trunc_gumbel, n_out, lse)."""
+             node_id=None, seed=0, step=0, out=None, static_scratch=False):
+    """rsd_sbs_step; returns dict(tokens, parent, sum_logprob, trunc_gumbel, n_out, lse).
+    `out` (a dict as returned) makes the call write into existing tensors; with
+    static_scratch=True the call goes to rsd_sbs_step_static, which takes no workspace, so that
+    with `out` given nothing at all is allocated."""
     _dev(logits, torch.float32)
     _dev(sum_logprob, torch.float32)
     _dev(trunc_gumbel, torch.float32)
     _dev(n_in, torch.int32)
     B, W_in, V = logits.shape
     dev = logits.device
-    tokens = torch.empty((B, width), dtype=torch.int32, device=dev)
-    parent = torch.empty((B, width), dtype=torch.int32, device=dev)
-    s_out = torch.empty((B, width), dtype=torch.float32, device=dev)
-    g_out = torch.empty((B, width), dtype=torch.float32, device=dev)
-    n_out = torch.empty(B, dtype=torch.int32, device=dev)
-    lse = torch.empty((B, W_in), dtype=torch.float32, device=dev)
+    if out is not None:
+        tokens, parent, s_out, g_out = out["tokens"], out["parent"], out["sum_logprob"], out["trunc_gumbel"]
+        n_out, lse = out["n_out"], out["lse"]
+        for t, dt in ((tokens, torch.int32), (parent, torch.int32), (s_out, torch.float32),
+                      (g_out, torch.float32), (n_out, torch.int32), (lse, torch.float32)):
+            _dev(t, dt)
+        if tokens.shape != (B, width) or lse.shape != (B, W_in):
+            raise ValueError("output tensors do not fit this call")
+    else:
+        tokens = torch.empty((B, width), dtype=torch.int32, device=dev)
+        parent = torch.empty((B, width), dtype=torch.int32, device=dev)
+        s_out = torch.empty((B, width), dtype=torch.float32, device=dev)
+        g_out = torch.empty((B, width), dtype=torch.float32, device=dev)
+        n_out = torch.empty(B, dtype=torch.int32, device=dev)
+        lse = torch.empty((B, W_in), dtype=torch.float32, device=dev)
+    if static_scratch:
+        _check(lib().rsd_sbs_step_static(_ptr(logits), _ptr(sum_logprob), _ptr(trunc_gumbel), _ptr(n_in),
+                                         _ptr(_opt_i32(seq_id)), _ptr(_opt_i32(node_id)), B, W_in, V, width,
+                                         inv_temperature, seed, step, _ptr(tokens), _ptr(parent), _ptr(s_out),
+                                         _ptr(g_out), _ptr(n_out), _ptr(lse), _stream()))
+        return dict(tokens=tokens, parent=parent, sum_logprob=s_out, trunc_gumbel=g_out,
+                    n_out=n_out, lse=lse)
     nbytes = lib().rsd_sbs_step_workspace_bytes(B, W_in, V, width)
     ws = _workspace(nbytes, dev)
     _check(lib().rsd_sbs_step(_ptr(logits), _ptr(sum_logprob), _ptr(trunc_gumbel), _ptr(n_in),

@@ -12,6 +12,7 @@ extern "C" const char *rsd_status_string(int32_t status) {
         case RSD_ERR_WORKSPACE: return "workspace missing, too small or not 16-byte aligned";
         case RSD_ERR_LAUNCH: return "the HIP runtime refused a launch";
         case RSD_ERR_UNSUPPORTED: return "request outside what the kernels implement";
+        case RSD_ERR_TOO_LARGE: return "request needs more scratch than the library's fixed-size buffer holds";
         default: return "unknown status";
     }
 }

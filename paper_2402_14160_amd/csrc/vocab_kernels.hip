@@ -9,6 +9,8 @@
 #include <limits.h>
 #include <math.h>
 
+#include <mutex>
+
 #include "../../include/rsd.h"
 #include "rsd_device.hpp"
 
@@ -587,26 +589,31 @@ extern "C" size_t rsd_sbs_step_workspace_bytes(int32_t B, int32_t W_in, int32_t 
     return 3 * align_up(lists * W * 4, 256) + align_up(lists * 4, 256) + align_up(lists * sizeof(MaxSum), 256);
 }
 
-extern "C" int32_t rsd_sbs_step(const float *logits, const float *sum_logprob,
-                                const float *trunc_gumbel, const int32_t *n_in,
-                                const int32_t *seq_id, const int32_t *node_id, int32_t B,
-                                int32_t W_in, int32_t V, int32_t W, float inv_temperature,
-                                uint64_t seed, uint32_t step, int32_t *tokens, int32_t *parent,
-                                float *sum_logprob_out, float *trunc_gumbel_out, int32_t *n_out,
-                                float *lse, void *workspace, size_t workspace_bytes, void *stream) {
+// Shared by rsd_sbs_step and rsd_sbs_step_static: validation and the two launches on a scratch
+// buffer `ws` (device memory, 16-byte aligned, at least rsd_sbs_step_workspace_bytes() long).
+static int32_t sbs_check_args(const float *logits, const float *sum_logprob, const float *trunc_gumbel,
+                              const int32_t *n_in, int32_t B, int32_t W_in, int32_t V, int32_t W,
+                              float inv_temperature, const int32_t *tokens, const int32_t *parent,
+                              const float *sum_logprob_out, const float *trunc_gumbel_out,
+                              const int32_t *n_out) {
     if (!logits || !sum_logprob || !trunc_gumbel || !n_in || !tokens || !parent ||
         !sum_logprob_out || !trunc_gumbel_out || !n_out)
         return RSD_ERR_NULL;
     if (B < 0 || W_in < 1 || W_in > RSD_K_MAX || W < 1 || W > RSD_K_MAX || V < 1 ||
         V > RSD_VOCAB_MAX || W > V || !aligned16(logits) || !(inv_temperature > 0.f) || ((V & 3) && (int64_t)B * W_in > 1))
         return RSD_ERR_SHAPE;
-    if (B == 0) return RSD_OK;
-    const size_t need = rsd_sbs_step_workspace_bytes(B, W_in, V, W);
-    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return RSD_ERR_WORKSPACE;
+    return RSD_OK;
+}
+
+static int32_t sbs_step_on(char *ws, const float *logits, const float *sum_logprob,
+                           const float *trunc_gumbel, const int32_t *n_in, const int32_t *seq_id,
+                           const int32_t *node_id, int32_t B, int32_t W_in, int32_t V, int32_t W,
+                           float inv_temperature, uint64_t seed, uint32_t step, int32_t *tokens,
+                           int32_t *parent, float *sum_logprob_out, float *trunc_gumbel_out,
+                           int32_t *n_out, float *lse, hipStream_t stream) {
     const size_t rows = (size_t)B * W_in;
     const int nseg = sbs_segments(B, W_in, V, W);
     const size_t lists = rows * nseg;
-    char *ws = static_cast<char *>(workspace);
     const size_t seg = align_up(lists * W * 4, 256);
     int *row_tok = reinterpret_cast<int *>(ws);
     float *row_pert = reinterpret_cast<float *>(ws + seg);
@@ -620,7 +627,7 @@ extern "C" int32_t rsd_sbs_step(const float *logits, const float *sum_logprob,
     a.seq_default_is_b = 1; a.node_default_is_w = 1; a.inv_t = inv_temperature;
     a.seed = seed; a.step = step; a.tokens = row_tok; a.perturbed = row_pert;
     a.logprob = row_logp; a.lse = lse; a.count = row_cnt; a.nseg = nseg; a.seg_ms = seg_ms;
-    const int32_t rc = launch_topk(a, (int)rows, (hipStream_t)stream);
+    const int32_t rc = launch_topk(a, (int)rows, stream);
     if (rc != RSD_OK) return rc;
 
     SbsSelectArgs s{};
@@ -629,6 +636,68 @@ extern "C" int32_t rsd_sbs_step(const float *logits, const float *sum_logprob,
     s.sum_logprob = sum_logprob; s.trunc_gumbel = trunc_gumbel; s.n_in = n_in;
     s.W_in = W_in; s.W = W; s.V = V; s.tokens = tokens; s.parent = parent;
     s.sum_out = sum_logprob_out; s.gum_out = trunc_gumbel_out; s.n_out = n_out;
-    hipLaunchKernelGGL(sbs_select_kernel, dim3(B), dim3(256), 0, (hipStream_t)stream, s);
+    hipLaunchKernelGGL(sbs_select_kernel, dim3(B), dim3(256), 0, stream, s);
     return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
+}
+
+extern "C" int32_t rsd_sbs_step(const float *logits, const float *sum_logprob,
+                                const float *trunc_gumbel, const int32_t *n_in,
+                                const int32_t *seq_id, const int32_t *node_id, int32_t B,
+                                int32_t W_in, int32_t V, int32_t W, float inv_temperature,
+                                uint64_t seed, uint32_t step, int32_t *tokens, int32_t *parent,
+                                float *sum_logprob_out, float *trunc_gumbel_out, int32_t *n_out,
+                                float *lse, void *workspace, size_t workspace_bytes, void *stream) {
+    const int32_t bad = sbs_check_args(logits, sum_logprob, trunc_gumbel, n_in, B, W_in, V, W, inv_temperature,
+                                       tokens, parent, sum_logprob_out, trunc_gumbel_out, n_out);
+    if (bad != RSD_OK) return bad;
+    if (B == 0) return RSD_OK;
+    const size_t need = rsd_sbs_step_workspace_bytes(B, W_in, V, W);
+    if (!workspace || workspace_bytes < need || !aligned16(workspace)) return RSD_ERR_WORKSPACE;
+    return sbs_step_on(static_cast<char *>(workspace), logits, sum_logprob, trunc_gumbel, n_in, seq_id,
+                       node_id, B, W_in, V, W, inv_temperature, seed, step, tokens, parent,
+                       sum_logprob_out, trunc_gumbel_out, n_out, lse, (hipStream_t)stream);
+}
+
+// ---------------------------------------------------------------------------
+// The same step for callers that may not allocate: the per-row candidate lists live in a
+// device array of this library instead of a caller's workspace.  Every GPU holds its own copy
+// of the array at its own address, resolved once per device and kept.
+// ---------------------------------------------------------------------------
+static __device__ __align__(256) unsigned char scratch[RSD_SBS_STATIC_SCRATCH_BYTES];
+
+constexpr int kStaticDevicesMax = 64;
+static std::mutex g_scratch_mutex;
+static void *g_scratch_ptr[kStaticDevicesMax];  // device address of `scratch` on device i, or null
+
+extern "C" int32_t rsd_sbs_step_static(const float *logits, const float *sum_logprob,
+                                       const float *trunc_gumbel, const int32_t *n_in,
+                                       const int32_t *seq_id, const int32_t *node_id, int32_t B,
+                                       int32_t W_in, int32_t V, int32_t W, float inv_temperature,
+                                       uint64_t seed, uint32_t step, int32_t *tokens, int32_t *parent,
+                                       float *sum_logprob_out, float *trunc_gumbel_out,
+                                       int32_t *n_out, float *lse, void *stream) {
+    const int32_t bad = sbs_check_args(logits, sum_logprob, trunc_gumbel, n_in, B, W_in, V, W, inv_temperature,
+                                       tokens, parent, sum_logprob_out, trunc_gumbel_out, n_out);
+    if (bad != RSD_OK) return bad;
+    if (rsd_sbs_step_workspace_bytes(B, W_in, V, W) > (size_t)RSD_SBS_STATIC_SCRATCH_BYTES)
+        return RSD_ERR_TOO_LARGE;
+    if (B == 0) return RSD_OK;
+    int dev = -1;
+    if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kStaticDevicesMax) return RSD_ERR_LAUNCH;
+    void *ptr = nullptr;
+    {
+        std::lock_guard<std::mutex> lock(g_scratch_mutex);
+        if (!g_scratch_ptr[dev]) {
+            // (in host code the array's name is only a handle: the device address comes from here)
+            void *p = nullptr;
+            if (hipGetSymbolAddress(&p, HIP_SYMBOL(scratch)) != hipSuccess || !p) return RSD_ERR_LAUNCH;
+            g_scratch_ptr[dev] = p;
+        }
+        ptr = g_scratch_ptr[dev];
+    }
+    // Nothing in the buffer has to start at zero: the Gumbel kernel writes every list slot, count
+    // and partial normaliser that the select kernel reads.
+    return sbs_step_on(static_cast<char *>(ptr), logits, sum_logprob, trunc_gumbel, n_in, seq_id, node_id,
+                       B, W_in, V, W, inv_temperature, seed, step, tokens, parent, sum_logprob_out,
+                       trunc_gumbel_out, n_out, lse, (hipStream_t)stream);
 }

@@ -35,7 +35,7 @@ def test_status_strings_and_version():
     lib = binding.lib()
     assert lib.rsd_version() >= 100
     seen = set()
-    for code in range(0, -7, -1):
+    for code in range(0, -8, -1):
         text = lib.rsd_status_string(code)
         assert text and text not in seen
         seen.add(text)
