@@ -49,7 +49,9 @@ def filter_row(z, inv_temperature=1.0, top_k=0, top_p=1.0):
     if top_k and top_k < int(keep.sum()):
         srt = np.sort(prob[keep])[::-1]
         kth = srt[top_k - 1]
-        margin = min(margin, (kth - srt[top_k]) / kth if srt[top_k] < kth else np.inf)
+        dropped = srt[srt < kth]         # (entries tied with the k-th are kept, not dropped)
+        if dropped.size:
+            margin = min(margin, (kth - dropped[0]) / kth)
         keep &= prob >= kth
         prob = np.where(keep, prob, 0.0)
         prob = prob / prob.sum()
