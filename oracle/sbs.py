@@ -67,12 +67,14 @@ def sbs_step_from_noise(logits, sum_logprob, trunc_gumbel, gumbel, width,
     idx = idx[keep]
     order = np.lexsort((idx, -flat[idx]))      # ties: lower row, then lower token
     sel = idx[order[:width]]
+    ranked = flat[idx[order[:width + 1]]]
+    min_gap = float(np.min(-np.diff(ranked))) if ranked.size > 1 else np.inf
     parent = sel // V
     tokens = sel % V
     return dict(tokens=tokens.astype(np.int64), parent=parent.astype(np.int64),
                 sum_logprob=phi[parent, tokens],                 # step 7
                 trunc_gumbel=psi[parent, tokens], perturbed=phi_tilde[parent, tokens],
-                lse=lse, psi_all=psi)
+                lse=lse, psi_all=psi, min_gap=min_gap)
 
 
 def sbs_step(logits, sum_logprob, trunc_gumbel, n_in, width, inv_temperature=1.0,
@@ -82,7 +84,9 @@ def sbs_step(logits, sum_logprob, trunc_gumbel, n_in, width, inv_temperature=1.0
     logits [B,W_in,V]; sum_logprob, trunc_gumbel [B,W_in]; n_in [B] live rows.
     Row (b, w) draws its noise at counter coordinates (seq_id[b], node_id[b,w]);
     defaults: seq = b, node = w.  Outputs padded to `width` with token/parent -1
-    and -inf scores; n_out[b] = number of valid entries.
+    and -inf scores; n_out[b] = number of valid entries; min_gap[b] as in
+    sbs_step_from_noise (a reader in lower precision may order or cut differently when it is
+    tiny).
     """
     logits = np.asarray(logits)
     B, W_in, V = logits.shape
@@ -96,6 +100,7 @@ def sbs_step(logits, sum_logprob, trunc_gumbel, n_in, width, inv_temperature=1.0
     p_out = np.full((B, width), -np.inf)
     lse = np.zeros((B, W_in))
     n_out = np.zeros(B, dtype=np.int64)
+    min_gap = np.full(B, np.inf)
     for b in range(B):
         n = int(n_in[b])
         if n == 0:
@@ -111,5 +116,6 @@ def sbs_step(logits, sum_logprob, trunc_gumbel, n_in, width, inv_temperature=1.0
         p_out[b, :m] = r["perturbed"]
         lse[b, :n] = r["lse"]
         n_out[b] = m
+        min_gap[b] = r["min_gap"]
     return dict(tokens=tokens, parent=parent, sum_logprob=s_out,
-                trunc_gumbel=g_out, perturbed=p_out, n_out=n_out, lse=lse)
+                trunc_gumbel=g_out, perturbed=p_out, n_out=n_out, lse=lse, min_gap=min_gap)

@@ -81,7 +81,11 @@ struct TopkArgs {
     // perturbed / logprob / count -- scores and logits NOT yet reduced by the row normaliser,
     // whose per-segment (max, sum) pair goes to seg_ms; `lse` is then left to the consumer.
     int nseg;
-    MaxSum *seg_ms;    // [R * nseg] when nseg > 1
+    MaxSum *seg_ms;    // [R * nseg] when nseg > 1 or raw_lists
+    // SBS: the lists keep the raw logit of every candidate in `logprob` and scores that are not
+    // reduced by the row normaliser, whose (max, sum) pair always goes to seg_ms: the consumer
+    // recomputes what it needs from exact inputs.
+    int raw_lists;
 };
 
 constexpr int kTopkThreads = 1024;
@@ -319,7 +323,8 @@ __global__ __launch_bounds__(kTopkThreads, (CH <= 8 && !WANT_LSE) ? 8 : 4) void 
     // ---- outputs ----------------------------------------------------------
     const int nout = s_nout;
     const int64_t orow = (int64_t)row * nseg + seg;  // list index: the row, or the row's segment
-    const float sub = nseg > 1 ? 0.f : lse_nat;       // segments leave the normaliser to the consumer
+    const bool raw = a.raw_lists != 0;
+    const float sub = (nseg > 1 || raw) ? 0.f : lse_nat;  // segments leave the normaliser to the consumer
     if (tid < a.k_max) {
         const int64_t o = orow * a.k_max + tid;
         if (tid < nout) {
@@ -327,7 +332,7 @@ __global__ __launch_bounds__(kTopkThreads, (CH <= 8 && !WANT_LSE) ? 8 : 4) void 
             a.tokens[o] = t;
             if (WANT_LSE) {
                 if (a.perturbed) a.perturbed[o] = s_outv[tid] - sub;
-                if (a.logprob) a.logprob[o] = zrow[t] * a.inv_t - sub;
+                if (a.logprob) a.logprob[o] = raw ? zrow[t] : zrow[t] * a.inv_t - sub;
             }
         } else {
             a.tokens[o] = -1;
@@ -337,8 +342,8 @@ __global__ __launch_bounds__(kTopkThreads, (CH <= 8 && !WANT_LSE) ? 8 : 4) void 
     }
     if (tid == 0) {
         if (a.count) a.count[orow] = nout;
-        if (WANT_LSE && nseg > 1) a.seg_ms[orow] = dead ? MaxSum{-INFINITY, 0.f} : acc;
-        if (WANT_LSE && nseg == 1 && a.lse) a.lse[row] = dead ? 0.f : lse_nat;
+        if (WANT_LSE && (nseg > 1 || raw)) a.seg_ms[orow] = dead ? MaxSum{-INFINITY, 0.f} : acc;
+        if (WANT_LSE && nseg == 1 && !raw && a.lse) a.lse[row] = dead ? 0.f : lse_nat;
     }
 }
 
@@ -349,35 +354,42 @@ __global__ __launch_bounds__(kTopkThreads, (CH <= 8 && !WANT_LSE) ? 8 : 4) void 
 // ---------------------------------------------------------------------------
 struct SbsSelectArgs {
     const int *row_tok;      // [B*W_in*nseg, W]
-    const float *row_pert;   // [B*W_in*nseg, W]  z/T + G  (- lse when nseg == 1)
-    const float *row_logp;   // [B*W_in*nseg, W]  z/T      (- lse when nseg == 1)
+    const float *row_pert;   // [B*W_in*nseg, W]  z/T + G in fp32 (ranks a row's candidates)
+    const float *row_z;      // [B*W_in*nseg, W]  the candidates' raw logits
     const int *row_cnt;      // [B*W_in*nseg]
-    const MaxSum *seg_ms;    // [B*W_in*nseg] partial normalisers when nseg > 1
+    const MaxSum *seg_ms;    // [B*W_in*nseg] (max, sum) of every list's share of the row, log2 domain
     const float *sum_logprob;   // [B, W_in]
     const float *trunc_gumbel;  // [B, W_in]
     const int *n_in;
+    const int *seq_id;       // [B] or null (= b)
+    const int *node_id;      // [B, W_in] or null (= w)
+    uint64_t seed;
+    uint32_t step;
+    float inv_t;
     int W_in, W, V, nseg;
     int *tokens;
     int *parent;
     float *sum_out;
     float *gum_out;
     int *n_out;
-    float *lse;  // [B, W_in] written here when nseg > 1, or null
+    float *lse;  // [B, W_in] or null
 };
 
 // One thread per candidate slot (row w, segment sg, position j): W_in * nseg * W <= 256.  With
 // segments, every slot of a row is a candidate (a superset of the row's top W, which is all
-// that can matter), the row normaliser is merged from the segments' (max, sum) pairs and the
-// row maximum Z is the largest first entry of the row's segment lists.
+// that can matter) and the row's W best by fp32 score go on.  For those the truncated Gumbel
+// of Eq. (11) is worked out in fp64 from exact inputs: the candidate's raw logit and the Gumbel
+// variate of its own Philox word, so that the distance Phi~ - Z to the row maximum -- which
+// Eq. (11) amplifies by exp(psi - Phi~) -- carries no fp32 rounding (within a row the
+// normaliser and the parent's sum cancel in it).
 __global__ __launch_bounds__(256) void sbs_select_kernel(SbsSelectArgs a) {
     __shared__ __align__(16) double s_psi[256];
+    __shared__ __align__(16) double s_rel[256];
     __shared__ __align__(16) int s_key[256];
     __shared__ __align__(16) int s_key2[256];
     __shared__ float s_rpert[256];
-    __shared__ float s_lse[RSD_K_MAX];   // per row (0 when the lists are already normalised)
-    __shared__ float s_top[RSD_K_MAX];   // per row: largest perturbed score (same offset as the lists)
+    __shared__ double s_lse[RSD_K_MAX];  // per row
     __shared__ MaxSum s_sms[RSD_K_MAX * 8];
-    __shared__ float s_stop[RSD_K_MAX * 8];
     const int b = blockIdx.x;
     const int t = threadIdx.x;
     const int nseg = a.nseg;
@@ -395,17 +407,17 @@ __global__ __launch_bounds__(256) void sbs_select_kernel(SbsSelectArgs a) {
     const int cnt = a.row_cnt[list];
     const int tok_in = a.row_tok[(int64_t)list * a.W + j % a.W];
     const float pert_in = a.row_pert[(int64_t)list * a.W + j % a.W];
-    const float logp_in = a.row_logp[(int64_t)list * a.W + j % a.W];
-    const MaxSum ms_in = nseg > 1 ? a.seg_ms[list] : MaxSum{-INFINITY, 0.f};
+    const float z_in = a.row_z[(int64_t)list * a.W + j % a.W];
+    const MaxSum ms_in = a.seg_ms[list];
     const float sigma_in = a.sum_logprob[row], gamma_in = a.trunc_gumbel[row];
+    const uint32_t seq = a.seq_id ? (uint32_t)a.seq_id[b] : (uint32_t)b;
+    const uint32_t node = a.node_id ? (uint32_t)a.node_id[row] : (uint32_t)(slot ? w : 0);
     const bool row_live = slot && w < n;
-    if (slot && j == 0) {  // head of list (w, sg)
-        s_sms[w * nseg + sg] = row_live ? ms_in : MaxSum{-INFINITY, 0.f};
-        s_stop[w * nseg + sg] = (row_live && cnt > 0) ? pert_in : -INFINITY;
-    }
+    if (slot && j == 0) s_sms[w * nseg + sg] = row_live ? ms_in : MaxSum{-INFINITY, 0.f};
     const int slots = a.W_in * a.W;  // entries of the table that the last ranking runs over
     if (t < ((slots + 3) & ~3)) {
         s_psi[t] = -INFINITY;
+        s_rel[t] = -INFINITY;
         s_key2[t] = INT_MAX;
     }
     bool live = row_live && j < cnt;
@@ -432,34 +444,42 @@ __global__ __launch_bounds__(256) void sbs_select_kernel(SbsSelectArgs a) {
         place = rr;
     }
     if (t < a.W_in) {
-        float lse = 0.f, top = -INFINITY;
+        double lse = 0.0;
         MaxSum ms{-INFINITY, 0.f};
-        for (int g = 0; g < nseg; ++g) {
-            ms = merge(ms, s_sms[t * nseg + g]);
-            top = fmaxf(top, s_stop[t * nseg + g]);
-        }
-        if (nseg > 1 && t < n) lse = (ms.m + log2f(ms.s)) * kLn2;
+        for (int g = 0; g < nseg; ++g) ms = merge(ms, s_sms[t * nseg + g]);
+        if (t < n) lse = ((double)ms.m + log2((double)ms.s)) * 0.6931471805599453;
         s_lse[t] = lse;
-        s_top[t] = top;
-        if (a.lse && nseg > 1) a.lse[b * a.W_in + t] = lse;
+        if (a.lse) a.lse[b * a.W_in + t] = (float)lse;
     }
-    __syncthreads();
-    double psi = -INFINITY, phi = -INFINITY;
+    // the candidate's score relative to its row: z/T + G in fp64, G from the candidate's own word
+    double rel = -INFINITY, s = 0.0;
     int tok = -1;
     if (live) {
         tok = tok_in;
+        const uint4 r = philox4x32_10((uint32_t)tok >> 2, node, seq, counter_word3(kTagDraftGumbel, a.step),
+                                      make_key(a.seed));
+        const uint32_t sel = (uint32_t)tok & 3u;
+        const uint32_t wd = sel == 0 ? r.x : (sel == 1 ? r.y : (sel == 2 ? r.z : r.w));
+        const double u = (double)((wd >> 8) | 1u) * 5.9604644775390625e-08;
+        s = (double)z_in * (double)a.inv_t;
+        rel = s - log(-log(u));
+        s_rel[w * a.W + place] = rel;
+    }
+    __syncthreads();
+    double psi = -INFINITY, phi = -INFINITY;
+    if (live) {
+        double top = -INFINITY;  // the row's maximum: it is among the row's candidates
+        for (int o = 0; o < a.W; ++o) top = fmax(top, s_rel[w * a.W + o]);
         const double sigma = (double)sigma_in;
         const double gamma = (double)gamma_in;
-        const double lse = (double)s_lse[w];
-        const double pj = (double)pert_in - lse;
-        const double p0 = (double)s_top[w] - lse;
-        phi = (double)logp_in - lse + sigma;
-        const double d = pj - p0;  // Phi~ - Z <= 0 (the row's sigma cancels)
+        const double shift = sigma - s_lse[w];
+        phi = s + shift;
+        const double d = rel - top;  // Phi~ - Z <= 0
         if (!(d < 0.0)) {
             psi = gamma;
         } else {
             const double log1m = d > -0.6931471805599453 ? log(-expm1(d)) : log1p(-exp(d));
-            const double v = gamma - (pj + sigma) + log1m;
+            const double v = gamma - (rel + shift) + log1m;
             psi = gamma - (fmax(v, 0.0) + log1p(exp(-fabs(v))));
         }
     }
@@ -626,13 +646,15 @@ static int32_t sbs_step_on(char *ws, const float *logits, const float *sum_logpr
     a.seq_id = seq_id; a.node_id = node_id; a.n_live = n_in; a.rows_per_seq = W_in;
     a.seq_default_is_b = 1; a.node_default_is_w = 1; a.inv_t = inv_temperature;
     a.seed = seed; a.step = step; a.tokens = row_tok; a.perturbed = row_pert;
-    a.logprob = row_logp; a.lse = lse; a.count = row_cnt; a.nseg = nseg; a.seg_ms = seg_ms;
+    a.logprob = row_logp; a.lse = nullptr; a.count = row_cnt; a.nseg = nseg; a.seg_ms = seg_ms;
+    a.raw_lists = 1;
     const int32_t rc = launch_topk(a, (int)rows, stream);
     if (rc != RSD_OK) return rc;
 
     SbsSelectArgs s{};
-    s.row_tok = row_tok; s.row_pert = row_pert; s.row_logp = row_logp; s.row_cnt = row_cnt;
+    s.row_tok = row_tok; s.row_pert = row_pert; s.row_z = row_logp; s.row_cnt = row_cnt;
     s.seg_ms = seg_ms; s.nseg = nseg; s.lse = lse;
+    s.seq_id = seq_id; s.node_id = node_id; s.seed = seed; s.step = step; s.inv_t = inv_temperature;
     s.sum_logprob = sum_logprob; s.trunc_gumbel = trunc_gumbel; s.n_in = n_in;
     s.W_in = W_in; s.W = W; s.V = V; s.tokens = tokens; s.parent = parent;
     s.sum_out = sum_logprob_out; s.gum_out = trunc_gumbel_out; s.n_out = n_out;

@@ -3,6 +3,7 @@ import itertools
 
 import mpmath
 import numpy as np
+import pytest
 from scipy import special, stats
 
 from oracle import philox
@@ -133,3 +134,27 @@ def test_batched_entry_padding_and_dead_rows():
     own_best = out["tokens"][1][out["parent"][1] == 0]
     if len(own_best):
         assert own_best[0] == one["tokens"][0]
+
+
+def test_min_gap_reports_the_closest_call_among_the_top_width_plus_one():
+    """Hand-built step: one parent with Gamma = 0 and noise that is cancelled by the logits, so that
+    the perturbed scores are chosen values; at the single parent psi = T(0, phi~) is increasing in
+    phi~, and the two entries placed `gap` apart in phi~ map to psi values whose distance follows
+    from Eq. (11) in closed form."""
+    V, width = 6, 2
+    g = np.array([0.3, -1.0, 2.0, 0.1, -0.4, 1.5])
+    for gap in (3e-6, 0.4):
+        target = np.array([-1.0, -3.0, -3.0 - gap, -6.0, -7.0, -8.0])      # phi~ up to a common shift
+        logits = (target - g)[None, :]
+        r = sbs_step_from_noise(logits, [0.0], [0.0], g[None, :], width)
+        assert r["tokens"].tolist() == [0, 1]
+        pt = np.sort(r["psi_all"][0])[::-1]
+        # closest pair among the top three: ranks 2 and 3 (the cut) when gap is tiny
+        assert r["min_gap"] == pytest.approx(min(pt[0] - pt[1], pt[1] - pt[2]), rel=1e-12)
+        lse = r["lse"][0]
+        psi = lambda t: -np.log(np.exp(0.0) - np.exp(-(target[0] - lse)) + np.exp(-(t - lse)))   # Eq. (11)
+        assert pt[1] - pt[2] == pytest.approx(psi(target[1]) - psi(target[2]), rel=1e-6, abs=1e-12)
+        assert (r["min_gap"] < 1e-5) == (gap < 1e-5)
+    # a single candidate: nothing to compare
+    r = sbs_step_from_noise(np.array([[0.0, -np.inf]]), [0.0], [0.0], np.zeros((1, 2)), 1)
+    assert r["min_gap"] == np.inf

@@ -61,8 +61,7 @@ def test_sbs_step_static_matches_workspace_variant_twice():
         assert np.array_equal(to_np(got["n_out"]), ref["n_out"])
         for b in range(B):
             n, live = int(ref["n_out"][b]), int(host["n_in"][b])
-            gaps = -np.diff(ref["trunc_gumbel"][b, :n])
-            if n > 1 and gaps.min() < 1e-4:
+            if ref["min_gap"][b] < 1e-5:
                 continue
             assert np.array_equal(to_np(got["tokens"])[b, :n], ref["tokens"][b, :n])
             assert np.array_equal(to_np(got["parent"])[b, :n], ref["parent"][b, :n])
