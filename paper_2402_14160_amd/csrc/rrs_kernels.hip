@@ -1,25 +1,31 @@
 // Recursive rejection sampling over the draft tree (Sec. 3.1; Sec. 3.2.2; Alg. 6).
 //
 // A sibling group (the children x_1..x_K of one node) is verified by one
-// workgroup.  The residual distributions q^(k) of Eq. (2) are never stored:
-// with e_t(x) = 2^(zt(x) - max zt), e_d(x) = 2^(zd(x) - max zd) (log2 domain),
-//   q^(1)(x)   = e_t(x) / s_t
-//   p^(k)(x)   = e_d(x) / s_k          for x not in {x_1..x_{k-1}}, else 0
-//   q^(k+1)(x) = max(q^(k)(x) - p^(k)(x), 0) / S_k,   S_k = sum_x max(q^(k) - p^(k), 0)
-// The resident variants keep u(x) = q^(k)(x) * A_k and e_d(x) on chip (registers, and LDS
-// for the larger vocabularies) and update u in place at every stage; the streaming variant
-// (largest vocabularies) re-reads the two rows at every stage and evaluates the short
-// per-entry chain from the scalars (s_t, s_1.., S_1..) found so far.  Either way only the
-// scalars go to memory, and the last-token pass re-evaluates the chain from them.
-// s_k sums the draft row without the removed tokens directly (no 1 - p
-// cancellation).  Sums are accumulated per lane in fp32, across waves in fp64
-// in a fixed order, so results do not depend on scheduling.
+// workgroup.  The residual distributions q^(k) of Eq. (2) are never stored: with
+//   e_t(x) = 2^(zt(x) c - m_t),  e_d(x) = 2^(zd(x) c - m_d),  c = log2(e) / T,
+// the kernels carry u(x) = q^(k)(x) A_k, starting from u = e_t, A_1 = sum_x e_t(x), and a stage is
+//   gamma_k = A_k / s_k,          s_k = sum of e_d over the tokens not yet removed,
+//   u <- max(u - gamma_k e_d, 0), A_{k+1} = S_k = sum_x u(x),   then e_d(x_k) <- 0,
+// so that Theta_k = (u(x_k) / A_k) / (e_d(x_k) / s_k) (Eq. (3)).  Only the gamma_k go to memory;
+// the last-token pass re-evaluates the chain from them.
+//
+// Precision.  A stage whose residual mass S_k is a small fraction of A_k cancels the leading
+// digits of u - gamma e_d at the probable tokens, so what Theta of the later siblings sees is the
+// absolute error of the big entries divided by that fraction.  Three measures keep it near 1e-7:
+//  * exponents are z c - m formed by fused multiply-adds with c split into two floats, rounded
+//    once at the size of the result (a probable token has a result near zero);
+//  * the child tokens and every entry within 2^-4 of its row's maximum are followed in fp64
+//    (exponentials from the raw logits), by one lane each, and are zero in the fp32 arrays;
+//  * gamma is applied as a pair of floats once the residual mass has shrunk below 1/16.
+// Sums are accumulated per lane in fp32 (entries below 2^-4 only), across lanes in a fixed order
+// and across waves in fp64, so results do not depend on scheduling.
 //
 // ALL_GROUPS runs three kernels (plan, groups, walk + last token), PATH one persistent
 // workgroup per sequence.
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <math.h>
+#include <stddef.h>
 
 #include "../../include/rsd.h"
 #include "rsd_device.hpp"
@@ -29,38 +35,44 @@ namespace rsd {
 typedef __attribute__((address_space(3))) void lds_void;
 typedef __attribute__((address_space(1))) const void global_void;
 
-constexpr int kGroupThreads = 512;   // streaming variant (any vocabulary size)
-constexpr int kRegThreads = 512;     // register-resident variant: 2 waves per SIMD, 256 VGPRs each
-// resident variant with most of the draft row in LDS (larger vocabularies): 12 waves, three per
-// SIMD, so that a thread has 168 registers
-constexpr int kLdsThreads = 768;
-constexpr int kLdsChunks = 17;       // float4 chunks per thread: 52224 entries
-constexpr int kLdsChunksInLds = 12;  // of which in LDS: 12 * 768 * 16 B = 144 KB
+constexpr int kStreamThreads = 512;  // streaming variant (any vocabulary size)
+// Resident variants <threads, float4 chunks per thread, of which in LDS>:
+//  up to 8192 entries:   256 threads, 8 chunks in registers (small vocabularies)
+//  up to 32768 entries:  512 threads, both rows in registers (2 x 64 per thread)
+//  up to 52224 entries:  768 threads, 12 of 17 draft chunks in LDS (144 KB), one workgroup per CU
+constexpr int kSmallThreads = 256, kSmallChunks = 8;
+constexpr int kRegThreads = 512, kRegChunks = 16, kRegChunksInLds = 0;
+constexpr int kLdsThreads = 768, kLdsChunks = 17, kLdsChunksInLds = 12;
 constexpr int kGroupWavesMax = 16;
 constexpr int kFinalThreads = 512;
 constexpr int kFinalSplitsMax = 8;
+#ifndef RSD_X_HEAVY
+#define RSD_X_HEAVY 4.f
+#endif
+constexpr float kHeavy = RSD_X_HEAVY;   // entries with exponent >= -kHeavy are followed in fp64
+constexpr int kCandCap = 48;    // such entries per wave: lanes 16..63 (lanes 0..15 of wave 0: the children)
 
 // Per (sequence, node) record produced by the group pass, kept in workspace.
 struct GroupRec {
-    float mt2;      // max of target row, log2 domain
-    float md2;      // max of draft row, log2 domain
-    float inv_st;   // 1 / sum_x 2^(zt2 - mt2)
+    float mt2;      // exponent offset of the target row (about its maximum, log2 domain)
+    float md2;      // the same for the draft row
     int K;          // number of verified children (<= RSD_K_MAX); 0 for a leaf
     uint32_t flags;
-    int pad[3];
     int kid[RSD_K_MAX];      // child node ids in stored order
     int tok[RSD_K_MAX];      // their tokens
-    float inv_s[RSD_K_MAX];  // 1 / s_k (draft mass left at stage k); 0 marks a skipped stage
-    float inv_S[RSD_K_MAX];  // 1 / S_k (1 for a skipped stage)
     float theta[RSD_K_MAX];
+    double gam[RSD_K_MAX];   // gamma_k of stage k (0 marks a skipped stage: q^(k+1) = q^(k))
 };
+static_assert(offsetof(GroupRec, gam) % 8 == 0, "");
 
 struct RrsArgs {
     const float *zd;
     const float *zt;
     int B, N, V;
     float inv_t;   // 1/T
-    float c2;      // log2(e)/T
+    float c2h;     // c = log2(e)/T as a pair of floats: c2h < c <= c2h + c2l, c2l > 0
+    float c2l;
+    double c2e;    // c in fp64
     const int *tokens;
     const int *parent;
     const int *n_nodes;
@@ -82,7 +94,7 @@ struct RrsArgs {
     int *fdone;                 // [B]
     int *kcount;                // [B, N] number of children of every node
     int2 *work;                 // [B, N] non-leaf nodes {b * N + node, nodes of the tree}, most children first
-    int *wq;                    // [0] number of work items
+    int *wq;                    // [0] number of work items, [1] next item to hand out
 };
 
 __device__ __forceinline__ int removal_stage(int x, const int *tok, int K) {
@@ -96,53 +108,70 @@ __device__ __forceinline__ float uniform_f(float v) {
     return __int_as_float(__builtin_amdgcn_readfirstlane(__float_as_int(v)));
 }
 
-// The group's scalars pulled into (scalar) registers once per pass so that the
-// per-entry chain indexes them statically.
+// z c - m in fp32 with c = c2h + c2l: the first fused multiply-add rounds once at the size of the
+// result, the second adds the part of c that a float cannot hold (c2l > 0, so a logit of -inf
+// stays -inf).  neg_m = -inf turns any finite z into -inf (entries outside the row).
+__device__ __forceinline__ float exponent_of(float z, float c2h, float c2l, float neg_m) {
+    return fmaf(z, c2l, fmaf(z, c2h, neg_m));
+}
+
+// fp64 sum over the 64 lanes in a fixed order (all lanes active, all receive the result).
+template <int CTRL>
+__device__ __forceinline__ double dpp_move_d(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double read_lane_d(double v, int lane) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), lane));
+}
+__device__ __forceinline__ double wave_sum_f64(double v) {
+    v += dpp_move_d<0xB1>(v);
+    v += dpp_move_d<0x4E>(v);
+    v += dpp_move_d<0x124>(v);
+    v += dpp_move_d<0x128>(v);
+    return (read_lane_d(v, 0) + read_lane_d(v, 16)) + (read_lane_d(v, 32) + read_lane_d(v, 48));
+}
+
+// The stage scalars of a group pulled into (scalar) registers once per pass so that the
+// per-entry chain indexes them statically: gamma_j as a pair of floats.
 struct ChainRegs {
-    float mt2, md2, inv_st;
-    float is[RSD_K_MAX];
-    float iS[RSD_K_MAX];
+    float mt2, md2;
+    float gh[RSD_K_MAX];
+    float gl[RSD_K_MAX];
 };
 
 __device__ __forceinline__ ChainRegs load_chain(const GroupRec &g) {
     ChainRegs r;
     r.mt2 = uniform_f(g.mt2);
     r.md2 = uniform_f(g.md2);
-    r.inv_st = uniform_f(g.inv_st);
 #pragma unroll
     for (int j = 0; j < RSD_K_MAX; ++j) {
-        r.is[j] = uniform_f(g.inv_s[j]);
-        r.iS[j] = uniform_f(g.inv_S[j]);
+        const double gam = g.gam[j];
+        const float hi = (float)gam;
+        r.gh[j] = uniform_f(hi);
+        r.gl[j] = uniform_f((float)(gam - (double)hi));
     }
     return r;
 }
 
-// q^(nst+1) for four entries none of which is a child token.
-__device__ __forceinline__ void chain4(const float et[4], const float ed[4], const ChainRegs &r,
-                                       int nst, float q[4]) {
-#pragma unroll
-    for (int i = 0; i < 4; ++i) q[i] = et[i] * r.inv_st;
+// u after the first nst stages for four entries none of which is followed in fp64.
+__device__ __forceinline__ void chain4(float u[4], const float ed[4], const ChainRegs &r, int nst) {
 #pragma unroll
     for (int j = 0; j < RSD_K_MAX - 1; ++j) {
         if (j < nst) {  // wave-uniform; keeps the scalar arrays statically indexed
 #pragma unroll
-            for (int i = 0; i < 4; ++i) q[i] = fmaxf(q[i] - ed[i] * r.is[j], 0.f) * r.iS[j];
+            for (int i = 0; i < 4; ++i) u[i] = fmaxf(fmaf(-r.gl[j], ed[i], fmaf(-r.gh[j], ed[i], u[i])), 0.f);
         }
     }
 }
 
-// q^(nst+1)(x) when x may be the child token removed at stage rs (rs = K: never).
-__device__ __forceinline__ float chain1_masked(float et, float ed, int rs, const ChainRegs &r,
-                                               int nst) {
-    float q = et * r.inv_st;
-#pragma unroll
-    for (int j = 0; j < RSD_K_MAX - 1; ++j) {
-        if (j < nst) {
-            const float p = (rs < j) ? 0.f : ed * r.is[j];
-            q = fmaxf(q - p, 0.f) * r.iS[j];
-        }
-    }
-    return q;
+// The same chain in fp64 from the raw logits, for an entry that the draft distribution loses
+// after stage rs (rs = K: never).  Returns u after nst stages.
+__device__ __forceinline__ double chain1_f64(double U, double E, int rs, const GroupRec &g, int nst) {
+    for (int j = 0; j < nst; ++j) U = fmax(U - g.gam[j] * (j <= rs ? E : 0.0), 0.0);
+    return U;
 }
 
 // Bit i set: this thread's i-th chunk (c = c_lo + tid + i*THREADS) holds a child token.
@@ -164,128 +193,21 @@ struct GroupShared {
     MaxSum ms[kGroupWavesMax];
     double red[kGroupWavesMax];
     double red2[kGroupWavesMax];
-    float czt[RSD_K_MAX];   // raw target / draft logits of the child tokens (resident variant)
+    float czt[RSD_K_MAX];   // raw target / draft logits of the child tokens
     float czd[RSD_K_MAX];
     double ce[RSD_K_MAX];   // draft exponentials of the child tokens (fp64)
-    double sred[2][kGroupWavesMax];  // stage sums of the resident variant, alternating
+    double sred[2][kGroupWavesMax];  // stage sums, alternating
     unsigned long long cmask[RSD_NODES_MAX / kWave];  // per-wave ballots of the child scan
     int cur;
     int done;
+    int next_idx;   // work queue: the item this workgroup takes next
+    int2 next_ent;
 };
 
-// Pass 0: maxima and sums of both rows.  The draft sum leaves out every child token.
-template <int THREADS>
-__device__ void group_lse_pass(const float *zt, const float *zd, int V, float c2, GroupShared &sh) {
-    const int nchunk = V >> 2;
-    const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
-    const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
-    const uint64_t hits = child_chunk_mask<THREADS>(sh.g, 0, nchunk);
-    MaxSum at{-INFINITY, 0.f}, ad{-INFINITY, 0.f};
-    int it = 0;
-#pragma unroll 2
-    for (int c = threadIdx.x; c < nchunk; c += THREADS, ++it) {
-        const float4 t = zt4[c];
-        const float4 d = zd4[c];
-        const float a[4] = {t.x * c2, t.y * c2, t.z * c2, t.w * c2};
-        const float e[4] = {d.x * c2, d.y * c2, d.z * c2, d.w * c2};
-        const float mt = fmaxf(fmaxf(a[0], a[1]), fmaxf(a[2], a[3]));
-        const float md = fmaxf(fmaxf(e[0], e[1]), fmaxf(e[2], e[3]));
-        if (mt > at.m) { at.s *= exp2f(at.m - mt); at.m = mt; }
-        if (md > ad.m) { ad.s *= exp2f(ad.m - md); ad.m = md; }
-        if (at.m > -INFINITY)
-            at.s += (exp2f(a[0] - at.m) + exp2f(a[1] - at.m)) + (exp2f(a[2] - at.m) + exp2f(a[3] - at.m));
-        if (ad.m > -INFINITY) {
-            if (!((hits >> it) & 1ull)) {
-                ad.s += (exp2f(e[0] - ad.m) + exp2f(e[1] - ad.m)) + (exp2f(e[2] - ad.m) + exp2f(e[3] - ad.m));
-            } else {
-#pragma unroll
-                for (int i = 0; i < 4; ++i)
-                    if (removal_stage((c << 2) + i, sh.g.tok, sh.g.K) == sh.g.K) ad.s += exp2f(e[i] - ad.m);
-            }
-        }
-    }
-    at = block_merge<THREADS>(at, sh.ms);
-    ad = block_merge<THREADS>(ad, sh.ms);
-    if (threadIdx.x == 0) {
-        sh.g.mt2 = at.m;
-        sh.g.md2 = ad.m;
-        sh.g.inv_st = 1.f / at.s;
-        // draft mass still available at stage k: the rest plus the children not yet removed
-        double e[RSD_K_MAX];
-        for (int i = 0; i < sh.g.K; ++i) e[i] = exp2((double)zd[sh.g.tok[i]] * (double)c2 - (double)ad.m);
-        double s = (double)ad.s;
-        for (int k = RSD_K_MAX - 1; k >= 0; --k) {
-            if (k < sh.g.K) {
-                s += e[k];
-                sh.g.inv_s[k] = (float)(1.0 / s);
-            } else {
-                sh.g.inv_s[k] = 0.f;
-            }
-            sh.g.inv_S[k] = 1.f;
-        }
-        if (!(at.s > 0.f) || !isfinite(at.s) || !(s > 0.0) || !isfinite(s)) sh.g.flags |= RSD_FLAG_NONFINITE;
-    }
-    __syncthreads();
-}
-
-// Stage pass: S = sum_x max(q^(nst+1)(x) - p^(nst+1)(x), 0).
-template <int THREADS>
-__device__ double group_residual_mass(const float *zt, const float *zd, int V, float c2, int nst,
-                                      GroupShared &sh) {
-    const int nchunk = V >> 2;
-    const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
-    const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
-    const GroupRec &g = sh.g;
-    const ChainRegs cr = load_chain(g);
-    const float inv_s = uniform_f(g.inv_s[nst]);
-    const uint64_t hits = child_chunk_mask<THREADS>(g, 0, nchunk);
-    float part = 0.f;
-    int it = 0;
-#pragma unroll 2
-    for (int c = threadIdx.x; c < nchunk; c += THREADS, ++it) {
-        const float4 t = zt4[c];
-        const float4 d = zd4[c];
-        const float et[4] = {exp2f(fmaf(t.x, c2, -cr.mt2)), exp2f(fmaf(t.y, c2, -cr.mt2)),
-                             exp2f(fmaf(t.z, c2, -cr.mt2)), exp2f(fmaf(t.w, c2, -cr.mt2))};
-        const float ed[4] = {exp2f(fmaf(d.x, c2, -cr.md2)), exp2f(fmaf(d.y, c2, -cr.md2)),
-                             exp2f(fmaf(d.z, c2, -cr.md2)), exp2f(fmaf(d.w, c2, -cr.md2))};
-        float r[4];
-        if (!((hits >> it) & 1ull)) {
-            float q[4];
-            chain4(et, ed, cr, nst, q);
-#pragma unroll
-            for (int i = 0; i < 4; ++i) r[i] = fmaxf(q[i] - ed[i] * inv_s, 0.f);
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int rs = removal_stage((c << 2) + i, g.tok, g.K);
-                const float p = (rs < nst) ? 0.f : ed[i] * inv_s;
-                r[i] = fmaxf(chain1_masked(et[i], ed[i], rs, cr, nst) - p, 0.f);
-            }
-        }
-        part += (r[0] + r[1]) + (r[2] + r[3]);
-    }
-    return block_sum<THREADS>(part, sh.red);
-}
-
-// Threshold of child k (Eq. (3)) from the scalars found so far, in fp64.
-__device__ double child_theta(const float *zt, const float *zd, float c2, int k, const GroupRec &g) {
-    const int x = g.tok[k];
-    const double et = exp2((double)zt[x] * (double)c2 - (double)g.mt2);
-    const double ed = exp2((double)zd[x] * (double)c2 - (double)g.md2);
-    double q = et * (double)g.inv_st;
-    for (int j = 0; j < k; ++j)  // x_k is not removed before stage k
-        q = fmax(q - ed * (double)g.inv_s[j], 0.0) * (double)g.inv_S[j];
-    const double p = ed * (double)g.inv_s[k];
-    if (!(p > 0.0)) return 1.0;
-    return fmin(1.0, q / p);
-}
-
-// Children of `node` in stored order, into sh.g (kid, tok, K): the first RSD_NODES_MAX threads
-// test one node each, wave ballots give every match its rank.  All threads of the workgroup
-// take part; ends with a barrier.  The halves can be called apart: fetch_candidate only issues
-// this thread's loads (its parent and token), fetch_child_logits the two logits of its token
-// when it is a child (sh.czt / sh.czd then hold them by rank), rank_children consumes them.
+// Children of `node` in stored order: thread j < RSD_NODES_MAX tests node j, wave ballots give
+// every match its rank.  The halves can be called apart: fetch_candidate only issues this
+// thread's loads (its parent and token), fetch_child_logits the two logits of its token when it
+// is a child (sh.czt / sh.czd then hold them by rank).
 struct ChildCandidate {
     int parent, token;
     float zt, zd;
@@ -312,11 +234,11 @@ __device__ __forceinline__ void fetch_child_logits(const float *zt, const float 
     }
 }
 
-__device__ __forceinline__ void rank_children(const RrsArgs &a, int node, ChildCandidate cand, GroupShared &sh,
-                                              int j) {
+// Publishes the ranks of the matching candidates (kid, tok, czt, czd by rank) and K.  Every
+// thread of the workgroup calls it; two barriers.
+__device__ __forceinline__ void rank_children(int node, const ChildCandidate &cand, GroupShared &sh, int j) {
     const int lane = j & (kWave - 1), wave = j / kWave;
     const bool match = cand.parent == node;
-    const int t = cand.token;
     const unsigned long long mask = __ballot(match);
     if (wave < RSD_NODES_MAX / kWave && lane == 0) sh.cmask[wave] = mask;
     __syncthreads();
@@ -325,7 +247,7 @@ __device__ __forceinline__ void rank_children(const RrsArgs &a, int node, ChildC
         for (int w = 0; w < wave; ++w) rank += __popcll(sh.cmask[w]);
         if (rank < RSD_K_MAX) {
             sh.g.kid[rank] = j;
-            sh.g.tok[rank] = t;
+            sh.g.tok[rank] = cand.token;
             sh.czt[rank] = cand.zt;
             sh.czd[rank] = cand.zd;
         }
@@ -339,76 +261,172 @@ __device__ __forceinline__ void rank_children(const RrsArgs &a, int node, ChildC
     __syncthreads();
 }
 
-__device__ __forceinline__ void scan_children(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
-    ChildCandidate c = fetch_candidate(a, b, node, n, threadIdx.x);
-    c.token = min(max(c.token, 0), a.V - 1);
-    rank_children(a, node, c, sh, threadIdx.x);
-}
-
+// ---------------------------------------------------------------------------
+// Streaming variant (vocabularies that no resident variant holds): the rows are read from
+// memory at every stage and the chain is re-evaluated per entry from the gammas found so far.
+// Only the child tokens are followed in fp64 here.
+// ---------------------------------------------------------------------------
 template <int THREADS>
-__device__ void process_group(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
-    scan_children(a, b, node, n, sh);
-    const int K = sh.g.K;
-    if (K == 0) return;
+__device__ void process_group_stream(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
+    constexpr int NW = THREADS / kWave;
+    static_assert(THREADS >= RSD_NODES_MAX && NW <= kGroupWavesMax, "");
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wave = tid / kWave;
     const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
     const float *zd = a.zd + ((int64_t)b * a.N + node) * a.V;
-    group_lse_pass<THREADS>(zt, zd, a.V, a.c2, sh);
-    for (int k = 0; k < K; ++k) {
-        if (threadIdx.x == 0) sh.g.theta[k] = (float)child_theta(zt, zd, a.c2, k, sh.g);
-        if (k == K - 1) break;
-        __syncthreads();
-        const double S = group_residual_mass<THREADS>(zt, zd, a.V, a.c2, k, sh);
-        if (threadIdx.x == 0) {
-            if (S > 0.0 && isfinite(S)) {
-                sh.g.inv_S[k] = (float)(1.0 / S);
-            } else {  // keep q^(k): no subtraction, no rescale
-                sh.g.inv_s[k] = 0.f;
-                sh.g.inv_S[k] = 1.f;
-                sh.g.flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
+    ChildCandidate cand = fetch_candidate(a, b, node, n, tid);
+    fetch_child_logits(zt, zd, a.V, node, cand);
+    rank_children(node, cand, sh, tid);
+    const int K = sh.g.K;
+    if (K == 0) return;
+    const int nchunk = a.V >> 2;
+    const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
+    const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
+    const float c2h = a.c2h, c2l = a.c2l;
+    // pass A: row maxima of the raw logits
+    float mt = -INFINITY, md = -INFINITY;
+    for (int c = tid; c < nchunk; c += THREADS) {
+        const float4 t = zt4[c], d = zd4[c];
+        mt = fmaxf(mt, fmaxf(fmaxf(t.x, t.y), fmaxf(t.z, t.w)));
+        md = fmaxf(md, fmaxf(fmaxf(d.x, d.y), fmaxf(d.z, d.w)));
+    }
+    mt = wave_max(mt);
+    md = wave_max(md);
+    if (lane == 0) sh.ms[wave] = MaxSum{mt, md};
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { mt = fmaxf(mt, sh.ms[w].m); md = fmaxf(md, sh.ms[w].s); }
+    const float m_t = (mt == -INFINITY) ? 0.f : mt * c2h, m_d = (md == -INFINITY) ? 0.f : md * c2h;
+    const uint64_t hits = child_chunk_mask<THREADS>(sh.g, 0, nchunk);
+    // children: lane k < K of wave 0 follows child k in fp64
+    double tU = 0.0, tE = 0.0;
+    if (tid < K) {
+        tU = exp2((double)sh.czt[tid] * a.c2e - (double)m_t);
+        tE = exp2((double)sh.czd[tid] * a.c2e - (double)m_d);
+        sh.ce[tid] = tE;
+    }
+    // pass B: sums without the child tokens
+    float st = 0.f, sd = 0.f;
+    {
+        int it = 0;
+        for (int c = tid; c < nchunk; c += THREADS, ++it) {
+            const float4 t = zt4[c], d = zd4[c];
+            const float tz[4] = {t.x, t.y, t.z, t.w}, dz[4] = {d.x, d.y, d.z, d.w};
+            const bool hit = (hits >> it) & 1ull;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool child = hit && removal_stage((c << 2) + i, sh.g.tok, K) < K;
+                st += child ? 0.f : __builtin_amdgcn_exp2f(exponent_of(tz[i], c2h, c2l, -m_t));
+                sd += child ? 0.f : __builtin_amdgcn_exp2f(exponent_of(dz[i], c2h, c2l, -m_d));
             }
         }
+    }
+    st = wave_sum(st);
+    sd = wave_sum(sd);
+    double su = (double)st;
+    if (wave == 0) su += wave_sum_f64(tU);
+    if (lane == 0) {
+        sh.red[wave] = su;
+        sh.red2[wave] = (double)sd;
+    }
+    __syncthreads();
+    double St = 0.0, Sd = 0.0;
+#pragma unroll
+    for (int w = 0; w < NW; ++w) { St += sh.red[w]; Sd += sh.red2[w]; }
+    if (tid == 0) {
+        sh.g.mt2 = m_t;
+        sh.g.md2 = m_d;
+        double s0 = Sd;
+        for (int i = 0; i < K; ++i) s0 += sh.ce[i];
+        if (!(St > 0.0) || !isfinite(St) || !(s0 > 0.0) || !isfinite(s0)) sh.g.flags |= RSD_FLAG_NONFINITE;
+    }
+    for (int i = tid; i < RSD_K_MAX; i += THREADS) sh.g.gam[i] = 0.0;
+    __syncthreads();
+    double A = St;
+    for (int k = 0; k < K; ++k) {
+        double s_k = Sd;
+        for (int i = K - 1; i >= k; --i) s_k += sh.ce[i];
+        const double gam = A / s_k;
+        if (tid == k) {  // threshold of child k (Eq. (3))
+            const double p = tE / s_k;
+            sh.g.theta[k] = (p > 0.0) ? (float)fmin(1.0, tU / (A * p)) : 1.f;
+        }
+        if (k == K - 1) {
+            if (tid == 0) sh.g.gam[k] = gam;
+            break;
+        }
+        const ChainRegs cr = load_chain(sh.g);
+        const float gh = uniform_f((float)gam), gl = uniform_f((float)(gam - (double)(float)gam));
+        float part = 0.f;
+        int it = 0;
+        for (int c = tid; c < nchunk; c += THREADS, ++it) {
+            const float4 t = zt4[c], d = zd4[c];
+            const float tz[4] = {t.x, t.y, t.z, t.w}, dz[4] = {d.x, d.y, d.z, d.w};
+            float u[4], e[4];
+            const bool hit = (hits >> it) & 1ull;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const bool child = hit && removal_stage((c << 2) + i, sh.g.tok, K) < K;
+                u[i] = child ? 0.f : __builtin_amdgcn_exp2f(exponent_of(tz[i], c2h, c2l, -m_t));
+                e[i] = child ? 0.f : __builtin_amdgcn_exp2f(exponent_of(dz[i], c2h, c2l, -m_d));
+            }
+            chain4(u, e, cr, k);
+#pragma unroll
+            for (int i = 0; i < 4; ++i) part += fmaxf(fmaf(-gl, e[i], fmaf(-gh, e[i], u[i])), 0.f);
+        }
+        const double cnew = fmax(tU - gam * tE, 0.0);
+        part = wave_sum(part);
+        double wsum = (double)part;
+        if (wave == 0) wsum += wave_sum_f64(tid < K ? cnew : 0.0);
+        double *red = sh.sred[k & 1];
+        if (lane == 0) red[wave] = wsum;
         __syncthreads();
+        double S = 0.0;
+#pragma unroll
+        for (int w = 0; w < NW; ++w) S += red[w];
+        if (S > 0.0 && isfinite(S)) {
+            tU = cnew;
+            if (tid == 0) sh.g.gam[k] = gam;
+            A = S;
+        } else if (tid == 0) {  // keep q^(k): no subtraction
+            sh.g.gam[k] = 0.0;
+            sh.g.flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
+        }
+        if (tid == k) tE = 0.0;  // x_k leaves the draft distribution either way
+        __syncthreads();         // gam[k] is read by the next stage's chain
     }
     __syncthreads();
 }
 
-
+// ---------------------------------------------------------------------------
 // Resident variant for vocabularies up to T * 4 * CH entries: both logit rows are read from
-// memory once; each thread keeps its share of the target-side value u(x) (q^(k) = u / A_k) in
-// registers and its share of the draft exponentials e_d(x) in registers (chunks CL..CH-1) and,
-// for the larger vocabularies, in LDS (chunks 0..CL-1, a slot of its own per thread and chunk,
-// so no barrier guards them).  A stage is
-//     S = sum_x max(u - gamma_k * e_d, 0);   u <- max(u - gamma_k * e_d, 0);   A_{k+1} = S
-// with gamma_k = A_k / s_k: three to five ALU operations per entry, one wave reduction and a
-// single barrier.  Every thread carries the scalars; lane t < K follows child token t in fp64.
+// memory once; each thread keeps its share of u(x) in registers and its share of e_d(x) in
+// registers (chunks CL..CH-1) and in LDS (chunks 0..CL-1, a slot of its own per thread and
+// chunk, so no barrier guards them).  Lane k < K of wave 0 follows child token k in fp64; lanes
+// 16..63 of every wave follow the heavy entries that the wave met (see the file header).  A
+// stage is three to four ALU operations per entry, one wave reduction and a single barrier.
+// ---------------------------------------------------------------------------
 template <int T, int CH, int CL>
-__device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
+__device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, ChildCandidate cand,
+                                                  float (&ut)[CH * 4], float (&edr)[(CH - CL) * 4],
+                                                  float4 *s_ed, GroupShared &sh) {
     constexpr int NW = T / kWave;
-    constexpr int CR = CH - CL;  // chunks of e_d held in registers
-    static_assert(NW <= kGroupWavesMax && CL >= 0 && CL < CH, "");
-    __shared__ float4 s_ed[CL > 0 ? CL * T : 1];
+    static_assert(NW <= kGroupWavesMax && CL >= 0 && CL < CH && T >= RSD_NODES_MAX, "");
+    static_assert(CH * 4 <= 128, "the child mask holds 128 entries");
+    // heavy entries met by each wave: their two raw logits (three scalar arrays rather than one
+    // of records: a record would need its fields in consecutive registers when it is stored)
+    __shared__ float s_trk_zt[NW * kCandCap];
+    __shared__ float s_trk_zd[NW * kCandCap];
     // (a copy of the thread index that the compiler takes for a new value in every call: what
     // derives from it -- chunk addresses, LDS slots, lane masks -- is then worked out here, next
     // to its use, instead of being kept in registers from one group to the next)
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
     const int wave = tid / kWave;
-    const bool lane0 = (tid & (kWave - 1)) == 0;
-    const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
-    const float *zd = a.zd + ((int64_t)b * a.N + node) * a.V;
-    const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
-    const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
+    const int lane = tid & (kWave - 1);
+    const bool lane0 = lane == 0;
     const int nchunk = a.V >> 2;
-    const float c2 = a.c2;
+    const float c2h = a.c2h, c2l = a.c2l;
     const int last = nchunk - 1;  // the caller checks V >= 4
-    // The children's lookup is requested first and the rows right after it, before the lookup
-    // is used: its dependent steps (the children's own logits, two barriers) then run under
-    // the rows' memory latency.  Every row load is unconditional (a chunk past the end of the
-    // row reads the row's last chunk instead and is set to -inf when it is scaled), so that
-    // the loads form one straight line and a wait can name exactly the loads it needs.  A node
-    // without children (the end of a path) costs one row pair that is not used.
-    ChildCandidate cand = fetch_candidate(a, b, node, n, tid);
-    float ut[CH * 4], edr[CR * 4];
     // chunk j of e_d, wherever it lives (j is a constant once the loops are unrolled)
     auto ed_get = [&](int j) -> float4 {
         if (j < CL) return s_ed[j * T + tid];
@@ -423,50 +441,19 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
             edr[r] = v.x; edr[r + 1] = v.y; edr[r + 2] = v.z; edr[r + 3] = v.w;
         }
     };
-#pragma unroll
-    for (int j = 0; j < CH; ++j) {
-        const int c = min(j * T + tid, last);
-        const float4 t = zt4[c];
-        ut[4 * j + 0] = t.x; ut[4 * j + 1] = t.y; ut[4 * j + 2] = t.z; ut[4 * j + 3] = t.w;
-        if (j >= CL) ed_put(j, zd4[c]);
-    }
-    // (the candidate is consumed from here on: its wait and the children's own logit loads come
-    // after every row load has been issued)
-    asm volatile("" : "+v"(cand.parent), "+v"(cand.token));
-    fetch_child_logits(zt, zd, a.V, node, cand);
-    // chunks 0..CL-1 of the draft row go from memory straight into this thread's LDS slots (no
-    // registers, raw logits; 64 lanes x 16 bytes land contiguously, which is the slot layout;
-    // issued last, so that the wait above counts register loads only)
-    if constexpr (CL > 0) {
-#pragma unroll
-        for (int j = 0; j < CL; ++j)
-            __builtin_amdgcn_global_load_lds((global_void *)(zd4 + min(j * T + tid, last)),
-                                             (lds_void *)(s_ed + j * T + wave * kWave), 16, 0, 0);
-    }
-    // The row maxima and the children's ranks share their barriers: every wave first reduces
-    // its part of the two rows (scaled in place) and takes the ballot of its candidates, then
-    // one barrier publishes both, and the ranks are written while the maxima are combined.
-    float mt = -INFINITY, md = -INFINITY;
-    // the LDS part of the draft row: wait for this wave's memory-to-LDS loads (the slots are the
-    // wave's own, so no barrier)
+    // Row maxima of the raw logits (a chunk past the end repeats real entries of the row, so it
+    // needs no mask here) and the children's ranks share their barriers.
     if constexpr (CL > 0) asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    // scaling: x * c2 + 0 for a chunk of the row, x * c2 - inf = -inf for a chunk past its end
+    float mt = -INFINITY, md = -INFINITY;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
-        const float bias = (j * T + tid <= last) ? 0.f : -INFINITY;
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-            ut[4 * j + e] = fmaf(ut[4 * j + e], c2, bias);
-            mt = fmaxf(mt, ut[4 * j + e]);
-        }
-        float4 d = ed_get(j);
-        d.x = fmaf(d.x, c2, bias); d.y = fmaf(d.y, c2, bias); d.z = fmaf(d.z, c2, bias); d.w = fmaf(d.w, c2, bias);
+        mt = fmaxf(mt, fmaxf(fmaxf(ut[4 * j], ut[4 * j + 1]), fmaxf(ut[4 * j + 2], ut[4 * j + 3])));
+        const float4 d = ed_get(j);
         md = fmaxf(md, fmaxf(fmaxf(d.x, d.y), fmaxf(d.z, d.w)));
-        ed_put(j, d);
+        if (j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
     }
     mt = wave_max(mt);
     md = wave_max(md);
-    const int lane = tid & (kWave - 1);
     const bool match = cand.parent == node;
     const unsigned long long cmask = __ballot(match);
     if (lane0) {
@@ -496,7 +483,6 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
     const int K = sh.g.K;
     if (K == 0) return;
     // bit (4 j + e) set: this thread's entry (j, e) is a child token
-    static_assert(CH * 4 <= 128, "element mask holds 128 entries");
     uint64_t elmask[2] = {0, 0};
     for (int i = 0; i < K; ++i) {
         const int x = sh.g.tok[i], c = x >> 2;
@@ -505,146 +491,266 @@ __device__ void process_group_reg(const RrsArgs &a, int b, int node, int n, Grou
             if (bit < 64) elmask[0] |= 1ull << bit; else elmask[1] |= 1ull << (bit - 64);
         }
     }
-    // children: lane t < K follows its token's two logits in fp64
-    double cu = 0.0, ce = 0.0;
-    if (tid < K) {
-        cu = (double)sh.czt[tid] * (double)c2;
-        ce = (double)sh.czd[tid] * (double)c2;
+    const float m_t = (mt == -INFINITY) ? 0.f : mt * c2h, m_d = (md == -INFINITY) ? 0.f : md * c2h;
+    // Exponents in place first.  Child tokens and heavy entries leave the fp32 arrays (exponent
+    // -inf); the heavy ones go to this wave's list with their raw logits.
+    int ncand = 0;  // (wave-uniform)
+    // (chunk numbers are worked out again here rather than kept from the load loop)
+    int tid_x = tid;
+    asm volatile("" : "+v"(tid_x));
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const bool inrow = j * T + tid_x <= last;
+        const float bt = inrow ? -m_t : -INFINITY, bd = inrow ? -m_d : -INFINITY;
+        const float4 dr = ed_get(j);
+        const float tz[4] = {ut[4 * j], ut[4 * j + 1], ut[4 * j + 2], ut[4 * j + 3]};
+        const float dz[4] = {dr.x, dr.y, dr.z, dr.w};
+        float at[4], ad[4];
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+            at[e] = exponent_of(tz[e], c2h, c2l, bt);
+            ad[e] = exponent_of(dz[e], c2h, c2l, bd);
+        }
+        const float amax = fmaxf(fmaxf(fmaxf(at[0], at[1]), fmaxf(at[2], at[3])),
+                                 fmaxf(fmaxf(ad[0], ad[1]), fmaxf(ad[2], ad[3])));
+        const uint32_t cbits = (uint32_t)(elmask[(4 * j) >> 6] >> ((4 * j) & 63)) & 0xFu;
+        if (__ballot(amax >= -kHeavy || cbits != 0u) != 0ull) {
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+                const bool child = (cbits >> e) & 1u;
+                const bool push = !child && (at[e] >= -kHeavy || ad[e] >= -kHeavy);
+                const unsigned long long bal = __ballot(push);
+                bool drop = child;
+                if (bal != 0ull) {
+                    const int slot = ncand + __popcll(bal & ((1ull << lane) - 1ull));
+                    if (push && slot < kCandCap) {
+                        s_trk_zt[wave * kCandCap + slot] = tz[e];
+                        s_trk_zd[wave * kCandCap + slot] = dz[e];
+                        drop = true;
+                    }
+                    ncand += __popcll(bal);
+                }
+                if (drop) {
+                    at[e] = -INFINITY;
+                    ad[e] = -INFINITY;
+                }
+            }
+        }
+#pragma unroll
+        for (int e = 0; e < 4; ++e) ut[4 * j + e] = at[e];
+        ed_put(j, make_float4(ad[0], ad[1], ad[2], ad[3]));
     }
-    const float mt_use = (mt == -INFINITY) ? 0.f : mt, md_use = (md == -INFINITY) ? 0.f : md;
-    // exponentials in place; the draft sum leaves out every child token
+    // ... then the exponentials and the sums of what stays in fp32, one straight line
     float st = 0.f, sd = 0.f;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
         float4 d = ed_get(j);
-        d.x = __builtin_amdgcn_exp2f(d.x - md_use);
-        d.y = __builtin_amdgcn_exp2f(d.y - md_use);
-        d.z = __builtin_amdgcn_exp2f(d.z - md_use);
-        d.w = __builtin_amdgcn_exp2f(d.w - md_use);
+        d.x = __builtin_amdgcn_exp2f(d.x);
+        d.y = __builtin_amdgcn_exp2f(d.y);
+        d.z = __builtin_amdgcn_exp2f(d.z);
+        d.w = __builtin_amdgcn_exp2f(d.w);
         ed_put(j, d);
 #pragma unroll
-        for (int e = 0; e < 4; ++e) ut[4 * j + e] = __builtin_amdgcn_exp2f(ut[4 * j + e] - mt_use);
+        for (int e = 0; e < 4; ++e) ut[4 * j + e] = __builtin_amdgcn_exp2f(ut[4 * j + e]);
         st += (ut[4 * j] + ut[4 * j + 1]) + (ut[4 * j + 2] + ut[4 * j + 3]);
-        const float dv[4] = {d.x, d.y, d.z, d.w};
-        float dsum[4];
-#pragma unroll
-        for (int e = 0; e < 4; ++e)
-            dsum[e] = ((elmask[(4 * j + e) >> 6] >> ((4 * j + e) & 63)) & 1ull) ? 0.f : dv[e];
-        sd += (dsum[0] + dsum[1]) + (dsum[2] + dsum[3]);
+        sd += (d.x + d.y) + (d.z + d.w);
+        if (j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
+    }
+    ncand = min(ncand, kCandCap);
+    __builtin_amdgcn_wave_barrier();
+    // the entries this lane follows in fp64: child `lane` (wave 0, lanes < K) or heavy entry lane - 16
+    const bool is_child = wave == 0 && lane < K;
+    const bool is_cand = lane >= 16 && lane - 16 < ncand;
+    const bool tracked = ncand > 0 || wave == 0;  // (wave-uniform)
+    double tU = 0.0, tE = 0.0;
+    if (tracked) {
+        float fzt = -INFINITY, fzd = -INFINITY;
+        if (is_child) {
+            fzt = sh.czt[lane];
+            fzd = sh.czd[lane];
+        } else if (is_cand) {
+            fzt = s_trk_zt[wave * kCandCap + lane - 16];
+            fzd = s_trk_zd[wave * kCandCap + lane - 16];
+        }
+        // (one copy of the fp64 exponential in the code, run twice: its temporaries would
+        // otherwise push the resident rows out of their registers)
+        double x = (double)fzt * a.c2e - (double)m_t;
+#pragma unroll 1
+        for (int i = 0; i < 2; ++i) {
+            asm volatile("" : "+v"(x));
+            const double r = (is_child || is_cand) ? exp2(x) : 0.0;
+            if (i == 0) {
+                tU = r;
+                x = (double)fzd * a.c2e - (double)m_d;
+            } else {
+                tE = r;
+            }
+        }
+        if (is_child) sh.ce[lane] = tE;
     }
     st = wave_sum(st);
     sd = wave_sum(sd);
-    if (tid < K) {
-        cu = exp2(cu - (double)mt_use);
-        ce = exp2(ce - (double)md_use);
-        sh.ce[tid] = ce;
-    }
-    if (lane0) {
-        sh.red[wave] = (double)st;
-        sh.red2[wave] = (double)sd;
+    {
+        double su = (double)st, se = (double)sd;
+        if (tracked) {
+            su += wave_sum_f64(tU);
+            se += wave_sum_f64(is_child ? 0.0 : tE);
+        }
+        if (lane0) {
+            sh.red[wave] = su;
+            sh.red2[wave] = se;
+        }
     }
     __syncthreads();
     double St = 0.0, Sd = 0.0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) { St += sh.red[w]; Sd += sh.red2[w]; }
-    // draft mass still available at stage k: the rest plus the children not yet removed.  Lane
-    // k writes 1 / s_k into the record; the stage loop below works the same number out in every
-    // thread (same order of additions), so no barrier stands between the two.
-    if (tid < RSD_K_MAX) {
-        double s = Sd;
-        for (int i = K - 1; i >= tid; --i) s += sh.ce[i];
-        const double inv = (tid < K) ? 1.0 / s : 0.0;
-        sh.g.inv_s[tid] = (float)inv;
-        sh.g.inv_S[tid] = 1.f;
-        if (tid == 0) {
-            sh.g.mt2 = mt_use;
-            sh.g.md2 = md_use;
-            sh.g.inv_st = (float)(1.0 / St);
-            if (!(St > 0.0) || !isfinite(St) || !(s > 0.0) || !isfinite(s)) sh.g.flags |= RSD_FLAG_NONFINITE;
-        }
+    if (tid == 0) {
+        sh.g.mt2 = m_t;
+        sh.g.md2 = m_d;
+        double s0 = Sd;
+        for (int i = 0; i < K; ++i) s0 += sh.ce[i];
+        if (!(St > 0.0) || !isfinite(St) || !(s0 > 0.0) || !isfinite(s0)) sh.g.flags |= RSD_FLAG_NONFINITE;
     }
     double A = St;  // q^(k) = u / A
     for (int k = 0; k < K; ++k) {
+        // draft mass still available at stage k: the rest plus the children not yet removed
         double s_k = Sd;
         for (int i = K - 1; i >= k; --i) s_k += sh.ce[i];
-        const double inv_sk = 1.0 / s_k;
+        const double gam = A / s_k;
         if (tid == k) {  // threshold of child k (Eq. (3))
-            const double p = ce * inv_sk;
-            sh.g.theta[k] = (p > 0.0) ? (float)fmin(1.0, cu / (A * p)) : 1.f;
+            const double p = tE / s_k;
+            sh.g.theta[k] = (p > 0.0) ? (float)fmin(1.0, tU / (A * p)) : 1.f;
         }
-        if (k == K - 1) break;
-        const float gamma = (float)(inv_sk * A);
+        if (k == K - 1) {
+            if (tid == 0) sh.g.gam[k] = gam;
+            break;
+        }
+        const float gh = (float)gam, gl = (float)(gam - (double)(float)gam);
+        const bool fine = A < St * 0.0625;  // (uniform) small residual mass: gamma as a pair of floats
         float part = 0.f;
+        if (!fine) {
 #pragma unroll
-        for (int j = 0; j < CH; ++j) {
-            const float4 d = ed_get(j);
-            part += fmaxf(fmaf(-gamma, d.x, ut[4 * j + 0]), 0.f);
-            part += fmaxf(fmaf(-gamma, d.y, ut[4 * j + 1]), 0.f);
-            part += fmaxf(fmaf(-gamma, d.z, ut[4 * j + 2]), 0.f);
-            part += fmaxf(fmaf(-gamma, d.w, ut[4 * j + 3]), 0.f);
+            for (int j = 0; j < CH; ++j) {
+                const float4 d = ed_get(j);
+                part += fmaxf(fmaf(-gh, d.x, ut[4 * j + 0]), 0.f);
+                part += fmaxf(fmaf(-gh, d.y, ut[4 * j + 1]), 0.f);
+                part += fmaxf(fmaf(-gh, d.z, ut[4 * j + 2]), 0.f);
+                part += fmaxf(fmaf(-gh, d.w, ut[4 * j + 3]), 0.f);
+                if (j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
+            }
+        } else {
+#pragma unroll
+            for (int j = 0; j < CH; ++j) {
+                const float4 d = ed_get(j);
+                part += fmaxf(fmaf(-gl, d.x, fmaf(-gh, d.x, ut[4 * j + 0])), 0.f);
+                part += fmaxf(fmaf(-gl, d.y, fmaf(-gh, d.y, ut[4 * j + 1])), 0.f);
+                part += fmaxf(fmaf(-gl, d.z, fmaf(-gh, d.z, ut[4 * j + 2])), 0.f);
+                part += fmaxf(fmaf(-gl, d.w, fmaf(-gh, d.w, ut[4 * j + 3])), 0.f);
+                if (j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
+            }
         }
+        const double cnew = fmax(tU - gam * tE, 0.0);
         part = wave_sum(part);
+        double wsum = (double)part;
+        if (tracked) wsum += wave_sum_f64(cnew);
         double *red = sh.sred[k & 1];
-        if (lane0) red[wave] = (double)part;
+        if (lane0) red[wave] = wsum;
         __syncthreads();
         double S = 0.0;
 #pragma unroll
         for (int w = 0; w < NW; ++w) S += red[w];
         const bool ok = S > 0.0 && isfinite(S);
-        if (ok) {
+        {
+            // One branch-free update for all cases (a stage that is skipped subtracts zero): the
+            // rows' registers then have a single definition per stage.
+            const float uh = ok ? gh : 0.f, ul = (ok && fine) ? gl : 0.f;
 #pragma unroll
             for (int j = 0; j < CH; ++j) {
                 const float4 d = ed_get(j);
-                ut[4 * j + 0] = fmaxf(fmaf(-gamma, d.x, ut[4 * j + 0]), 0.f);
-                ut[4 * j + 1] = fmaxf(fmaf(-gamma, d.y, ut[4 * j + 1]), 0.f);
-                ut[4 * j + 2] = fmaxf(fmaf(-gamma, d.z, ut[4 * j + 2]), 0.f);
-                ut[4 * j + 3] = fmaxf(fmaf(-gamma, d.w, ut[4 * j + 3]), 0.f);
+                ut[4 * j + 0] = fmaxf(fmaf(-ul, d.x, fmaf(-uh, d.x, ut[4 * j + 0])), 0.f);
+                ut[4 * j + 1] = fmaxf(fmaf(-ul, d.y, fmaf(-uh, d.y, ut[4 * j + 1])), 0.f);
+                ut[4 * j + 2] = fmaxf(fmaf(-ul, d.z, fmaf(-uh, d.z, ut[4 * j + 2])), 0.f);
+                ut[4 * j + 3] = fmaxf(fmaf(-ul, d.w, fmaf(-uh, d.w, ut[4 * j + 3])), 0.f);
+                if (j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
             }
-            if (tid < K) cu = fmax(cu - (double)gamma * ce, 0.0);
-            if (tid == 0) sh.g.inv_S[k] = (float)(A / S);
+        }
+        if (ok) {
+            tU = cnew;
+            if (tid == 0) sh.g.gam[k] = gam;
             A = S;
-        } else if (tid == 0) {  // keep q^(k): no subtraction, no rescale
-            sh.g.inv_s[k] = 0.f;
-            sh.g.inv_S[k] = 1.f;
+        } else if (tid == 0) {  // keep q^(k): no subtraction
+            sh.g.gam[k] = 0.0;
             sh.g.flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
         }
         // x_k leaves the draft distribution either way
-        if (tid == k) ce = 0.0;
-        if ((elmask[0] | elmask[1]) != 0ull) {
-            const int xk = sh.g.tok[k], ck = xk >> 2;
-            const int target = (ck % T == tid) ? (((ck / T) << 2) | (xk & 3)) : -1;
-            if (target >= 0) {
-#pragma unroll
-                for (int j = 0; j < CH; ++j) {
-                    if ((target >> 2) == j) {
-                        float4 d = ed_get(j);
-                        if ((target & 3) == 0) d.x = 0.f;
-                        if ((target & 3) == 1) d.y = 0.f;
-                        if ((target & 3) == 2) d.z = 0.f;
-                        if ((target & 3) == 3) d.w = 0.f;
-                        ed_put(j, d);
-                    }
-                }
-            }
-        }
+        if (tid == k) tE = 0.0;
     }
     __syncthreads();
+}
+
+// The resident variant on rows that it loads itself: one row pair per call, nothing overlapped
+// beyond the children's lookup.
+template <int T, int CH, int CL>
+__device__ void process_group_res(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
+    constexpr int CR = CH - CL;  // chunks of e_d held in registers
+    __shared__ float4 s_ed[CL > 0 ? CL * T : 1];
+    int tid = threadIdx.x;
+    asm volatile("" : "+v"(tid));
+    const int wave = tid / kWave;
+    const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
+    const float *zd = a.zd + ((int64_t)b * a.N + node) * a.V;
+    const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
+    const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
+    const int last = (a.V >> 2) - 1;
+    // The children's lookup is requested first and the rows right after it, before the lookup
+    // is used: its dependent steps (the children's own logits, two barriers) then run under
+    // the rows' memory latency.  Every row load is unconditional (a chunk past the end of the
+    // row reads the row's last chunk instead and gets the exponent -inf), so that the loads
+    // form one straight line and a wait can name exactly the loads it needs.
+    ChildCandidate cand = fetch_candidate(a, b, node, n, tid);
+    float ut[CH * 4], edr[CR * 4];
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const int c = min(j * T + tid, last);
+        const float4 t = zt4[c];
+        ut[4 * j + 0] = t.x; ut[4 * j + 1] = t.y; ut[4 * j + 2] = t.z; ut[4 * j + 3] = t.w;
+        if (j >= CL) {
+            const float4 d = zd4[c];
+            const int r = 4 * (j - CL);
+            edr[r] = d.x; edr[r + 1] = d.y; edr[r + 2] = d.z; edr[r + 3] = d.w;
+        }
+    }
+    // (the candidate is consumed from here on: its wait and the children's own logit loads come
+    // after every row load has been issued)
+    asm volatile("" : "+v"(cand.parent), "+v"(cand.token));
+    fetch_child_logits(zt, zd, a.V, node, cand);
+    // chunks 0..CL-1 of the draft row go from memory straight into this thread's LDS slots (no
+    // registers, raw logits; 64 lanes x 16 bytes land contiguously, which is the slot layout)
+    if constexpr (CL > 0) {
+#pragma unroll
+        for (int j = 0; j < CL; ++j)
+            __builtin_amdgcn_global_load_lds((global_void *)(zd4 + min(j * T + tid, last)),
+                                             (lds_void *)(s_ed + j * T + wave * kWave), 16, 0, 0);
+        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+    }
+    compute_group_res<T, CH, CL>(a, node, cand, ut, edr, s_ed, sh);
 }
 
 // CH == 0: streaming variant; else the resident variant with CH chunks per thread, CL of them in LDS
 template <int THREADS, int CH, int CL>
 __device__ __forceinline__ void verify_group(const RrsArgs &a, int b, int node, int n, GroupShared &sh) {
     if constexpr (CH > 0)
-        process_group_reg<THREADS, CH, CL>(a, b, node, n, sh);
+        process_group_res<THREADS, CH, CL>(a, b, node, n, sh);
     else
-        process_group<THREADS>(a, b, node, n, sh);
+        process_group_stream<THREADS>(a, b, node, n, sh);
 }
 
 // ---------------------------------------------------------------------------
 // Last-token sampling (Alg. 6, last lines): arg-max over x of log r(x) + G(x)
-// for entries [x_lo, x_hi) of one node.  r = q^(K+1) (unnormalised) when the
-// node's K children were all rejected, or the target row itself for a leaf.
-// Tracks a second arg-max over q^(K) used when the last residual is empty.
+// for entries [x_lo, x_hi) of one node.  r = u after all K stages (q^(K+1) up to a
+// factor) when the node's K children were all rejected, or the target row itself for
+// a leaf.  Tracks a second arg-max over q^(K) used when the last residual is empty.
 // ---------------------------------------------------------------------------
 __device__ __forceinline__ unsigned long long pack_key(float v, int idx) {
     uint32_t bits = __float_as_uint(v);
@@ -652,18 +758,44 @@ __device__ __forceinline__ unsigned long long pack_key(float v, int idx) {
     return ((unsigned long long)bits << 32) | (unsigned long long)(0xFFFFFFFFu - (uint32_t)idx);
 }
 
-// Hardware exp2 / log2 (one instruction each).  The logarithm's operand is scaled out of the
-// denormal range first, which the instruction would read as zero.
-__device__ __forceinline__ float fast_exp2(float x) { return __builtin_amdgcn_exp2f(x); }
+// Hardware log2 (one instruction).  The operand is scaled out of the denormal range first,
+// which the instruction would read as zero.
 __device__ __forceinline__ float fast_ln(float x) {
     const bool tiny = x < 0x1p-100f;
     const float l2 = __builtin_amdgcn_logf(tiny ? x * 0x1p100f : x) - (tiny ? 100.f : 0.f);
     return l2 * kLn2;
 }
 
+constexpr int kFinalHeavyCap = 256;  // fp64 entries per workgroup that get a thread of their own
+
+struct FinalShared {
+    int count;
+    int x[kFinalHeavyCap];
+};
+
+// Scores of one entry with the chain in fp64 from the raw logits (child tokens, heavy entries).
+__device__ __forceinline__ void final_scores_f64(const RrsArgs &a, const GroupRec &g, const float *zt,
+                                                 const float *zd, int x, uint32_t node, uint32_t seq,
+                                                 float &s_res, float &s_alt) {
+    const int K = g.K;
+    const int rs = removal_stage(x, g.tok, K);
+    const double U0 = exp2((double)zt[x] * a.c2e - (double)g.mt2);
+    const double E = exp2((double)zd[x] * a.c2e - (double)g.md2);
+    const double UK = chain1_f64(U0, E, rs, g, K - 1);
+    const double R = fmax(UK - g.gam[K - 1] * (K - 1 <= rs ? E : 0.0), 0.0);
+    const uint4 rnd = philox4x32_10((uint32_t)x >> 2, node, seq, counter_word3(kTagLastGumbel, a.step),
+                                    make_key(a.seed));
+    const uint32_t sel = (uint32_t)x & 3u;
+    const float gum = gumbel_from_word(sel == 0 ? rnd.x : (sel == 1 ? rnd.y : (sel == 2 ? rnd.z : rnd.w)));
+    s_res = (float)log(R) + gum;
+    s_alt = (float)log(UK) + gum;
+}
+
+// Every thread of the workgroup calls this (one barrier inside when the node has children).
 template <int THREADS>
 __device__ void final_sample_range(const RrsArgs &a, int b, int node, const GroupRec &g, int c_lo,
-                                   int c_hi, float &best_v, int &best_i, float &alt_v, int &alt_i) {
+                                   int c_hi, FinalShared &fs, float &best_v, int &best_i, float &alt_v,
+                                   int &alt_i) {
     const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
     const float *zd = a.zd + ((int64_t)b * a.N + node) * a.V;
     const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
@@ -687,8 +819,11 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
         }
         return;
     }
+    if (threadIdx.x == 0) fs.count = 0;
+    __syncthreads();
     const ChainRegs cr = load_chain(g);
-    const float inv_s_last = uniform_f(g.inv_s[K - 1]);
+    const float gh_last = uniform_f((float)g.gam[K - 1]);
+    const float gl_last = uniform_f((float)(g.gam[K - 1] - (double)(float)g.gam[K - 1]));
     const uint64_t hits = child_chunk_mask<THREADS>(g, c_lo, c_hi);
     int it = 0;
     for (int c = c_lo + (int)threadIdx.x; c < c_hi; c += THREADS, ++it) {
@@ -696,31 +831,48 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
         const float4 d = zd4[c];
         const uint4 rnd = philox4x32_10((uint32_t)c, (uint32_t)node, seq, c3, key);
         const uint32_t wd[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
-        const float et[4] = {fast_exp2(fmaf(t.x, a.c2, -cr.mt2)), fast_exp2(fmaf(t.y, a.c2, -cr.mt2)),
-                             fast_exp2(fmaf(t.z, a.c2, -cr.mt2)), fast_exp2(fmaf(t.w, a.c2, -cr.mt2))};
-        const float ed[4] = {fast_exp2(fmaf(d.x, a.c2, -cr.md2)), fast_exp2(fmaf(d.y, a.c2, -cr.md2)),
-                             fast_exp2(fmaf(d.z, a.c2, -cr.md2)), fast_exp2(fmaf(d.w, a.c2, -cr.md2))};
-        float q[4], r[4];
-        if (!((hits >> it) & 1ull)) {
-            chain4(et, ed, cr, K - 1, q);                                      // q^(K)
-#pragma unroll
-            for (int i = 0; i < 4; ++i) r[i] = fmaxf(q[i] - ed[i] * inv_s_last, 0.f);  // ~ q^(K+1)
-        } else {
-#pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const int rs = removal_stage((c << 2) + i, g.tok, K);
-                q[i] = chain1_masked(et[i], ed[i], rs, cr, K - 1);
-                r[i] = fmaxf(q[i] - ((rs < K - 1) ? 0.f : ed[i] * inv_s_last), 0.f);
-            }
-        }
+        const float tz[4] = {t.x, t.y, t.z, t.w}, dz[4] = {d.x, d.y, d.z, d.w};
+        float u[4], e[4];
+        bool f64[4];
+        const bool hit = (hits >> it) & 1ull;
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-            const float gum = gumbel_from_word(wd[i]);
-            const float s = fast_ln(r[i]) + gum;
-            const float s2 = fast_ln(q[i]) + gum;
-            if (better(s, (c << 2) + i, best_v, best_i)) { best_v = s; best_i = (c << 2) + i; }
-            if (better(s2, (c << 2) + i, alt_v, alt_i)) { alt_v = s2; alt_i = (c << 2) + i; }
+            const float at = exponent_of(tz[i], a.c2h, a.c2l, -cr.mt2);
+            const float ad = exponent_of(dz[i], a.c2h, a.c2l, -cr.md2);
+            // child tokens and heavy entries get the chain in fp64, from a thread of their own
+            f64[i] = at >= -kHeavy || ad >= -kHeavy || (hit && removal_stage((c << 2) + i, g.tok, K) < K);
+            u[i] = __builtin_amdgcn_exp2f(at);
+            e[i] = __builtin_amdgcn_exp2f(ad);
         }
+        chain4(u, e, cr, K - 1);  // ~ q^(K)
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+            const int x = (c << 2) + i;
+            float s, s2;
+            if (!f64[i]) {
+                const float gum = gumbel_from_word(wd[i]);
+                s2 = fast_ln(u[i]) + gum;
+                s = fast_ln(fmaxf(fmaf(-gl_last, e[i], fmaf(-gh_last, e[i], u[i])), 0.f)) + gum;
+            } else {
+                const int slot = atomicAdd(&fs.count, 1);
+                if (slot < kFinalHeavyCap) {
+                    fs.x[slot] = x;
+                    continue;
+                }
+                final_scores_f64(a, g, zt, zd, x, (uint32_t)node, seq, s, s2);  // (list full: in place)
+            }
+            if (better(s, x, best_v, best_i)) { best_v = s; best_i = x; }
+            if (better(s2, x, alt_v, alt_i)) { alt_v = s2; alt_i = x; }
+        }
+    }
+    __syncthreads();
+    const int nlist = min(fs.count, kFinalHeavyCap);
+    for (int t = threadIdx.x; t < nlist; t += THREADS) {
+        const int x = fs.x[t];
+        float s, s2;
+        final_scores_f64(a, g, zt, zd, x, (uint32_t)node, seq, s, s2);
+        if (better(s, x, best_v, best_i)) { best_v = s; best_i = x; }
+        if (better(s2, x, alt_v, alt_i)) { alt_v = s2; alt_i = x; }
     }
 }
 
@@ -741,7 +893,12 @@ __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
     // the counts are accumulated in LDS when they fit (LDS atomics instead of global ones)
     const bool in_lds = total <= kPlanLds;
     int *cnt = in_lds ? s_k : a.kcount;
-    for (int i = tid; i < total; i += kPlanThreads) cnt[i] = 0;
+    for (int i = tid; i < total; i += kPlanThreads) {
+        cnt[i] = 0;
+        // thresholds of nodes that no group verifies (the root, padding, children beyond the
+        // supported group size, nodes with an invalid parent) read NaN
+        if (a.theta) a.theta[i] = NAN;
+    }
     if (tid <= RSD_K_MAX) hist[tid] = 0;
     // the last kernel's per-sequence maxima and arrival counters start at zero
     for (int i = tid; i < a.B; i += kPlanThreads) {
@@ -773,6 +930,7 @@ __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
             running += hist[k];
         }
         a.wq[0] = running;
+        a.wq[1] = 0;
     }
     __syncthreads();
     for (int i = tid; i < total; i += kPlanThreads) {
@@ -785,30 +943,32 @@ __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
 }
 
 // ---------------------------------------------------------------------------
-// ALL_GROUPS, kernel 1: persistent workgroups go through the work list (largest groups
-// first) in rounds of gridDim.x items, forwards in even rounds and backwards in odd ones, so
-// that a workgroup that drew a large group in one round draws a small one in the next.  The
-// assignment is static: the next item's entry is read while the current group is verified.
+// ALL_GROUPS, kernel 1: persistent workgroups take items off the work list (largest groups
+// first) through one atomic counter; a workgroup asks for its next item, and reads that item's
+// entry, while it verifies the current one, so neither round trip is waited for.
 // ---------------------------------------------------------------------------
 template <int THREADS, int CH, int CL>
 __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
     const int count = a.wq[0];
-    const int G = gridDim.x, g = blockIdx.x;
-    auto item_of_round = [&](int r) { return r * G + ((r & 1) ? G - 1 - g : g); };
-    // (every lane reads the same entry through an offset the compiler cannot see is zero: the
-    // value then stays in a vector register, and its wait at the first use, one round later)
-    int lane_zero = 0;
-    asm volatile("" : "+v"(lane_zero));
-    int idx = item_of_round(0);
-    int2 ent = make_int2(0, 1);
-    if (idx < count) ent = a.work[idx + lane_zero];
-    for (int r = 0; idx < count; ++r) {
-        const int i = __builtin_amdgcn_readfirstlane(ent.x), n = __builtin_amdgcn_readfirstlane(ent.y);
-        const int nidx = item_of_round(r + 1);
-        // (an entry past the end of the list is never used: any entry will do, and the load
-        // stays unconditional)
-        int2 nent = a.work[min(nidx, count - 1) + lane_zero];
+    if (threadIdx.x == 0) {
+        const int first = atomicAdd(&a.wq[1], 1);
+        sh.next_idx = first;
+        sh.next_ent = a.work[min(first, max(count - 1, 0))];
+    }
+    __syncthreads();
+    int idx = sh.next_idx;
+    int2 ent = sh.next_ent;
+    __syncthreads();
+    while (idx < count) {
+        const int i = ent.x, n = ent.y;
+        // (thread 0 only; the two dependent round trips complete under this group's row loads)
+        int nidx = 0;
+        int2 nent = make_int2(0, 1);
+        if (threadIdx.x == 0) {
+            nidx = atomicAdd(&a.wq[1], 1);
+            nent = a.work[min(nidx, count - 1)];
+        }
         const int b = i / a.N, node = i - b * a.N;
         verify_group<THREADS, CH, CL>(a, b, node, n, sh);
         GroupRec *out = a.rec + i;
@@ -816,18 +976,16 @@ __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
         const uint32_t *src = reinterpret_cast<const uint32_t *>(&sh.g);
         uint32_t *dst = reinterpret_cast<uint32_t *>(out);
         for (int w = threadIdx.x; w < words; w += THREADS) dst[w] = src[w];
-        if (a.theta) {
-            // children beyond the supported group size are not verified: mark them
-            const int *par = a.parent + (int64_t)b * a.N;
-            const int last = sh.g.K > 0 ? sh.g.kid[sh.g.K - 1] : node;
-            for (int j = last + 1 + (int)threadIdx.x; j < n; j += THREADS)
-                if (par[j] == node) a.theta[(int64_t)b * a.N + j] = NAN;
-            if ((int)threadIdx.x < sh.g.K)
-                a.theta[(int64_t)b * a.N + sh.g.kid[threadIdx.x]] = sh.g.theta[threadIdx.x];
+        if (a.theta && (int)threadIdx.x < sh.g.K)
+            a.theta[(int64_t)b * a.N + sh.g.kid[threadIdx.x]] = sh.g.theta[threadIdx.x];
+        if (threadIdx.x == 0) {
+            sh.next_idx = nidx;
+            sh.next_ent = nent;
         }
+        __syncthreads();
+        idx = sh.next_idx;
+        ent = sh.next_ent;
         __syncthreads();  // sh is reused by the next item
-        ent = nent;
-        idx = nidx;
     }
 }
 
@@ -852,7 +1010,7 @@ struct WalkResult {
 __device__ __forceinline__ WalkResult walk_tree(const RrsArgs &a, int b, int lane, bool write, GroupRec &g) {
     constexpr int W_K = offsetof(GroupRec, K) / 4, W_FLAGS = offsetof(GroupRec, flags) / 4;
     constexpr int W_KID = offsetof(GroupRec, kid) / 4, W_TOK = offsetof(GroupRec, tok) / 4;
-    constexpr int W_INVS = offsetof(GroupRec, inv_s) / 4, W_THETA = offsetof(GroupRec, theta) / 4;
+    constexpr int W_GAM = offsetof(GroupRec, gam) / 4, W_THETA = offsetof(GroupRec, theta) / 4;
     constexpr int kWords = sizeof(GroupRec) / 4;
     static_assert(kWords <= 2 * kWave && RSD_K_MAX <= kWave, "a record is two words per lane at most");
     // word w of the record sits in lane w % 64, register w / 64
@@ -879,14 +1037,15 @@ __device__ __forceinline__ WalkResult walk_tree(const RrsArgs &a, int b, int lan
         flags |= gflags & RSD_FLAG_NONFINITE;
         const int kid = (int)word(r0, r1, W_KID + min(lane, RSD_K_MAX - 1));
         const float theta = __uint_as_float(word(r0, r1, W_THETA + min(lane, RSD_K_MAX - 1)));
-        const float inv_s = __uint_as_float(word(r0, r1, W_INVS + min(lane, RSD_K_MAX - 1)));
+        // (the high word of a stage's gamma: zero only for a skipped stage)
+        const uint32_t gam_hi = word(r0, r1, W_GAM + 2 * min(lane, RSD_K_MAX - 1) + 1);
         const bool ok = lane < K && accept_uniform(a, b, kid) < theta;
         const unsigned long long acc = __ballot(ok);
         const int took = acc ? __ffsll((long long)acc) - 1 : -1;
         // degenerate stages matter only if their residual was used
         if (gflags & RSD_FLAG_DEGENERATE_RESIDUAL) {
             const int used = took < 0 ? K - 1 : took;
-            if (__ballot(lane < used && inv_s == 0.f)) flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
+            if (__ballot(lane < used && gam_hi == 0u)) flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
         }
         if (took < 0) break;
         const int next = __shfl(kid, took, kWave);
@@ -915,6 +1074,7 @@ __device__ __forceinline__ WalkResult walk_tree(const RrsArgs &a, int b, int lan
 // the path.
 __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
     __shared__ GroupRec g;
+    __shared__ FinalShared fs;
     __shared__ float s_v[2 * kFinalThreads / kWave];
     __shared__ int s_i[2 * kFinalThreads / kWave];
     __shared__ int s_last;
@@ -928,7 +1088,6 @@ __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
     if (writer) {
         for (int j = tid; j < a.N; j += kFinalThreads) {
             if (a.uniforms) a.uniforms[(int64_t)b * a.N + j] = (j < n) ? accept_uniform(a, b, j) : 0.f;
-            if (a.theta && (j == 0 || j >= n)) a.theta[(int64_t)b * a.N + j] = NAN;
         }
     }
     if (tid < kWave) {
@@ -957,7 +1116,7 @@ __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
     const int c_lo = min(split * per, nchunk), c_hi = min(c_lo + per, nchunk);
     float bv, av;
     int bi, ai;
-    final_sample_range<kFinalThreads>(a, b, node, g, c_lo, c_hi, bv, bi, av, ai);
+    final_sample_range<kFinalThreads>(a, b, node, g, c_lo, c_hi, fs, bv, bi, av, ai);
     block_argmax_pair<kFinalThreads>(bv, bi, av, ai, s_v, s_i);
     if (nsplit > 1) {
         if (threadIdx.x == 0) {
@@ -996,6 +1155,7 @@ __global__ __launch_bounds__(kFinalThreads) void rrs_final_kernel(RrsArgs a) {
 template <int THREADS, int CH, int CL>
 __global__ __launch_bounds__(THREADS) void rrs_path_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
+    __shared__ FinalShared fs;
     __shared__ float s_v[2 * THREADS / kWave];
     __shared__ int s_i[2 * THREADS / kWave];
     __shared__ int s_nacc;
@@ -1036,7 +1196,7 @@ __global__ __launch_bounds__(THREADS) void rrs_path_kernel(RrsArgs a) {
             if (sh.g.flags & RSD_FLAG_DEGENERATE_RESIDUAL) {
                 const int used = took < 0 ? K - 1 : took;
                 for (int j = 0; j < used; ++j)
-                    if (sh.g.inv_s[j] == 0.f) flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
+                    if (sh.g.gam[j] == 0.0) flags |= RSD_FLAG_DEGENERATE_RESIDUAL;
             }
             s_flags = flags;
             if (took >= 0) {
@@ -1059,7 +1219,7 @@ __global__ __launch_bounds__(THREADS) void rrs_path_kernel(RrsArgs a) {
     const int node = sh.cur;
     float bv, av;
     int bi, ai;
-    final_sample_range<THREADS>(a, b, node, sh.g, 0, a.V >> 2, bv, bi, av, ai);
+    final_sample_range<THREADS>(a, b, node, sh.g, 0, a.V >> 2, fs, bv, bi, av, ai);
     block_argmax_pair<THREADS>(bv, bi, av, ai, s_v, s_i);
     if (tid == 0) {
         uint32_t flags = s_flags;
@@ -1114,7 +1274,11 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
     RrsArgs a{};
     a.zd = draft_logits; a.zt = target_logits; a.B = B; a.N = N_max; a.V = V;
     a.inv_t = inv_temperature;
-    a.c2 = (float)((double)inv_temperature * 1.4426950408889634);
+    // c = log2(e) / T in fp64 and as a pair of floats with a strictly positive low part
+    a.c2e = (double)inv_temperature * 1.4426950408889634;
+    a.c2h = (float)a.c2e;
+    if ((double)a.c2h >= a.c2e) a.c2h = nextafterf(a.c2h, 0.f);
+    a.c2l = (float)(a.c2e - (double)a.c2h);
     a.tokens = tokens; a.parent = parent; a.n_nodes = n_nodes; a.seq_id = seq_id;
     a.seed = seed; a.step = step; a.accepted_nodes = accepted_nodes;
     a.accepted_tokens = accepted_tokens; a.depth_max = depth_max; a.n_accepted = n_accepted;
@@ -1128,38 +1292,41 @@ extern "C" int32_t rsd_recursive_reject(const float *draft_logits, const float *
     a.work = reinterpret_cast<int2 *>(ws + off); off += 2 * align_up((size_t)B * N_max * 4, 256);
     a.wq = reinterpret_cast<int *>(ws + off);
     hipStream_t st = (hipStream_t)stream;
-    // Rows of up to 32768 entries fit the register-resident variant (128 data registers per
-    // thread); up to 52224 entries (the 50k vocabularies) the variant that keeps most of the
-    // draft row in LDS; beyond that the rows are streamed from memory at every stage.
-    const bool reg16 = V <= kRegThreads * 4 * 16;
-    const bool lds13 = !reg16 && V <= kLdsThreads * 4 * kLdsChunks;
+    // Which variant holds a row (see the constants at the top of this file).
+    const bool small = V <= kSmallThreads * 4 * kSmallChunks;
+    const bool reg = !small && V <= kRegThreads * 4 * kRegChunks;
+    const bool lds = !small && !reg && V <= kLdsThreads * 4 * kLdsChunks;
     if (mode == RSD_MODE_PATH) {
-        if (reg16)
-            hipLaunchKernelGGL((rrs_path_kernel<kRegThreads, 16, 0>), dim3(B), dim3(kRegThreads), 0, st, a);
-        else if (lds13)
+        if (small)
+            hipLaunchKernelGGL((rrs_path_kernel<kSmallThreads, kSmallChunks, 0>), dim3(B), dim3(kSmallThreads), 0, st, a);
+        else if (reg)
+            hipLaunchKernelGGL((rrs_path_kernel<kRegThreads, kRegChunks, kRegChunksInLds>), dim3(B),
+                               dim3(kRegThreads), 0, st, a);
+        else if (lds)
             hipLaunchKernelGGL((rrs_path_kernel<kLdsThreads, kLdsChunks, kLdsChunksInLds>), dim3(B),
                                dim3(kLdsThreads), 0, st, a);
         else
-            hipLaunchKernelGGL((rrs_path_kernel<kGroupThreads, 0, 0>), dim3(B), dim3(kGroupThreads), 0, st, a);
+            hipLaunchKernelGGL((rrs_path_kernel<kStreamThreads, 0, 0>), dim3(B), dim3(kStreamThreads), 0, st, a);
     } else {
-        static int n_cu = 0;
-        if (n_cu == 0) {
-            int dev = 0, cus = 0;
-            if (hipGetDevice(&dev) != hipSuccess ||
-                hipDeviceGetAttribute(&cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || cus < 1)
-                cus = 256;
-            n_cu = cus;
-        }
+        int dev = 0, n_cu = 0;
+        if (hipGetDevice(&dev) != hipSuccess ||
+            hipDeviceGetAttribute(&n_cu, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess || n_cu < 1)
+            n_cu = 256;
         const long items_max = (long)B * N_max;
-        const int grid = (int)(items_max < n_cu ? items_max : n_cu);
+        // persistent workgroups: as many as are resident at once (two per CU where two fit)
+        auto grid_for = [&](int per_cu) { return (int)(items_max < (long)per_cu * n_cu ? items_max : (long)per_cu * n_cu); };
         hipLaunchKernelGGL(rrs_plan_kernel, dim3(1), dim3(kPlanThreads), 0, st, a);
-        if (reg16)
-            hipLaunchKernelGGL((rrs_group_kernel<kRegThreads, 16, 0>), dim3(grid), dim3(kRegThreads), 0, st, a);
-        else if (lds13)
-            hipLaunchKernelGGL((rrs_group_kernel<kLdsThreads, kLdsChunks, kLdsChunksInLds>), dim3(grid),
+        if (small)
+            hipLaunchKernelGGL((rrs_group_kernel<kSmallThreads, kSmallChunks, 0>), dim3(grid_for(4)),
+                               dim3(kSmallThreads), 0, st, a);
+        else if (reg)
+            hipLaunchKernelGGL((rrs_group_kernel<kRegThreads, kRegChunks, kRegChunksInLds>), dim3(grid_for(1)),
+                               dim3(kRegThreads), 0, st, a);
+        else if (lds)
+            hipLaunchKernelGGL((rrs_group_kernel<kLdsThreads, kLdsChunks, kLdsChunksInLds>), dim3(grid_for(1)),
                                dim3(kLdsThreads), 0, st, a);
         else
-            hipLaunchKernelGGL((rrs_group_kernel<kGroupThreads, 0, 0>), dim3(2 * grid), dim3(kGroupThreads), 0, st, a);
+            hipLaunchKernelGGL((rrs_group_kernel<kStreamThreads, 0, 0>), dim3(grid_for(2)), dim3(kStreamThreads), 0, st, a);
         // enough workgroups to fill the chip, but no more: every split costs two device-wide fences
         int fsplits = 256 / (B > 0 ? B : 1);
         fsplits = fsplits < 1 ? 1 : (fsplits > kFinalSplitsMax ? kFinalSplitsMax : fsplits);

@@ -609,6 +609,68 @@ def test_recursive_reject_matches_oracle(mode, kind, B, V, branching, inv_t):
     assert near <= 1
 
 
+@pytest.mark.parametrize("V,inv_t,closeness", [
+    (32000, 1.0 / 0.3, 0.1),     # sharp rows, drafter close to the target: residual masses down to ~1e-5
+    (32000, 1.0 / 0.3, 1.0),     # sharp rows, the ordinary drafter
+    (32000, 1.0, 0.02),          # flat rows and a very close drafter: many entries cancel a little
+    (50272, 1.0 / 0.3, 0.1),     # the variant with most of the draft row in LDS
+    (4000, 1.0 / 0.3, 0.05),     # small-vocabulary variant
+])
+def test_recursive_reject_small_residual_mass(V, inv_t, closeness):
+    """Stages whose residual mass S_k = sum (q^(k) - p^(k))^+ is a small fraction of what went in:
+    the leading digits of q - p cancel at the probable tokens, and the thresholds of the later
+    siblings see that error divided by S_k.  Every sibling's threshold of every group (ALL_GROUPS)
+    is compared with the oracle at the ordinary tolerance; the oracle's own chain confirms that the
+    regime is reached."""
+    say(f"rrs small residual mass V={V} invT={inv_t:.2f} draft-target distance x{closeness}")
+    d = dev()
+    B, branching = 4, (5, 3)
+    n_cap = 1 + 5 + 15
+    zt, zd = workloads.make_logits("zipf", B, n_cap, V, seed=31)
+    zd = (zt + closeness * (zd - zt)).contiguous()
+    counts = [workloads.full_tree_child_counts(branching)] * B
+    tree = draft_tree.create_draft_tree_const(zd.to(d), counts, seed=31, step=4, inv_temperature=inv_t)
+    g = binding.recursive_reject(zd.to(d), zt.to(d), tree["tokens"], tree["parent"], tree["n_nodes"],
+                                 inv_temperature=inv_t, mode=binding.MODE_ALL_GROUPS, seed=31, step=4)
+    tokens, parent, n_nodes = to_np(tree["tokens"]), to_np(tree["parent"]), to_np(tree["n_nodes"])
+    ref = o_rrs.recursive_reject(zt.numpy(), zd.numpy(), tokens, parent, n_nodes,
+                                 inv_temperature=np.float32(inv_t), mode=o_rrs.MODE_ALL_GROUPS, seed=31, step=4)
+    # how small the residual masses get (oracle arithmetic, per stage, relative to the stage's input)
+    smallest = 1.0
+    for b in range(B):
+        for node in range(int(n_nodes[b])):
+            kids = o_rrs.children_of(parent[b], n_nodes[b], node)
+            if len(kids) < 2:
+                continue
+            q = o_rrs.softmax_row(zt[b, node].numpy(), np.float32(inv_t))
+            p = o_rrs.softmax_row(zd[b, node].numpy(), np.float32(inv_t))
+            for x in tokens[b, kids[:-1]]:
+                mass = np.maximum(q - p, 0.0).sum()
+                smallest = min(smallest, float(mass))
+                _, res, _ = o_rrs.sibling_chain(q, p, [x])
+                q = res[1]
+                p = p.copy(); p[x] = 0.0; p /= p.sum()
+    th_g, th_r = to_np(g["theta"]).astype(np.float64), ref["theta"]
+    both = np.isfinite(th_r)
+    assert np.array_equal(np.isfinite(th_g), both)
+    err = np.abs(th_g[both] - th_r[both]) / (1e-6 + 1e-5 * np.abs(th_r[both]))
+    say(f"  smallest stage residual mass {smallest:.2e}; worst threshold error {err.max():.2f} of the tolerance")
+    if closeness <= 0.1:
+        assert smallest < 1e-2
+    assert np.allclose(th_g[both], th_r[both], rtol=1e-5, atol=1e-6)
+    near = 0
+    for b in range(B):
+        if ref["near_tie"][b] or ref["last_gap"][b] < NEAR_TIE:
+            near += 1
+            continue
+        k = int(ref["n_accepted"][b])
+        assert int(g["n_accepted"][b]) == k
+        assert np.array_equal(to_np(g["accepted_nodes"])[b, :k], ref["accepted_nodes"][b, :k])
+        assert int(g["final_node"][b]) == int(ref["final_node"][b])
+        assert int(g["last_token"][b]) == int(ref["last_token"][b]), (b, k)
+    assert near <= 1
+
+
 def test_recursive_reject_on_sbs_tree_and_ragged_subtrees():
     say("rrs on an SBS tree (interleaved parents) and random subtrees")
     near, ref = _rrs_case("zipf", 3, 32000, None, 37, 13, 1.0, binding.MODE_ALL_GROUPS, sbs=(6, 6))
