@@ -4,9 +4,10 @@
 A step is one pass of the whole hot path over one batch of synthetic input that
 is already resident in HBM: drafting (Gumbel-Top-k per tree level, or the
 Stochastic Beam Search steps), one layer of tree-masked attention, and recursive
-rejection sampling.  The headline value is tree nodes per second of the whole
-step; the attention+verification-only figure of the metric's definition
-(B*N / (t_attention_one_layer + t_rrs)) is reported beside it.
+rejection sampling.  The headline value is the metric's own definition,
+tree nodes / (t_attention_one_layer + t_rrs); the figure over the whole step
+(drafting included) is reported beside it as value_full_step, and ms_per_step is
+the whole step.
 
 Prints ONE JSON line.  Default workload: the largest single-GPU configuration
 ("cfg4_stress"); the other configurations are timed briefly and listed under
@@ -22,9 +23,30 @@ ROOT = os.path.dirname(os.path.abspath(__file__))
 if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
-# HBM bytes per launch of the dominant kernel from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs,
-# scaled by the same counters over plain device copies (profiles/cfg4_stress_attention_traffic.md).
-MEASURED_TRAFFIC_BYTES = {"cfg4_stress": 8.758e9}
+# HBM bytes per launch of the dominant kernel come from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE runs
+# scaled by the same counters over plain device copies.  The figure is not kept here: it is read
+# from the committed summary of those runs (a line "traffic_bytes_per_launch: <number>"), which also
+# names the kernel source it was taken on; a summary taken on another kernel source gives null.
+TRAFFIC_SUMMARY = {"cfg4_stress": os.path.join(ROOT, "profiles", "cfg4_stress_attention_traffic.md")}
+ATTENTION_SOURCE = os.path.join(ROOT, "paper_2402_14160_amd", "csrc", "tree_attention.hip")
+
+
+def measured_traffic(name):
+    """(bytes per launch, provenance) from the committed counter summary, or (None, reason)."""
+    import hashlib
+    import re
+    path = TRAFFIC_SUMMARY.get(name)
+    if not path or not os.path.exists(path):
+        return None, "no counter summary committed for this workload"
+    text = open(path).read()
+    m = re.search(r"traffic_bytes_per_launch:\s*([0-9.eE+]+)", text)
+    h = re.search(r"kernel_source_sha256_16:\s*([0-9a-f]{16})", text)
+    if not m or not h:
+        return None, "counter summary has no machine-readable figure"
+    now = hashlib.sha256(open(ATTENTION_SOURCE, "rb").read()).hexdigest()[:16]
+    if h.group(1) != now:
+        return None, f"counter summary was taken on kernel source {h.group(1)}, this build is {now}"
+    return float(m.group(1)), os.path.relpath(path, ROOT)
 
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
@@ -208,10 +230,20 @@ def report(case, t):
                         if draft_s > 0 and cfg["sampler"] == "gumbel" else None),
         draft_GBps=fig["draft_bytes"] / draft_s / 1e9 if draft_s > 0 else None,
         draft_frac_hbm=fig["draft_bytes"] / draft_s / 1e9 / HBM_PEAK_GBS if draft_s > 0 else None,
-        model_equiv_nodes_per_s=(fig["nodes"] / (N_LAYERS[cfg["name"]] * attn_s + rrs_s)
-                                 if cfg["name"] in N_LAYERS else None),
     )
     return out, fig
+
+
+def model_step(rep, fig, layers):
+    """Tree nodes per second of a whole-model verification step: all layers' tree attention (measured
+    in one multi-layer call; scaled from the measured layers when the model's K/V does not fit the
+    memory budget of the benchmark) plus one recursive rejection sampling call."""
+    if not layers:
+        return {}
+    scale = layers["layers_of_model"] / layers["layers"]
+    t = layers["layers_ms"] * scale / 1e3 + rep["rrs_ms"] / 1e3
+    return dict(model_step_nodes_per_s=fig["nodes"] / t,
+                model_step_layers_measured=layers["layers"], model_step_layers_of_model=layers["layers_of_model"])
 
 
 def cpu_baseline(case, fig, torch, budget_s=12.0):
@@ -299,6 +331,66 @@ def vocab_pass(case, torch, binding, steps=10):
     ms = e0.elapsed_time(e1) / steps
     gbs = rows.numel() * 4 / ms / 1e6
     return dict(lse_ms=round(ms, 4), lse_GBps=gbs, lse_frac_hbm=gbs / HBM_PEAK_GBS)
+
+
+def layers_pass(case, torch, binding, workloads, steps=5, mem_budget=48 << 30):
+    """Tree attention of ALL layers of the model the shape stands for in one call
+    (rsd_tree_attention_layers: the layers share the tree, its mask and the launch plan), on
+    distinct K/V buffers per layer, so nothing is served from the on-package cache.  Also times the
+    single-layer call rotated over those buffers (the cold figure of the one-layer call)."""
+    cfg, tree = case["cfg"], case["tree"]
+    if cfg["name"] not in N_LAYERS or cfg["dtype"] != "bf16":
+        return {}
+    dev = case["q"].device
+    B, Hq, Hkv, N, D, P = cfg["B"], cfg["Hq"], cfg["Hkv"], cfg["N"], cfg["D"], cfg["P"]
+    per_layer = 2 * B * Hkv * (P + N) * D * 2
+    want = N_LAYERS[cfg["name"]]
+    L = max(1, min(want, mem_budget // per_layer))
+    q = torch.empty((L, B, Hq, N, D), dtype=torch.bfloat16, device=dev)
+    kp = torch.empty((L, B, Hkv, P, D), dtype=torch.bfloat16, device=dev)
+    vp = torch.empty_like(kp)
+    kt = torch.empty((L, B, Hkv, N, D), dtype=torch.bfloat16, device=dev)
+    vt = torch.empty_like(kt)
+    for l in range(L):
+        ql, kpl, vpl, ktl, vtl = workloads.make_qkv(B, Hq, Hkv, N, D, P, "bf16", 1000 + l, device=dev)
+        q[l], kp[l], vp[l], kt[l], vt[l] = ql, kpl, vpl, ktl, vtl
+        del ql, kpl, vpl, ktl, vtl
+    out = torch.empty((L, B, Hq, N, D), dtype=torch.float32, device=dev)
+    nn, par, plen, scale = tree["n_nodes"], tree["parent"], case["plen"], case["scale"]
+    run = lambda: binding.tree_attention_layers(q, kp, vp, kt, vt, plen, nn, par, scale, out=out)
+    ev = lambda: torch.cuda.Event(enable_timing=True)
+    run()
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    e0.record()
+    for _ in range(steps):
+        run()
+    e1.record()
+    torch.cuda.synchronize()
+    ms = e0.elapsed_time(e1) / steps
+    # one-layer call on a different layer's buffers every time (cold) ...
+    one = lambda l: binding.tree_attention(q[l], kp[l], vp[l], kt[l], vt[l], plen, nn, par, scale, out=out[l])
+    one(0)
+    torch.cuda.synchronize()
+    e0, e1 = ev(), ev()
+    reps = max(L, 8)
+    e0.record()
+    for i in range(reps):
+        one(i % L)
+    e1.record()
+    torch.cuda.synchronize()
+    cold_ms = e0.elapsed_time(e1) / reps
+    fig = algorithmic_figures(case)
+    res = dict(layers=L, layers_of_model=want, layers_ms=round(ms, 4), ms_per_layer=round(ms / L, 5),
+               layers_GBps=fig["attn_bytes"] * L / ms / 1e6, layers_TFLOPs=fig["attn_flops"] * L / ms / 1e9,
+               layers_frac_hbm=fig["attn_bytes"] * L / ms / 1e6 / HBM_PEAK_GBS,
+               layers_frac_mfma=fig["attn_flops"] * L / ms / 1e9 / MFMA_BF16_PEAK_TFLOPS,
+               one_layer_cold_ms=round(cold_ms, 4),
+               one_layer_cold_GBps=fig["attn_bytes"] / cold_ms / 1e6,
+               one_layer_cold_TFLOPs=fig["attn_flops"] / cold_ms / 1e9)
+    del q, kp, vp, kt, vt, out
+    torch.cuda.empty_cache()
+    return res
 
 
 def rrs_path_pass(case, torch, binding, steps=20):
@@ -412,16 +504,20 @@ def main():
     vocab.update(rrs_path_pass(case, torch, binding))
     vocab.update(filter_kv_pass(case, torch, binding))
     vocab.update(filter_logits_pass(case, torch, binding))
+    layers = layers_pass(case, torch, binding, workloads)
+    vocab.update(layers)
+    vocab.update(model_step(rep, fig, layers))
 
     # roofline of the dominant kernel: the tree-attention launch
     bound = rep["attn_bound"]
+    traffic, traffic_source = measured_traffic(cfg["name"])
     if bound == "hbm":
         roof = dict(bound="hbm", achieved=rep["attn_GBps"], peak=HBM_PEAK_GBS, unit="GB/s",
-                    frac=rep["attn_frac_hbm"], traffic=MEASURED_TRAFFIC_BYTES.get(cfg["name"]),
+                    frac=rep["attn_frac_hbm"], traffic=traffic, traffic_source=traffic_source,
                     kernel="tree_attn_bf16_kernel", algorithmic_bytes=fig["attn_bytes"])
     else:
         roof = dict(bound="mfma", achieved=rep["attn_TFLOPs"], peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s",
-                    frac=rep["attn_frac_mfma"], traffic=MEASURED_TRAFFIC_BYTES.get(cfg["name"]),
+                    frac=rep["attn_frac_mfma"], traffic=traffic, traffic_source=traffic_source,
                     kernel="tree_attn_bf16_w32_kernel", algorithmic_flops=fig["attn_flops"])
 
     per_config = {}
@@ -433,8 +529,11 @@ def main():
             torch.cuda.empty_cache()
             case = build_case(dict(other), args.seed, torch, binding, draft_tree, workloads)
             tt = time_case(case, max(5, args.steps), args.warmup, torch)
-            per_config[other["name"]], _ = report(case, tt)
+            per_config[other["name"]], ofig = report(case, tt)
             per_config[other["name"]]["graph_ms_per_step"] = round(graph_step_ms(case, torch), 4)
+            olayers = layers_pass(case, torch, binding, workloads)
+            per_config[other["name"]].update(olayers)
+            per_config[other["name"]].update(model_step(per_config[other["name"]], ofig, olayers))
         del case
         torch.cuda.empty_cache()
         case = build_case(cfg, args.seed, torch, binding, draft_tree, workloads)
@@ -443,18 +542,20 @@ def main():
 
     line = dict(
         metric="draft-tree nodes verified/sec (attn+RRS) at 1 GPU; % HBM and % MFMA peak",
-        value=rep["nodes_per_s_full_step"], unit="tree nodes/s", n_gpus=1, steps=args.steps,
+        value=rep["nodes_per_s_attn_rrs"], unit="tree nodes/s", n_gpus=1, steps=args.steps,
         warmup=args.warmup, ms_per_step=rep["ms_per_step"], higher_is_better=True, scaling="weak",
         vs_baseline=None, dtype="bf16" if cfg["dtype"] == "bf16" else "f32", data="synthetic",
         config=dict(workload=cfg["name"], batch=cfg["B"], vocab=cfg["V"], nodes_per_seq=cfg["N"],
                     q_heads=cfg["Hq"], kv_heads=cfg["Hkv"], head_dim=cfg["D"], kv_prefix=cfg["P"],
                     sampler=cfg["sampler"], rrs_mode="all_groups"),
-        value_attn_rrs_only=rep["nodes_per_s_attn_rrs"],
+        value_definition="tree nodes / (one layer of tree attention + recursive rejection sampling), both timed "
+                         "inside the whole step",
+        value_full_step=rep["nodes_per_s_full_step"],
         phases=dict(draft_ms=rep["draft_ms"], attn_ms=rep["attn_ms"], rrs_ms=rep["rrs_ms"],
                     attn_GBps=rep["attn_GBps"], attn_TFLOPs=rep["attn_TFLOPs"],
                     rrs_GBps=rep["rrs_GBps"], rrs_per_sibling_GBps=rep["rrs_per_sibling_GBps"],
-                    draft_GBps=rep["draft_GBps"], draft_alu_frac=rep["draft_alu_frac"],
-                    model_equiv_nodes_per_s=rep["model_equiv_nodes_per_s"], **vocab),
+                    rrs_frac_hbm=rep["rrs_frac_hbm"],
+                    draft_GBps=rep["draft_GBps"], draft_alu_frac=rep["draft_alu_frac"], **vocab),
         roofline=roof, cpu_baseline=cpu, per_config=per_config,
     )
     print(json.dumps(line))

@@ -20,7 +20,8 @@
  *    counter = (vocab_index >> 2, node_row, seq, tag | step << 4); entry x uses
  *    output word x & 3.  Tags: 0 drafting Gumbel noise, 1 accept/reject uniform
  *    (vocab_index 0, node_row = the verified node), 2 last-token Gumbel noise
- *    (node_row = the node whose distribution is sampled).  A 32-bit word w maps
+ *    (node_row = the node whose distribution is sampled).  Only the low 28 bits of
+ *    `step` enter the counter: streams repeat after 2^28 steps of one seed.  A 32-bit word w maps
  *    to u = (2*(w >> 9) + 1) * 2^-24 and to the Gumbel variate -log(-log u).
  *  - Tree layout: nodes of one sequence are stored in level order; node 0 is the
  *    root (the last already-known token), parent[0] = -1 and 0 <= parent[i] < i
@@ -206,6 +207,36 @@ int32_t rsd_tree_attention(const void *q, const void *k_prefix, const void *v_pr
                            const int32_t *parent, float scale, int32_t num_splits,
                            float *out, float *lse_out,
                            void *workspace, size_t workspace_bytes, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * The same attention for L layers in one call (Alg. 2 / Alg. 7, step 2: the target
+ * model evaluates the draft tree in every layer; the tree, its mask and the prefix
+ * lengths are the same in all of them).  Layer l reads q + l * q_stride_l,
+ * k_prefix / v_prefix + l * prefix_stride_l, k_tree / v_tree + l * tree_stride_l and
+ * writes out + l * out_stride_l (lse_out + l * lse_stride_l); strides are in
+ * elements of the respective tensor, multiples of 8 (bf16) or 4 (fp32) for the
+ * inputs and of 4 for `out`.  Inside a layer every tensor is laid out as for
+ * rsd_tree_attention, and every output row equals what that call gives for the
+ * layer alone.  The ancestor sets and the launch plan are shared: the work of all
+ * L * B (layer, sequence) pairs goes into one set of launches, so that a small
+ * batch fills the chip over its layers instead of splitting the prefix.
+ * Limits: those of rsd_tree_attention, 1 <= L, L * B <= 65535.
+ * Workspace: rsd_tree_attention_layers_workspace_bytes(...) with the same num_splits.
+ * ------------------------------------------------------------------------- */
+size_t rsd_tree_attention_layers_workspace_bytes(int32_t dtype, int32_t L, int32_t B, int32_t H_q,
+                                                 int32_t H_kv, int32_t N_max, int32_t D,
+                                                 int32_t P_max, int32_t num_splits);
+int32_t rsd_tree_attention_layers(const void *q, const void *k_prefix, const void *v_prefix,
+                                  const void *k_tree, const void *v_tree, int32_t dtype,
+                                  int32_t L, int64_t q_stride_l, int64_t prefix_stride_l,
+                                  int64_t tree_stride_l, int64_t out_stride_l, int64_t lse_stride_l,
+                                  int32_t B, int32_t H_q, int32_t H_kv, int32_t N_max, int32_t D,
+                                  int32_t P_max, int64_t prefix_stride_b, int64_t prefix_stride_h,
+                                  int64_t prefix_stride_p,
+                                  const int32_t *prefix_len, const int32_t *n_nodes,
+                                  const int32_t *parent, float scale, int32_t num_splits,
+                                  float *out, float *lse_out,
+                                  void *workspace, size_t workspace_bytes, void *stream);
 
 /* ---------------------------------------------------------------------------
  * Recursive rejection sampling over the draft tree (Sec. 3.1, Eqs. (1)-(4),

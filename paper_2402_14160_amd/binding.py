@@ -42,6 +42,10 @@ _SIGNATURES = {
     "rsd_tree_attention_workspace_bytes": (_sz, [_i32] * 8),
     "rsd_tree_attention": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i32,
                                   _i64, _i64, _i64, _vp, _vp, _vp, _f32, _i32, _vp, _vp, _vp, _sz, _vp]),
+    "rsd_tree_attention_layers_workspace_bytes": (_sz, [_i32] * 9),
+    "rsd_tree_attention_layers": (_i32, [_vp, _vp, _vp, _vp, _vp, _i32, _i32, _i64, _i64, _i64, _i64, _i64,
+                                         _i32, _i32, _i32, _i32, _i32, _i32, _i64, _i64, _i64, _vp, _vp, _vp,
+                                         _f32, _i32, _vp, _vp, _vp, _sz, _vp]),
     "rsd_recursive_reject_workspace_bytes": (_sz, [_i32, _i32, _i32]),
     "rsd_recursive_reject": (_i32, [_vp, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _i32,
                                     _u64, _u32, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp,
@@ -223,6 +227,45 @@ def tree_attention(q, k_prefix, v_prefix, k_tree, v_tree, prefix_len, n_nodes, p
                                     dtype, B, Hq, Hkv, N, D, P_max, sb, sh, sp, _ptr(prefix_len),
                                     _ptr(n_nodes), _ptr(parent), scale, num_splits, _ptr(out),
                                     _ptr(lse), _ptr(ws), ws.numel(), _stream()))
+    return (out, lse) if return_lse else out
+
+
+def tree_attention_layers(q, k_prefix, v_prefix, k_tree, v_tree, prefix_len, n_nodes, parent, scale,
+                          num_splits=0, return_lse=False, out=None, workspace=None):
+    """rsd_tree_attention_layers: q [L,B,Hq,N,D]; k_prefix/v_prefix [L,B,Hkv,P,D] (any layer/b/h/row
+    strides, D contiguous) or None; k_tree/v_tree [L,B,Hkv,N,D]; prefix_len, n_nodes [B] and parent
+    [B,N] are shared by the layers.  Returns out [L,B,Hq,N,D] fp32."""
+    dtype = {torch.bfloat16: DTYPE_BF16, torch.float32: DTYPE_F32}[q.dtype]
+    for t in (q, k_tree, v_tree):
+        if not t.is_cuda or t.dtype != q.dtype or not t[0].is_contiguous():
+            raise ValueError("q, k_tree, v_tree: GPU tensors of one dtype, contiguous inside a layer")
+    if k_tree.stride(0) != v_tree.stride(0):
+        raise ValueError("k_tree and v_tree need the same layer stride")
+    _dev(prefix_len, torch.int32)
+    _dev(n_nodes, torch.int32)
+    _dev(parent, torch.int32)
+    L, B, Hq, N, D = q.shape
+    Hkv = k_tree.shape[2]
+    if k_prefix is not None:
+        if k_prefix.dtype != q.dtype or v_prefix.dtype != q.dtype or not k_prefix.is_cuda:
+            raise TypeError("prefix K/V must match q's dtype and device")
+        if k_prefix.stride(4) != 1 or v_prefix.stride() != k_prefix.stride():
+            raise ValueError("prefix K and V need a contiguous last dim and identical strides")
+        P_max = k_prefix.shape[3]
+        sl, sb, sh, sp = k_prefix.stride(0), k_prefix.stride(1), k_prefix.stride(2), k_prefix.stride(3)
+    else:
+        P_max, sl, sb, sh, sp = 0, 0, 0, 0, D
+    dev = q.device
+    if out is None:
+        out = torch.empty((L, B, Hq, N, D), dtype=torch.float32, device=dev)
+    lse = torch.empty((L, B, Hq, N), dtype=torch.float32, device=dev) if return_lse else None
+    nbytes = lib().rsd_tree_attention_layers_workspace_bytes(dtype, L, B, Hq, Hkv, N, D, P_max, num_splits)
+    ws = workspace if workspace is not None else _workspace(nbytes, dev)
+    _check(lib().rsd_tree_attention_layers(_ptr(q), _ptr(k_prefix), _ptr(v_prefix), _ptr(k_tree), _ptr(v_tree),
+                                           dtype, L, q.stride(0), sl, k_tree.stride(0), out.stride(0),
+                                           lse.stride(0) if lse is not None else 0, B, Hq, Hkv, N, D, P_max,
+                                           sb, sh, sp, _ptr(prefix_len), _ptr(n_nodes), _ptr(parent), scale,
+                                           num_splits, _ptr(out), _ptr(lse), _ptr(ws), ws.numel(), _stream()))
     return (out, lse) if return_lse else out
 
 

@@ -43,7 +43,9 @@ constexpr int kAncWords = RSD_NODES_MAX / 64;
 
 struct AttnArgs {
     const void *q, *kp, *vp, *kt, *vt;
-    int B, Hq, Hkv, N, D, P_max;
+    int B, Hq, Hkv, N, D, P_max;   // B: sequences per layer
+    int L;                         // layers in this launch; a "batch index" below counts (layer, sequence) pairs
+    int64_t lq, lp, lt, lo, ll;    // layer strides in elements: q, prefix K/V, tree K/V, out, lse_out
     int64_t sb, sh, sp;  // prefix strides in elements
     const int *plen;
     const int *nn;
@@ -217,8 +219,9 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
 
     int b, kvh, rb, sp;
     decode_block(a, b, kvh, rb, sp);
-    const int n = min(max(a.nn[b], 0), a.N);
-    const int plen = min(max(a.plen[b], 0), a.P_max);
+    const int layer = b / a.B, bs = b - layer * a.B;  // the tree and the prefix length are the sequence's
+    const int n = min(max(a.nn[bs], 0), a.N);
+    const int plen = min(max(a.plen[bs], 0), a.P_max);
     const int G = a.Hq / a.Hkv;
     const int rows = G * n;
     if (a.row_base + rb * kRowsPerBlock >= rows) return;
@@ -232,7 +235,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     const bool qvalid = R < rows;
     const int hq = kvh * G + (qvalid ? R / n : 0);
     const int qi = qvalid ? R % n : 0;
-    const __bf16 *qptr = reinterpret_cast<const __bf16 *>(a.q) + (((int64_t)b * a.Hq + hq) * a.N + qi) * D;
+    const __bf16 *qptr = reinterpret_cast<const __bf16 *>(a.q) + layer * a.lq + (((int64_t)bs * a.Hq + hq) * a.N + qi) * D;
     bf16x8 qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -250,10 +253,10 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     const int npre = t1 - t0;
     const int ntiles = npre + (do_tree ? Tt : 0);
 
-    const __bf16 *kp = reinterpret_cast<const __bf16 *>(a.kp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
-    const __bf16 *vp = reinterpret_cast<const __bf16 *>(a.vp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
-    const __bf16 *kt = reinterpret_cast<const __bf16 *>(a.kt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
-    const __bf16 *vt = reinterpret_cast<const __bf16 *>(a.vt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
+    const __bf16 *kp = reinterpret_cast<const __bf16 *>(a.kp) + layer * a.lp + (int64_t)bs * a.sb + (int64_t)kvh * a.sh;
+    const __bf16 *vp = reinterpret_cast<const __bf16 *>(a.vp) + layer * a.lp + (int64_t)bs * a.sb + (int64_t)kvh * a.sh;
+    const __bf16 *kt = reinterpret_cast<const __bf16 *>(a.kt) + layer * a.lt + ((int64_t)bs * a.Hkv + kvh) * a.N * D;
+    const __bf16 *vt = reinterpret_cast<const __bf16 *>(a.vt) + layer * a.lt + ((int64_t)bs * a.Hkv + kvh) * a.N * D;
 
     auto stage = [&](int u) {  // tile u of this block's schedule into buffer u & 1
         const int buf = u & 1;
@@ -270,7 +273,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
 
     if (ntiles > 0) stage(0);
     // (after the first tile and the query rows have been asked for: one round trip for all three)
-    if (do_tree) build_ancestors(a.par + (int64_t)b * a.N, n, anc, kAttnThreads);
+    if (do_tree) build_ancestors(a.par + (int64_t)bs * a.N, n, anc, kAttnThreads);
     wait_tile_loads<0>();
     __syncthreads();
 
@@ -363,16 +366,17 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     float lt = l + __shfl_xor(l, 16, kWave);
     lt += __shfl_xor(lt, 32, kWave);
     if (!qvalid) return;
-    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + qi;
+    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + qi;       // row of the partial-result workspace
+    const int64_t orow_s = ((int64_t)bs * a.Hq + hq) * a.N + qi;   // row inside the layer
     if (a.splits == 1) {
         const float inv = lt > 0.f ? 1.f / lt : 0.f;
-        float *dst = a.out + orow * D;
+        float *dst = a.out + layer * a.lo + orow_s * D;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt) {
             float4 v = make_float4(o[dt][0] * inv, o[dt][1] * inv, o[dt][2] * inv, o[dt][3] * inv);
             *reinterpret_cast<float4 *>(dst + dt * 16 + g * 4) = v;
         }
-        if (a.lse_out && g == 0) a.lse_out[orow] = (m + log2f(lt)) * kLn2;
+        if (a.lse_out && g == 0) a.lse_out[layer * a.ll + orow_s] = (m + log2f(lt)) * kLn2;
     } else {
         float *dst = a.ws_o + (orow * a.ws_splits + sp) * D;
 #pragma unroll
@@ -425,8 +429,9 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
 
     int b, kvh, rb, sp;
     decode_block(a, b, kvh, rb, sp);
-    const int n = min(max(a.nn[b], 0), a.N);
-    const int plen = min(max(a.plen[b], 0), a.P_max);
+    const int layer = b / a.B, bs = b - layer * a.B;  // the tree and the prefix length are the sequence's
+    const int n = min(max(a.nn[bs], 0), a.N);
+    const int plen = min(max(a.plen[bs], 0), a.P_max);
     const int G = a.Hq / a.Hkv;
     const int rows = G * n;
     if (a.row_base + rb * RPB >= rows) return false;
@@ -440,7 +445,7 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
     const bool wave_active = a.row_base + rb * RPB + wave * 32 < rows;  // wave-uniform
     const int hq = kvh * G + (qvalid ? R / n : 0);
     const int qi = qvalid ? R % n : 0;
-    const __bf16 *qptr = reinterpret_cast<const __bf16 *>(a.q) + (((int64_t)b * a.Hq + hq) * a.N + qi) * D;
+    const __bf16 *qptr = reinterpret_cast<const __bf16 *>(a.q) + layer * a.lq + (((int64_t)bs * a.Hq + hq) * a.N + qi) * D;
     bf16x8 qf[KS];
 #pragma unroll
     for (int ks = 0; ks < KS; ++ks) {
@@ -457,10 +462,10 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
     const int npre = t1 - t0;
     const int ntiles = npre + (do_tree ? Tt : 0);
 
-    const __bf16 *kp = reinterpret_cast<const __bf16 *>(a.kp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
-    const __bf16 *vp = reinterpret_cast<const __bf16 *>(a.vp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
-    const __bf16 *kt = reinterpret_cast<const __bf16 *>(a.kt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
-    const __bf16 *vt = reinterpret_cast<const __bf16 *>(a.vt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
+    const __bf16 *kp = reinterpret_cast<const __bf16 *>(a.kp) + layer * a.lp + (int64_t)bs * a.sb + (int64_t)kvh * a.sh;
+    const __bf16 *vp = reinterpret_cast<const __bf16 *>(a.vp) + layer * a.lp + (int64_t)bs * a.sb + (int64_t)kvh * a.sh;
+    const __bf16 *kt = reinterpret_cast<const __bf16 *>(a.kt) + layer * a.lt + ((int64_t)bs * a.Hkv + kvh) * a.N * D;
+    const __bf16 *vt = reinterpret_cast<const __bf16 *>(a.vt) + layer * a.lt + ((int64_t)bs * a.Hkv + kvh) * a.N * D;
 
     const int wave_s = __builtin_amdgcn_readfirstlane(wave);
     const bool lean_stage = a.sp < (1 << 24);  // per-thread byte offset fits 32 bits
@@ -496,7 +501,7 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
 #pragma unroll
     for (int u = 0; u < STAGES - 1; ++u)
         if (u < ntiles) stage(u);
-    if (do_tree) build_ancestors(a.par + (int64_t)b * a.N, n, anc, THREADS);
+    if (do_tree) build_ancestors(a.par + (int64_t)bs * a.N, n, anc, THREADS);
     if (ntiles > STAGES - 2 && STAGES > 2) {
         if (ntiles > 1) wait_tile_loads<(STAGES - 2) * LOADS>(); else wait_tile_loads<0>();
     } else {
@@ -677,10 +682,11 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
         if (__syncthreads_or(qvalid && !(lt < kRowSumLimit))) return true;  // workgroup-uniform
     }
     if (!qvalid) return false;
-    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + qi;
+    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + qi;       // row of the partial-result workspace
+    const int64_t orow_s = ((int64_t)bs * a.Hq + hq) * a.N + qi;   // row inside the layer
     if (a.splits == 1) {
         const float inv = lt > 0.f ? 1.f / lt : 0.f;
-        float *dst = a.out + orow * D;
+        float *dst = a.out + layer * a.lo + orow_s * D;
 #pragma unroll
         for (int dt = 0; dt < DT; ++dt)
 #pragma unroll
@@ -689,7 +695,7 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
                                              o[dt][4 * rq + 2] * inv, o[dt][4 * rq + 3] * inv);
                 *reinterpret_cast<float4 *>(dst + dt * 32 + 8 * rq + 4 * h) = v;
             }
-        if (a.lse_out && h == 0) a.lse_out[orow] = (m + log2f(lt)) * kLn2;
+        if (a.lse_out && h == 0) a.lse_out[layer * a.ll + orow_s] = (m + log2f(lt)) * kLn2;
     } else {
         float *dst = a.ws_o + (orow * a.ws_splits + sp) * D;
 #pragma unroll
@@ -721,12 +727,14 @@ __global__ __launch_bounds__(WAVES * 64, WAVES == 4 ? 2 : 1) void tree_attn_bf16
 // every (sequence, KV head) pair: one wave per row, `splits` partial results each.
 __global__ __launch_bounds__(kWave) void tree_attn_merge_kernel(AttnArgs a) {
     const int R = a.row_base + blockIdx.x, kvh = blockIdx.y, b = blockIdx.z;
-    const int n = min(max(a.nn[b], 0), a.N);
+    const int layer = b / a.B, bs = b - layer * a.B;
+    const int n = min(max(a.nn[bs], 0), a.N);
     const int G = a.Hq / a.Hkv;
     if (R >= G * n) return;
     const int hq = kvh * G + R / n, i = R % n;
     const int splits = a.splits;  // at most 32: lane s holds split s
-    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + i;
+    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + i;       // row of the partial-result workspace
+    const int64_t orow_s = ((int64_t)bs * a.Hq + hq) * a.N + i;   // row inside the layer
     const int lane = threadIdx.x;
     const float wm = lane < splits ? a.ws_m[orow * a.ws_splits + lane] : -INFINITY;
     const float wl = lane < splits ? a.ws_l[orow * a.ws_splits + lane] : 0.f;
@@ -755,10 +763,10 @@ __global__ __launch_bounds__(kWave) void tree_attn_merge_kernel(AttnArgs a) {
         for (int s = 0; s < kEarly; ++s) acc += read_lane(w, s) * early[s][c];  // (w = 0 beyond the last split)
         if (d < a.D) {
             for (int s = kEarly; s < splits; ++s) acc += __shfl(w, s, kWave) * po[(int64_t)s * a.D + d];
-            a.out[orow * a.D + d] = acc * inv;
+            a.out[layer * a.lo + orow_s * a.D + d] = acc * inv;
         }
     }
-    if (a.lse_out && lane == 0) a.lse_out[orow] = (m + log2f(lsum)) * kLn2;
+    if (a.lse_out && lane == 0) a.lse_out[layer * a.ll + orow_s] = (m + log2f(lsum)) * kLn2;
 }
 
 // fp32 inputs (small configurations): one wave per query row, plain ALUs.
@@ -767,9 +775,10 @@ __global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnArgs a) {
     __shared__ float s_p[kWave];
     __shared__ float s_q[256];
     const int i = blockIdx.x, hq = blockIdx.y, b = blockIdx.z;
-    const int n = min(max(a.nn[b], 0), a.N);
+    const int layer = b / a.B, bs = b - layer * a.B;
+    const int n = min(max(a.nn[bs], 0), a.N);
     if (i >= n) return;
-    const int plen = min(max(a.plen[b], 0), a.P_max);
+    const int plen = min(max(a.plen[bs], 0), a.P_max);
     const int lane = threadIdx.x;
     const int D = a.D;
     const int kvh = hq / (a.Hq / a.Hkv);
@@ -777,7 +786,7 @@ __global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnArgs a) {
         uint64_t w[kAncWords];
         for (int k = 0; k < kAncWords; ++k) w[k] = 0;
         int j = i;
-        const int *par = a.par + (int64_t)b * a.N;
+        const int *par = a.par + (int64_t)bs * a.N;
         for (int guard = 0; guard <= n; ++guard) {
             w[j >> 6] |= 1ull << (j & 63);
             if (j <= 0) break;
@@ -785,13 +794,13 @@ __global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnArgs a) {
         }
         for (int k = 0; k < kAncWords; ++k) s_anc[k] = w[k];
     }
-    const float *q = reinterpret_cast<const float *>(a.q) + (((int64_t)b * a.Hq + hq) * a.N + i) * D;
+    const float *q = reinterpret_cast<const float *>(a.q) + layer * a.lq + (((int64_t)bs * a.Hq + hq) * a.N + i) * D;
     for (int d = lane; d < D; d += kWave) s_q[d] = q[d];
     __syncthreads();
-    const float *kp = reinterpret_cast<const float *>(a.kp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
-    const float *vp = reinterpret_cast<const float *>(a.vp) + (int64_t)b * a.sb + (int64_t)kvh * a.sh;
-    const float *kt = reinterpret_cast<const float *>(a.kt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
-    const float *vt = reinterpret_cast<const float *>(a.vt) + ((int64_t)b * a.Hkv + kvh) * a.N * D;
+    const float *kp = reinterpret_cast<const float *>(a.kp) + layer * a.lp + (int64_t)bs * a.sb + (int64_t)kvh * a.sh;
+    const float *vp = reinterpret_cast<const float *>(a.vp) + layer * a.lp + (int64_t)bs * a.sb + (int64_t)kvh * a.sh;
+    const float *kt = reinterpret_cast<const float *>(a.kt) + layer * a.lt + ((int64_t)bs * a.Hkv + kvh) * a.N * D;
+    const float *vt = reinterpret_cast<const float *>(a.vt) + layer * a.lt + ((int64_t)bs * a.Hkv + kvh) * a.N * D;
     float m = -INFINITY, l = 0.f;
     float acc[4] = {0.f, 0.f, 0.f, 0.f};  // output dims lane, lane+64, lane+128, lane+192
     const int total = plen + n;
@@ -835,14 +844,15 @@ __global__ __launch_bounds__(kWave) void tree_attn_f32_kernel(AttnArgs a) {
             }
         }
     }
-    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + i;
+    const int64_t orow = ((int64_t)b * a.Hq + hq) * a.N + i;       // row of the partial-result workspace
+    const int64_t orow_s = ((int64_t)bs * a.Hq + hq) * a.N + i;   // row inside the layer
     const float inv = l > 0.f ? 1.f / l : 0.f;
 #pragma unroll
     for (int k = 0; k < 4; ++k) {
         const int d = lane + k * kWave;
-        if (d < D) a.out[orow * D + d] = acc[k] * inv;
+        if (d < D) a.out[layer * a.lo + orow_s * D + d] = acc[k] * inv;
     }
-    if (a.lse_out && lane == 0) a.lse_out[orow] = (m + log2f(l)) * kLn2;
+    if (a.lse_out && lane == 0) a.lse_out[layer * a.ll + orow_s] = (m + log2f(l)) * kLn2;
 }
 
 static size_t align_up(size_t x, size_t al) { return (x + al - 1) / al * al; }
@@ -929,33 +939,31 @@ static size_t attn_smem_bytes(int N, int stages) {
     return (size_t)stages * 2 * kTile * D * 2 + (size_t)N * kAncWords * 8;
 }
 
+// The dynamic-LDS limit of a kernel covers the largest tree; setting it is idempotent and cheap,
+// so it is simply set at every launch (no state is kept between calls).
 template <typename Kernel>
-static hipError_t launch_attn(Kernel kernel, bool &attr_set, size_t smem_max, size_t smem, dim3 grid,
-                              int threads, hipStream_t st, const AttnArgs &a) {
-    if (!attr_set) {  // the limit covers the largest tree, set once per kernel
-        const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
-                                                   hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_max);
-        if (err != hipSuccess) return err;
-        attr_set = true;
-    }
+static hipError_t launch_attn(Kernel kernel, size_t smem_max, size_t smem, dim3 grid, int threads,
+                              hipStream_t st, const AttnArgs &a) {
+    const hipError_t err = hipFuncSetAttribute(reinterpret_cast<const void *>(kernel),
+                                               hipFuncAttributeMaxDynamicSharedMemorySize, (int)smem_max);
+    if (err != hipSuccess) return err;
     hipLaunchKernelGGL(kernel, grid, dim3(threads), smem, st, a);
     return hipGetLastError();
 }
 
 template <int D>
-static hipError_t launch_segment(const AttnSegment &sg, AttnArgs a, hipStream_t st) {
-    static bool set16 = false, set4 = false, set8 = false;
+static hipError_t launch_segment(const AttnSegment &sg, AttnArgs a, int pairs, hipStream_t st) {
     a.row_base = sg.row_base;
     a.row_blocks = sg.row_blocks;
     a.splits = sg.splits;
-    const dim3 grid((unsigned)((long)sg.row_blocks * a.splits * a.Hkv * a.B));
+    const dim3 grid((unsigned)((long)sg.row_blocks * a.splits * a.Hkv * pairs));
     if (sg.variant == kV32x8)
-        return launch_attn(tree_attn_bf16_w32_kernel<D, 8, 2>, set8, attn_smem_bytes<D>(RSD_NODES_MAX, 2),
+        return launch_attn(tree_attn_bf16_w32_kernel<D, 8, 2>, attn_smem_bytes<D>(RSD_NODES_MAX, 2),
                            attn_smem_bytes<D>(a.N, 2), grid, 512, st, a);
     if (sg.variant == kV32x4)
-        return launch_attn(tree_attn_bf16_w32_kernel<D, 4, 2>, set4, attn_smem_bytes<D>(RSD_NODES_MAX, 2),
+        return launch_attn(tree_attn_bf16_w32_kernel<D, 4, 2>, attn_smem_bytes<D>(RSD_NODES_MAX, 2),
                            attn_smem_bytes<D>(a.N, 2), grid, 256, st, a);
-    return launch_attn(tree_attn_bf16_kernel<D>, set16, attn_smem_bytes<D>(RSD_NODES_MAX, 2),
+    return launch_attn(tree_attn_bf16_kernel<D>, attn_smem_bytes<D>(RSD_NODES_MAX, 2),
                        attn_smem_bytes<D>(a.N, 2), grid, kAttnThreads, st, a);
 }
 
@@ -963,29 +971,31 @@ static hipError_t launch_segment(const AttnSegment &sg, AttnArgs a, hipStream_t 
 
 using namespace rsd;
 
-extern "C" size_t rsd_tree_attention_workspace_bytes(int32_t dtype, int32_t B, int32_t H_q,
-                                                     int32_t H_kv, int32_t N_max, int32_t D,
-                                                     int32_t P_max, int32_t num_splits) {
-    if (B <= 0 || H_q <= 0 || H_kv <= 0 || N_max <= 0 || D <= 0 || P_max < 0 || H_q % H_kv) return 0;
-    const int s = max_splits(dtype, B, H_q, H_kv, N_max, P_max, num_splits);
+// Shared by the two entry points: L layers of B sequences each in one set of launches.  The
+// launch plan (row blocks, prefix splits) is made for all L * B (layer, sequence) pairs, so a
+// small batch that could not fill the chip in one layer does so over its layers.
+static size_t attn_workspace_bytes(int32_t dtype, int32_t L, int32_t B, int32_t H_q, int32_t H_kv,
+                                   int32_t N_max, int32_t D, int32_t P_max, int32_t num_splits) {
+    if (L <= 0 || B <= 0 || H_q <= 0 || H_kv <= 0 || N_max <= 0 || D <= 0 || P_max < 0 || H_q % H_kv) return 0;
+    if ((int64_t)L * B > 65535) return 0;
+    const int s = max_splits(dtype, L * B, H_q, H_kv, N_max, P_max, num_splits);
     if (s <= 1) return 0;
-    const size_t rows = (size_t)B * H_q * N_max;
+    const size_t rows = (size_t)L * B * H_q * N_max;
     return align_up(rows * s * D * 4, 256) + 2 * align_up(rows * s * 4, 256);
 }
 
-extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const void *v_prefix,
-                                      const void *k_tree, const void *v_tree, int32_t dtype,
-                                      int32_t B, int32_t H_q, int32_t H_kv, int32_t N_max, int32_t D,
-                                      int32_t P_max, int64_t prefix_stride_b,
-                                      int64_t prefix_stride_h, int64_t prefix_stride_p,
-                                      const int32_t *prefix_len, const int32_t *n_nodes,
-                                      const int32_t *parent, float scale, int32_t num_splits,
-                                      float *out, float *lse_out, void *workspace,
-                                      size_t workspace_bytes, void *stream) {
+static int32_t attn_launch(const void *q, const void *k_prefix, const void *v_prefix, const void *k_tree,
+                           const void *v_tree, int32_t dtype, int32_t L, int64_t q_stride_l,
+                           int64_t prefix_stride_l, int64_t tree_stride_l, int64_t out_stride_l,
+                           int64_t lse_stride_l, int32_t B, int32_t H_q, int32_t H_kv, int32_t N_max,
+                           int32_t D, int32_t P_max, int64_t prefix_stride_b, int64_t prefix_stride_h,
+                           int64_t prefix_stride_p, const int32_t *prefix_len, const int32_t *n_nodes,
+                           const int32_t *parent, float scale, int32_t num_splits, float *out,
+                           float *lse_out, void *workspace, size_t workspace_bytes, void *stream) {
     if (!q || !k_tree || !v_tree || !prefix_len || !n_nodes || !parent || !out) return RSD_ERR_NULL;
     if (P_max > 0 && (!k_prefix || !v_prefix)) return RSD_ERR_NULL;
-    if (B < 0 || H_q < 1 || H_kv < 1 || H_q % H_kv || N_max < 1 || N_max > RSD_NODES_MAX ||
-        P_max < 0 || num_splits < 0)
+    if (B < 0 || L < 1 || H_q < 1 || H_kv < 1 || H_q % H_kv || N_max < 1 || N_max > RSD_NODES_MAX ||
+        P_max < 0 || num_splits < 0 || (int64_t)L * B > 65535)
         return RSD_ERR_SHAPE;
     if (dtype != RSD_DTYPE_BF16 && dtype != RSD_DTYPE_F32) return RSD_ERR_UNSUPPORTED;
     const int esz = dtype == RSD_DTYPE_BF16 ? 2 : 4;
@@ -999,31 +1009,36 @@ extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const
         (prefix_stride_b % vec || prefix_stride_h % vec || prefix_stride_p % vec || prefix_stride_p < D))
         return RSD_ERR_SHAPE;
     if (P_max > 0 && dtype == RSD_DTYPE_F32 && prefix_stride_p < D) return RSD_ERR_SHAPE;
+    if (L > 1 && (q_stride_l % vec || prefix_stride_l % vec || tree_stride_l % vec || out_stride_l % 4 ||
+                  q_stride_l < 0 || prefix_stride_l < 0 || tree_stride_l < 0 || out_stride_l < 0 || lse_stride_l < 0))
+        return RSD_ERR_SHAPE;
     if (B == 0) return RSD_OK;
 
     AttnArgs a{};
     a.q = q; a.kp = k_prefix; a.vp = v_prefix; a.kt = k_tree; a.vt = v_tree;
-    a.B = B; a.Hq = H_q; a.Hkv = H_kv; a.N = N_max; a.D = D; a.P_max = P_max;
+    a.B = B; a.L = L; a.Hq = H_q; a.Hkv = H_kv; a.N = N_max; a.D = D; a.P_max = P_max;
+    a.lq = q_stride_l; a.lp = prefix_stride_l; a.lt = tree_stride_l; a.lo = out_stride_l; a.ll = lse_stride_l;
     a.sb = prefix_stride_b; a.sh = prefix_stride_h; a.sp = prefix_stride_p;
     a.plen = prefix_len; a.nn = n_nodes; a.par = parent;
     a.scale_log2 = (float)((double)scale * 1.4426950408889634);
     a.out = out; a.lse_out = lse_out;
     hipStream_t st = (hipStream_t)stream;
+    const int BL = B * L;  // (layer, sequence) pairs: the kernels' batch index
 
     if (dtype == RSD_DTYPE_F32) {
         a.splits = 1;
-        hipLaunchKernelGGL(tree_attn_f32_kernel, dim3(N_max, H_q, B), dim3(kWave), 0, st, a);
+        hipLaunchKernelGGL(tree_attn_f32_kernel, dim3(N_max, H_q, BL), dim3(kWave), 0, st, a);
         return hipGetLastError() == hipSuccess ? RSD_OK : RSD_ERR_LAUNCH;
     }
 
     AttnSegment seg[kMaxSegments];
-    const int nseg = plan_segments(dtype, B, H_q, H_kv, N_max, P_max, num_splits, seg);
+    const int nseg = plan_segments(dtype, BL, H_q, H_kv, N_max, P_max, num_splits, seg);
     a.ws_splits = 1;
     for (int i = 0; i < nseg; ++i) a.ws_splits = seg[i].splits > a.ws_splits ? seg[i].splits : a.ws_splits;
     if (a.ws_splits > 1) {
-        const size_t need = rsd_tree_attention_workspace_bytes(dtype, B, H_q, H_kv, N_max, D, P_max, num_splits);
+        const size_t need = attn_workspace_bytes(dtype, L, B, H_q, H_kv, N_max, D, P_max, num_splits);
         if (!workspace || workspace_bytes < need || !aligned16(workspace)) return RSD_ERR_WORKSPACE;
-        const size_t rows = (size_t)B * H_q * N_max;
+        const size_t rows = (size_t)BL * H_q * N_max;
         char *ws = static_cast<char *>(workspace);
         a.ws_o = reinterpret_cast<float *>(ws);
         a.ws_m = reinterpret_cast<float *>(ws + align_up(rows * a.ws_splits * D * 4, 256));
@@ -1031,7 +1046,7 @@ extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const
                                            align_up(rows * a.ws_splits * 4, 256));
     }
     for (int i = 0; i < nseg; ++i) {
-        const hipError_t err = D == 128 ? launch_segment<128>(seg[i], a, st) : launch_segment<64>(seg[i], a, st);
+        const hipError_t err = D == 128 ? launch_segment<128>(seg[i], a, BL, st) : launch_segment<64>(seg[i], a, BL, st);
         if (err != hipSuccess) return RSD_ERR_LAUNCH;
     }
     const int rows_max = (H_q / H_kv) * N_max;
@@ -1040,8 +1055,51 @@ extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const
         const int row_end = (i + 1 < nseg) ? seg[i + 1].row_base : rows_max;
         a.row_base = seg[i].row_base;
         a.splits = seg[i].splits;
-        hipLaunchKernelGGL(tree_attn_merge_kernel, dim3(row_end - seg[i].row_base, H_kv, B), dim3(kWave), 0, st, a);
+        hipLaunchKernelGGL(tree_attn_merge_kernel, dim3(row_end - seg[i].row_base, H_kv, BL), dim3(kWave), 0, st, a);
         if (hipGetLastError() != hipSuccess) return RSD_ERR_LAUNCH;
     }
     return RSD_OK;
+}
+
+extern "C" size_t rsd_tree_attention_workspace_bytes(int32_t dtype, int32_t B, int32_t H_q,
+                                                     int32_t H_kv, int32_t N_max, int32_t D,
+                                                     int32_t P_max, int32_t num_splits) {
+    return attn_workspace_bytes(dtype, 1, B, H_q, H_kv, N_max, D, P_max, num_splits);
+}
+
+extern "C" int32_t rsd_tree_attention(const void *q, const void *k_prefix, const void *v_prefix,
+                                      const void *k_tree, const void *v_tree, int32_t dtype,
+                                      int32_t B, int32_t H_q, int32_t H_kv, int32_t N_max, int32_t D,
+                                      int32_t P_max, int64_t prefix_stride_b,
+                                      int64_t prefix_stride_h, int64_t prefix_stride_p,
+                                      const int32_t *prefix_len, const int32_t *n_nodes,
+                                      const int32_t *parent, float scale, int32_t num_splits,
+                                      float *out, float *lse_out, void *workspace,
+                                      size_t workspace_bytes, void *stream) {
+    return attn_launch(q, k_prefix, v_prefix, k_tree, v_tree, dtype, 1, 0, 0, 0, 0, 0, B, H_q, H_kv, N_max, D,
+                       P_max, prefix_stride_b, prefix_stride_h, prefix_stride_p, prefix_len, n_nodes, parent,
+                       scale, num_splits, out, lse_out, workspace, workspace_bytes, stream);
+}
+
+extern "C" size_t rsd_tree_attention_layers_workspace_bytes(int32_t dtype, int32_t L, int32_t B,
+                                                            int32_t H_q, int32_t H_kv, int32_t N_max,
+                                                            int32_t D, int32_t P_max, int32_t num_splits) {
+    return attn_workspace_bytes(dtype, L, B, H_q, H_kv, N_max, D, P_max, num_splits);
+}
+
+extern "C" int32_t rsd_tree_attention_layers(const void *q, const void *k_prefix, const void *v_prefix,
+                                             const void *k_tree, const void *v_tree, int32_t dtype,
+                                             int32_t L, int64_t q_stride_l, int64_t prefix_stride_l,
+                                             int64_t tree_stride_l, int64_t out_stride_l,
+                                             int64_t lse_stride_l, int32_t B, int32_t H_q, int32_t H_kv,
+                                             int32_t N_max, int32_t D, int32_t P_max,
+                                             int64_t prefix_stride_b, int64_t prefix_stride_h,
+                                             int64_t prefix_stride_p, const int32_t *prefix_len,
+                                             const int32_t *n_nodes, const int32_t *parent, float scale,
+                                             int32_t num_splits, float *out, float *lse_out,
+                                             void *workspace, size_t workspace_bytes, void *stream) {
+    return attn_launch(q, k_prefix, v_prefix, k_tree, v_tree, dtype, L, q_stride_l, prefix_stride_l,
+                       tree_stride_l, out_stride_l, lse_stride_l, B, H_q, H_kv, N_max, D, P_max,
+                       prefix_stride_b, prefix_stride_h, prefix_stride_p, prefix_len, n_nodes, parent, scale,
+                       num_splits, out, lse_out, workspace, workspace_bytes, stream);
 }

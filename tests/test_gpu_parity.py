@@ -269,6 +269,52 @@ def test_tree_attention_bf16(B, Hq, Hkv, N, D, P, splits, n_nodes, plens):
     assert err < 1e-2
 
 
+@pytest.mark.parametrize("L,B,Hq,Hkv,N,D,P,dtype,splits", [
+    (5, 1, 4, 4, 34, 128, 300, "bf16", 0),     # config-1-like: one sequence, layers fill the launch
+    (3, 2, 8, 1, 65, 128, 200, "bf16", 0),     # stacked heads: 32-row kernel plus remainder rows
+    (2, 2, 4, 2, 20, 64, 130, "bf16", 3),      # forced prefix splits: partial results per (layer, sequence)
+    (3, 2, 2, 1, 7, 48, 40, "f32", 0),         # fp32 kernel
+])
+def test_tree_attention_layers_equals_per_layer_oracle(L, B, Hq, Hkv, N, D, P, dtype, splits):
+    """One call over L layers that share the tree: every layer's output against the oracle called on
+    that layer alone, with ragged trees / prefixes and layer tensors that are strided views."""
+    say(f"attention over {L} layers B={B} Hq={Hq} Hkv={Hkv} N={N} D={D} P={P} {dtype} splits={splits}")
+    rng = np.random.default_rng(L * 100 + N)
+    d = dev()
+    cap = P + 8                                        # prefix cache with spare rows: strided layers
+    parts = [workloads.make_qkv(B, Hq, Hkv, N, D, cap, dtype, 50 + l) for l in range(L)]
+    q, kp, vp, kt, vt = (torch.stack([p[i] for p in parts]) for i in range(5))
+    n_nodes = rng.integers(1, N + 1, size=B).astype(np.int32); n_nodes[0] = N
+    plens = rng.integers(0, P + 1, size=B).astype(np.int32); plens[0] = P
+    parent = np.stack([_random_tree(rng, N) for _ in range(B)])
+    scale = workloads.attention_scale(D)
+    out, lse = binding.tree_attention_layers(q.to(d), kp.to(d)[:, :, :, :P], vp.to(d)[:, :, :, :P], kt.to(d),
+                                             vt.to(d), torch.from_numpy(plens).to(d),
+                                             torch.from_numpy(n_nodes).to(d), torch.from_numpy(parent).to(d),
+                                             scale, num_splits=splits, return_lse=True)
+    out, lse = to_np(out), to_np(lse)
+    f = lambda t: t.to(torch.float32).numpy()
+    tol, ltol = (1e-2, 2e-2) if dtype == "bf16" else (1e-4, 1e-4)
+    worst = 0.0
+    for l in range(L):
+        ref, ref_lse = o_attn.tree_attention(f(q[l]), f(kp[l][:, :, :P]), f(vp[l][:, :, :P]), f(kt[l]), f(vt[l]),
+                                             plens, n_nodes, parent, scale)
+        for b in range(B):
+            n = int(n_nodes[b])
+            worst = max(worst, float(np.abs(out[l, b, :, :n] - ref[b, :, :n]).max()))
+            assert np.allclose(lse[l, b, :, :n], ref_lse[b, :, :n], rtol=0, atol=ltol)
+    say(f"  max abs err {worst:.2e}")
+    assert worst < tol
+    # the single-layer call on layer 1 gives the same numbers when the launch plan is the same (forced splits)
+    if splits:
+        one = binding.tree_attention(q[1].to(d), kp[1].to(d)[:, :, :P], vp[1].to(d)[:, :, :P], kt[1].to(d), vt[1].to(d),
+                                     torch.from_numpy(plens).to(d), torch.from_numpy(n_nodes).to(d),
+                                     torch.from_numpy(parent).to(d), scale, num_splits=splits)
+        for b in range(B):
+            n = int(n_nodes[b])
+            assert np.array_equal(to_np(one)[b, :, :n], out[1, b, :, :n])
+
+
 def test_tree_attention_one_key_prefix_wide_rows():
     """A one-key prefix under 272 stacked rows: few visible keys per row, so single keys dominate, and the
     fixed softmax reference of the 32-row kernel (taken from the first tile, here that one key) makes the
