@@ -39,10 +39,10 @@ constexpr int kStreamThreads = 512;  // streaming variant (any vocabulary size)
 // Resident variants <threads, float4 chunks per thread, of which in LDS>:
 //  up to 8192 entries:   256 threads, 8 chunks in registers (small vocabularies)
 //  up to 32768 entries:  512 threads, both rows in registers (2 x 64 per thread)
-//  up to 52224 entries:  768 threads, 12 of 17 draft chunks in LDS (144 KB), one workgroup per CU
+//  up to 51200 entries:  512 threads, 18 of the 25 draft chunks in LDS (144 KB)
 constexpr int kSmallThreads = 256, kSmallChunks = 8;
 constexpr int kRegThreads = 512, kRegChunks = 16, kRegChunksInLds = 0;
-constexpr int kLdsThreads = 768, kLdsChunks = 17, kLdsChunksInLds = 12;
+constexpr int kLdsThreads = 512, kLdsChunks = 25, kLdsChunksInLds = 18;
 constexpr int kGroupWavesMax = 16;
 constexpr int kFinalThreads = 512;
 constexpr int kFinalSplitsMax = 8;
@@ -196,6 +196,7 @@ struct GroupShared {
     float czt[RSD_K_MAX];   // raw target / draft logits of the child tokens
     float czd[RSD_K_MAX];
     double ce[RSD_K_MAX];   // draft exponentials of the child tokens (fp64)
+    double th[RSD_K_MAX][4];  // per child: u, A, s, e_d at its own stage
     double sred[2][kGroupWavesMax];  // stage sums, alternating
     unsigned long long cmask[RSD_NODES_MAX / kWave];  // per-wave ballots of the child scan
     int cur;
@@ -613,14 +614,14 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
         if (!(St > 0.0) || !isfinite(St) || !(s0 > 0.0) || !isfinite(s0)) sh.g.flags |= RSD_FLAG_NONFINITE;
     }
     double A = St;  // q^(k) = u / A
+#pragma unroll 1
     for (int k = 0; k < K; ++k) {
         // draft mass still available at stage k: the rest plus the children not yet removed
         double s_k = Sd;
         for (int i = K - 1; i >= k; --i) s_k += sh.ce[i];
         const double gam = A / s_k;
-        if (tid == k) {  // threshold of child k (Eq. (3))
-            const double p = tE / s_k;
-            sh.g.theta[k] = (p > 0.0) ? (float)fmin(1.0, tU / (A * p)) : 1.f;
+        if (tid == k) {  // what child k's threshold needs, divided once after the loop
+            sh.th[k][0] = tU; sh.th[k][1] = A; sh.th[k][2] = s_k; sh.th[k][3] = tE;
         }
         if (k == K - 1) {
             if (tid == 0) sh.g.gam[k] = gam;
@@ -637,7 +638,7 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
                 part += fmaxf(fmaf(-gh, d.y, ut[4 * j + 1]), 0.f);
                 part += fmaxf(fmaf(-gh, d.z, ut[4 * j + 2]), 0.f);
                 part += fmaxf(fmaf(-gh, d.w, ut[4 * j + 3]), 0.f);
-                if (j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
+                if (CL > 0 && j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
             }
         } else {
 #pragma unroll
@@ -647,7 +648,7 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
                 part += fmaxf(fmaf(-gl, d.y, fmaf(-gh, d.y, ut[4 * j + 1])), 0.f);
                 part += fmaxf(fmaf(-gl, d.z, fmaf(-gh, d.z, ut[4 * j + 2])), 0.f);
                 part += fmaxf(fmaf(-gl, d.w, fmaf(-gh, d.w, ut[4 * j + 3])), 0.f);
-                if (j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
+                if (CL > 0 && j % 3 == 2) __builtin_amdgcn_sched_barrier(0);
             }
         }
         const double cnew = fmax(tU - gam * tE, 0.0);
@@ -672,7 +673,7 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
                 ut[4 * j + 1] = fmaxf(fmaf(-ul, d.y, fmaf(-uh, d.y, ut[4 * j + 1])), 0.f);
                 ut[4 * j + 2] = fmaxf(fmaf(-ul, d.z, fmaf(-uh, d.z, ut[4 * j + 2])), 0.f);
                 ut[4 * j + 3] = fmaxf(fmaf(-ul, d.w, fmaf(-uh, d.w, ut[4 * j + 3])), 0.f);
-                if (j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
+                if (CL > 0 && j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
             }
         }
         if (ok) {
@@ -685,6 +686,10 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
         }
         // x_k leaves the draft distribution either way
         if (tid == k) tE = 0.0;
+    }
+    if (tid < K) {  // threshold of child `tid` (Eq. (3)): (u / A) / (e_d / s); the lane's own values
+        const double p = sh.th[tid][3] / sh.th[tid][2];
+        sh.g.theta[tid] = (p > 0.0) ? (float)fmin(1.0, sh.th[tid][0] / (sh.th[tid][1] * p)) : 1.f;
     }
     __syncthreads();
 }
@@ -951,23 +956,25 @@ template <int THREADS, int CH, int CL>
 __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
     const int count = a.wq[0];
-    if (threadIdx.x == 0) {
-        const int first = atomicAdd(&a.wq[1], 1);
-        sh.next_idx = first;
-        sh.next_ent = a.work[min(first, max(count - 1, 0))];
-    }
-    __syncthreads();
-    int idx = sh.next_idx;
-    int2 ent = sh.next_ent;
-    __syncthreads();
+    const int G = gridDim.x;
+    // The first item of a workgroup is its own number; further ones come off the counter (which
+    // starts at zero and counts the items after the first G).  The number of the item after the
+    // next is asked for, and the entry of the next item read, while the current item is
+    // verified: no round trip is waited for inside the loop.
+    int lane_zero = 0;
+    asm volatile("" : "+v"(lane_zero));
+    int idx = blockIdx.x;
+    int2 ent = make_int2(0, 1);
+    if (idx < count) ent = a.work[idx + lane_zero];
+    int idx1 = 0;  // (thread 0) the next item
+    if (threadIdx.x == 0) idx1 = G + atomicAdd(&a.wq[1], 1);
     while (idx < count) {
-        const int i = ent.x, n = ent.y;
-        // (thread 0 only; the two dependent round trips complete under this group's row loads)
-        int nidx = 0;
+        const int i = __builtin_amdgcn_readfirstlane(ent.x), n = __builtin_amdgcn_readfirstlane(ent.y);
+        int idx2 = 0;
         int2 nent = make_int2(0, 1);
         if (threadIdx.x == 0) {
-            nidx = atomicAdd(&a.wq[1], 1);
-            nent = a.work[min(nidx, count - 1)];
+            nent = a.work[min(idx1, count - 1)];
+            idx2 = G + atomicAdd(&a.wq[1], 1);
         }
         const int b = i / a.N, node = i - b * a.N;
         verify_group<THREADS, CH, CL>(a, b, node, n, sh);
@@ -979,8 +986,9 @@ __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
         if (a.theta && (int)threadIdx.x < sh.g.K)
             a.theta[(int64_t)b * a.N + sh.g.kid[threadIdx.x]] = sh.g.theta[threadIdx.x];
         if (threadIdx.x == 0) {
-            sh.next_idx = nidx;
+            sh.next_idx = idx1;
             sh.next_ent = nent;
+            idx1 = idx2;
         }
         __syncthreads();
         idx = sh.next_idx;

@@ -774,6 +774,42 @@ def test_recursive_reject_at_the_limits(mode):
     assert max(ref["n_accepted"]) >= 8
 
 
+def test_recursive_reject_many_nodes_plan_in_global_memory():
+    """B * N_max above 8192: the planning kernel keeps its child counts in global memory instead of LDS.
+    40 sequences of up to 256 nodes (random trees of ragged size), small vocabulary, ALL_GROUPS."""
+    say("rrs with B * N_max = 10240 (> 8192 nodes)")
+    d = dev()
+    B, N, V = 40, 256, 256
+    rng = np.random.default_rng(77)
+    zt, zd = workloads.make_logits("normal", B, N, V, seed=77)
+    n_nodes = rng.integers(2, N + 1, size=B).astype(np.int32)
+    n_nodes[0] = N
+    parent = np.stack([_random_tree(rng, N, max_children=3) for _ in range(B)])
+    tokens = np.zeros((B, N), dtype=np.int32)
+    for b in range(B):                       # siblings carry distinct tokens (drawn without replacement)
+        for node in range(N):
+            kids = np.nonzero(parent[b] == node)[0]
+            tokens[b, kids] = rng.choice(V, size=len(kids), replace=False)
+    g = binding.recursive_reject(zd.to(d), zt.to(d), torch.from_numpy(tokens).to(d), torch.from_numpy(parent).to(d),
+                                 torch.from_numpy(n_nodes).to(d), mode=binding.MODE_ALL_GROUPS, seed=5, step=1)
+    ref = o_rrs.recursive_reject(zt.numpy(), zd.numpy(), tokens, parent, n_nodes, mode=o_rrs.MODE_ALL_GROUPS,
+                                 seed=5, step=1)
+    th_g, th_r = to_np(g["theta"]).astype(np.float64), ref["theta"]
+    both = np.isfinite(th_r)
+    assert np.array_equal(np.isfinite(th_g), both)       # NaN everywhere else (root, padding, unverified)
+    assert np.allclose(th_g[both], th_r[both], rtol=1e-5, atol=1e-6)
+    near = 0
+    for b in range(B):
+        if ref["near_tie"][b] or ref["last_gap"][b] < NEAR_TIE:
+            near += 1
+            continue
+        k = int(ref["n_accepted"][b])
+        assert int(g["n_accepted"][b]) == k
+        assert np.array_equal(to_np(g["accepted_nodes"])[b, :k], ref["accepted_nodes"][b, :k])
+        assert int(g["last_token"][b]) == int(ref["last_token"][b])
+    assert near <= 2
+
+
 def test_tree_attention_largest_tree():
     say("attention bf16 with 256 nodes (four ancestor words, four tree tiles)")
     err = _attention_case(1, 2, 1, 256, 128, 70, "bf16", 5, n_nodes=[256], plens=[70])
