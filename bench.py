@@ -53,10 +53,11 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0  # MI355X dense bf16 MFMA, published
 # plain vector ALU: 256 CUs x 4 SIMDs x 16 lanes x 2.4 GHz lane-instructions per second (half the
 # published 157.3 TFLOP/s fp32 vector figure counts an FMA as two flops and packs two per lane)
 VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
-# vector instructions the tokens-only Gumbel-Top-k kernel issues per vocabulary entry (rocprofv3
-# SQ_INSTS_VALU x 64 lanes / entries on the stress configuration); a fifth of them are quarter-rate
-# 64-bit multiplies of the Philox rounds and hardware logs, so the pipeline is busier than this fraction
-GUMBEL_VALU_PER_ENTRY = 27.3
+# vector instructions the tokens-only Gumbel-Top-k kernel issues per vocabulary entry: rocprofv3
+# SQ_INSTS_VALU x 64 lanes / entries over the three level launches of the stress configuration
+# (profiles/cfg4_stress_gumbel_topk_counters.md, which also gives the measured busy fraction of the
+# vector ALUs, SQ_ACTIVE_INST_VALU against SQ_BUSY_CYCLES: the rate the pipeline really runs at)
+GUMBEL_VALU_PER_ENTRY = 31.2
 N_LAYERS = {"cfg1_llama2_7b": 32, "cfg2_opt_13b_sbs": 40, "cfg3_llama2_70b_gqa": 80, "cfg4_stress": 32}
 # draft size / target size of the model pairs the shapes stand for (App. C: a 115M drafter for the
 # Llama 2 targets, OPT-125M for OPT-13B): the relative draft cost r of the memory-bound speed-up
@@ -446,6 +447,40 @@ def filter_kv_pass(case, torch, binding, steps=20):
     return out
 
 
+def acceptance_pass(case, torch, binding, trials=8):
+    """Acceptance of one level of K drafts at the root of every sequence, method against method on the
+    same synthetic logit rows (the comparison of the paper's toy example and first experiment, here on
+    a recipe instead of a trained model pair): recursive rejection sampling on K drafts drawn without
+    replacement, against K-SEQ (gamma = K) and multi-round rejection sampling on K i.i.d. drafts."""
+    cfg = case["cfg"]
+    K = cfg["branching"][0] if cfg["sampler"] == "gumbel" else cfg["width"]
+    zt, zd = case["zt"][:, 0].contiguous(), case["zd"][:, 0].contiguous()
+    B, V = zt.shape
+    dev = zt.device
+    rows3 = lambda t: torch.stack([t] + [t] * K, dim=1).contiguous()      # [B, K + 1, V]: only row 0 is read
+    zt3, zd3 = rows3(zt), rows3(zd)
+    parent = torch.tensor([[-1] + [0] * K] * B, dtype=torch.int32, device=dev)
+    n_nodes = torch.full((B,), K + 1, dtype=torch.int32, device=dev)
+    seq = torch.arange(B, dtype=torch.int32, device=dev)
+    hits = dict(rrs=0, kseq=0, multiround=0)
+    for t in range(trials):
+        top = binding.gumbel_topk(zd, K, seq_id=seq, seed=99, step=t, want_scores=False)["tokens"]
+        tokens = torch.cat([torch.full((B, 1), -1, dtype=torch.int32, device=dev), top], dim=1).contiguous()
+        r = binding.recursive_reject(zd3, zt3, tokens, parent, n_nodes, mode=binding.MODE_PATH, seed=99, step=t,
+                                     diagnostics=False)
+        hits["rrs"] += int((r["n_accepted"] > 0).sum().item())
+        iid = torch.cat([binding.gumbel_topk(zd, 1, seq_id=seq, node_id=seq * 0 + 1000 + k, seed=99, step=t,
+                                             want_scores=False)["tokens"] for k in range(K)], dim=1).contiguous()
+        for name, method, gamma in (("kseq", binding.BASELINE_KSEQ, float(K)),
+                                    ("multiround", binding.BASELINE_MULTIROUND, 1.0)):
+            g = binding.baseline_verify(zd, zt, iid, method, gamma=gamma, seq_id=seq, seed=99, step=t)
+            hits[name] += int((g["accepted"] >= 0).sum().item())
+    n = B * trials
+    return dict(level_acceptance_synthetic=dict(K=K, trials=n, rrs_without_replacement=round(hits["rrs"] / n, 4),
+                                                kseq_gamma_K=round(hits["kseq"] / n, 4),
+                                                multiround=round(hits["multiround"] / n, 4)))
+
+
 def filter_logits_pass(case, torch, binding, steps=5):
     """Nucleus filtering (top-p 0.95, the paper's instruction-following setting) of every target row:
     a preprocessing pass of that setting, timed on its own and not part of `value`."""
@@ -504,6 +539,7 @@ def main():
     vocab.update(rrs_path_pass(case, torch, binding))
     vocab.update(filter_kv_pass(case, torch, binding))
     vocab.update(filter_logits_pass(case, torch, binding))
+    vocab.update(acceptance_pass(case, torch, binding))
     layers = layers_pass(case, torch, binding, workloads)
     vocab.update(layers)
     vocab.update(model_step(rep, fig, layers))

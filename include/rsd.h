@@ -64,6 +64,9 @@ typedef enum rsd_status {
 #define RSD_MODE_PATH 0       /* verify only the sibling groups on the accepted path     */
 #define RSD_MODE_ALL_GROUPS 1 /* verify every sibling group in parallel, then walk        */
 
+#define RSD_BASELINE_KSEQ 0        /* K-SEQ draft selection of SpecTr                          */
+#define RSD_BASELINE_MULTIROUND 1  /* multi-round rejection sampling of SpecInfer              */
+
 /* bits of the per-sequence flag word written by rsd_recursive_reject */
 #define RSD_FLAG_DEGENERATE_RESIDUAL 1u /* a residual had no positive mass; q^(k) was kept */
 #define RSD_FLAG_NONFINITE 2u           /* a non-finite normaliser was met                  */
@@ -338,6 +341,43 @@ int32_t rsd_filter_kv_cache(void *k_cache, void *v_cache, const void *k_tree, co
 int32_t rsd_filter_logits(const float *logits, int64_t ld, int32_t R, int32_t V,
                           float inv_temperature, int32_t top_k, float top_p, float *out,
                           int64_t out_ld, int32_t *kept, void *stream);
+
+/* ---------------------------------------------------------------------------
+ * Baseline verifiers of one level of K draft tokens drawn i.i.d. (with
+ * replacement) from the draft distribution (Sec. 2, tree-based speculative
+ * decoding; compared with recursive rejection sampling in the toy example of
+ * Sec. 3.1).  Per row r with p = softmax(draft_logits[r]), q = softmax(target_logits[r])
+ * and drafts x_1..x_K = drafts[r, :]:
+ *   RSD_BASELINE_KSEQ        accept x_k with probability min(1, q(x_k) / (gamma p(x_k)));
+ *                            all rejected: draw from
+ *                            Norm[(q - min(p, q/gamma) (1 - (1-beta)^K) / beta)^+],
+ *                            beta = sum_x min(p(x), q(x)/gamma);
+ *   RSD_BASELINE_MULTIROUND  accept x_k with probability min(1, q^(k)(x_k) / p(x_k)),
+ *                            q^(1) = q, q^(k+1) = Norm[(q^(k) - p)^+];
+ *                            all rejected: draw from q^(K+1).
+ * The first accepted draft is the output; the final draw is a Gumbel-max sample.
+ * Randomness: uniform of draft k = accept stream (tag 1) at (seq_id[r], node_id[r],
+ * vocabulary index k); final noise = last-token stream (tag 2) at (seq_id[r], node_id[r]).
+ * Inputs
+ *   draft_logits, target_logits [R, V] fp32, row stride ld (elements, >= V), 16-byte aligned bases
+ *   drafts [R, K] tokens (clamped into the vocabulary), 1 <= K <= RSD_K_MAX
+ *   gamma  K-SEQ only, 1 <= gamma <= K (gamma = K is always admissible)
+ *   seq_id [R] or NULL (= 0), node_id [R] or NULL (= r)
+ * Outputs
+ *   accepted [R]  index of the accepted draft, or -1
+ *   token    [R]  the accepted draft token, or the token drawn from the residual
+ *   theta    [R, K] or NULL  every draft's threshold, as if all earlier ones were rejected
+ *   flags    [R] or NULL     RSD_FLAG_NONFINITE; RSD_FLAG_DEGENERATE_RESIDUAL when the draw used a
+ *                            residual that had no mass (the previous distribution was kept) or, for
+ *                            K-SEQ, a gamma too small for the residual to be non-negative
+ * No workspace.  The rows are streamed once per pass (multi-round: K + 2 passes).
+ * ------------------------------------------------------------------------- */
+int32_t rsd_baseline_verify(const float *draft_logits, const float *target_logits, int64_t ld,
+                            int32_t R, int32_t V, const int32_t *drafts, int32_t K, int32_t method,
+                            float gamma, float inv_temperature, const int32_t *seq_id,
+                            const int32_t *node_id, uint64_t seed, uint32_t step,
+                            int32_t *accepted, int32_t *token, float *theta, uint32_t *flags,
+                            void *stream);
 
 #ifdef __cplusplus
 }

@@ -18,6 +18,7 @@ NODES_MAX = 256
 VOCAB_MAX = 65536
 DTYPE_BF16, DTYPE_F32 = 0, 1
 MODE_PATH, MODE_ALL_GROUPS = 0, 1
+BASELINE_KSEQ, BASELINE_MULTIROUND = 0, 1
 FLAG_DEGENERATE_RESIDUAL, FLAG_NONFINITE = 1, 2
 
 _lib = None
@@ -50,6 +51,8 @@ _SIGNATURES = {
     "rsd_recursive_reject": (_i32, [_vp, _vp, _i32, _i32, _i32, _f32, _vp, _vp, _vp, _vp, _i32,
                                     _u64, _u32, _vp, _vp, _i32, _vp, _vp, _vp, _vp, _vp, _vp,
                                     _vp, _sz, _vp]),
+    "rsd_baseline_verify": (_i32, [_vp, _vp, _i64, _i32, _i32, _vp, _i32, _i32, _f32, _f32, _vp, _vp, _u64, _u32,
+                                   _vp, _vp, _vp, _vp, _vp]),
     "rsd_filter_logits": (_i32, [_vp, _i64, _i32, _i32, _f32, _i32, _f32, _vp, _i64, _vp, _vp]),
     "rsd_filter_kv_cache": (_i32, [_vp, _vp, _vp, _vp, _i32, _i32, _i32, _i32, _i32, _i32, _i64, _i64, _i64,
                                    _vp, _vp, _i32, _vp, _vp, _vp, _vp]),
@@ -356,3 +359,26 @@ def filter_logits(logits, inv_temperature=1.0, top_k=0, top_p=1.0, out=None, ret
     _check(lib().rsd_filter_logits(_ptr(rows), stride(rows), R, V, inv_temperature, top_k, top_p,
                                    _ptr(orows), stride(orows), _ptr(kept), _stream()))
     return (out, kept) if return_kept else out
+
+
+def baseline_verify(draft_logits, target_logits, drafts, method, gamma=1.0, inv_temperature=1.0,
+                    seq_id=None, node_id=None, seed=0, step=0):
+    """rsd_baseline_verify on rows [R,V] with drafts [R,K]; returns dict(accepted, token, theta, flags)."""
+    for t in (draft_logits, target_logits):
+        if t.dim() != 2 or t.stride(1) != 1 or not t.is_cuda or t.dtype != torch.float32:
+            raise ValueError("logits must be 2-D fp32 GPU tensors with contiguous rows")
+    if draft_logits.stride(0) != target_logits.stride(0) or draft_logits.shape != target_logits.shape:
+        raise ValueError("draft and target rows need the same shape and row stride")
+    _dev(drafts, torch.int32)
+    R, V = target_logits.shape
+    K = drafts.shape[1]
+    dev = target_logits.device
+    accepted = torch.empty(R, dtype=torch.int32, device=dev)
+    token = torch.empty(R, dtype=torch.int32, device=dev)
+    theta = torch.empty((R, K), dtype=torch.float32, device=dev)
+    flags = torch.empty(R, dtype=torch.int32, device=dev)
+    ld = target_logits.stride(0) if R > 1 else max(V, target_logits.stride(0))
+    _check(lib().rsd_baseline_verify(_ptr(draft_logits), _ptr(target_logits), ld, R, V, _ptr(drafts), K, method,
+                                     gamma, inv_temperature, _ptr(_opt_i32(seq_id)), _ptr(_opt_i32(node_id)),
+                                     seed, step, _ptr(accepted), _ptr(token), _ptr(theta), _ptr(flags), _stream()))
+    return dict(accepted=accepted, token=token, theta=theta, flags=flags)

@@ -6,7 +6,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "librsd.so")
-SOURCES = ["rsd_misc.hip", "vocab_kernels.hip", "rrs_kernels.hip", "tree_attention.hip", "filter_kv.hip", "prob_filter.hip"]
+SOURCES = ["rsd_misc.hip", "vocab_kernels.hip", "rrs_kernels.hip", "tree_attention.hip", "filter_kv.hip", "prob_filter.hip", "baselines.hip"]
 FLAGS = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-shared",
          # packed-fp32 VALU forms are kept out of the generated code
          "-Xclang", "-target-feature", "-Xclang", "-packed-fp32-ops",

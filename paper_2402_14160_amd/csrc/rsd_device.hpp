@@ -255,4 +255,45 @@ __device__ __forceinline__ void block_argmax_pair(float &v0, int &i0, float &v1,
     wave_argmax_dpp(v1, i1);
 }
 
+// z c - m in fp32 with c = c2h + c2l: the first fused multiply-add rounds once at the size of the
+// result, the second adds the part of c that a float cannot hold (c2l > 0, so a logit of -inf
+// stays -inf).  neg_m = -inf turns any finite z into -inf (entries outside the row).
+__device__ __forceinline__ float exponent_of(float z, float c2h, float c2l, float neg_m) {
+    return fmaf(z, c2l, fmaf(z, c2h, neg_m));
+}
+
+// fp64 sum over the 64 lanes in a fixed order (all lanes active, all receive the result).
+template <int CTRL>
+__device__ __forceinline__ double dpp_move_d(double v) {
+    const int lo = __builtin_amdgcn_update_dpp(0, __double2loint(v), CTRL, 0xF, 0xF, false);
+    const int hi = __builtin_amdgcn_update_dpp(0, __double2hiint(v), CTRL, 0xF, 0xF, false);
+    return __hiloint2double(hi, lo);
+}
+__device__ __forceinline__ double read_lane_d(double v, int lane) {
+    return __hiloint2double(__builtin_amdgcn_readlane(__double2hiint(v), lane),
+                            __builtin_amdgcn_readlane(__double2loint(v), lane));
+}
+__device__ __forceinline__ double wave_sum_f64(double v) {
+    v += dpp_move_d<0xB1>(v);
+    v += dpp_move_d<0x4E>(v);
+    v += dpp_move_d<0x124>(v);
+    v += dpp_move_d<0x128>(v);
+    return (read_lane_d(v, 0) + read_lane_d(v, 16)) + (read_lane_d(v, 32) + read_lane_d(v, 48));
+}
+
+// Hardware log2 (one instruction).  The operand is scaled out of the denormal range first,
+// which the instruction would read as zero.
+__device__ __forceinline__ float fast_ln(float x) {
+    const bool tiny = x < 0x1p-100f;
+    const float l2 = __builtin_amdgcn_logf(tiny ? x * 0x1p100f : x) - (tiny ? 100.f : 0.f);
+    return l2 * kLn2;
+}
+
+// c = log2(e) / T in fp64 and as a pair of floats with a strictly positive low part (so that a
+// logit of -inf keeps its sign through both fused multiply-adds of exponent_of).
+struct ScalePair {
+    double c2e;
+    float c2h, c2l;
+};
+
 }  // namespace rsd

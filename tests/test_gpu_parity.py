@@ -3,6 +3,7 @@ import numpy as np
 import pytest
 import torch
 
+from oracle import baselines as o_base
 from oracle import filter_kv as o_filter
 from oracle import prob_filter as o_pfilter
 from oracle import rrs as o_rrs
@@ -833,3 +834,66 @@ def test_non_finite_logits_are_flagged_not_fatal():
         flags = to_np(g["flags"])
         assert flags[0] == 0 and flags[1] & binding.FLAG_NONFINITE
         assert 0 <= int(g["n_accepted"][1]) <= 2 and -1 <= int(g["last_token"][1]) < 64
+
+
+# ------------------------------------------------------------------ baseline verifiers (Sec. 2)
+@pytest.mark.parametrize("method,gamma", [(binding.BASELINE_KSEQ, 4.0), (binding.BASELINE_KSEQ, 1.0),
+                                          (binding.BASELINE_MULTIROUND, 1.0)])
+@pytest.mark.parametrize("kind,R,V,K,inv_t", [("normal", 6, 64, 3, 1.0), ("zipf", 5, 32000, 4, 1.0),
+                                               ("zipf", 4, 50257, 4, 1.0 / 0.3), ("zipf", 3, 1001, 8, 1.0)])
+def test_baseline_verifiers_match_oracle(method, gamma, kind, R, V, K, inv_t):
+    """K-SEQ and multi-round rejection sampling on i.i.d. drafts (K independent Gumbel-max draws from the
+    draft row): thresholds, accepted draft and emitted token against the oracle."""
+    say(f"baseline verify method={method} gamma={gamma} {kind} R={R} V={V} K={K}")
+    d = dev()
+    zt, zd = workloads.make_logits(kind, 1, R, V, seed=17)
+    zt, zd = zt[0], zd[0]
+    if method == binding.BASELINE_KSEQ and gamma > K:
+        gamma = float(K)
+    ld = (V + 3) // 4 * 4
+    bt = torch.zeros((R, ld), dtype=torch.float32); bd = torch.zeros((R, ld), dtype=torch.float32)
+    bt[:, :V], bd[:, :V] = zt, zd
+    gt, gd = bt.to(d)[:, :V], bd.to(d)[:, :V]
+    # K i.i.d. draws from the draft distribution: one Gumbel-max sample per (row, k), each on its own noise
+    cols = []
+    for k in range(K):
+        node = torch.arange(R, dtype=torch.int32, device=d) + 1000 * (k + 1)
+        cols.append(binding.gumbel_topk(gd, 1, inv_temperature=inv_t, node_id=node, seed=17, step=5,
+                                        want_scores=False)["tokens"])
+    drafts = torch.cat(cols, dim=1).contiguous()
+    seq = torch.arange(R, dtype=torch.int32, device=d) % 3
+    g = binding.baseline_verify(gd, gt, drafts, method, gamma=gamma, inv_temperature=inv_t, seq_id=seq, seed=17, step=5)
+    ref = o_base.verify(zt.numpy(), zd.numpy(), to_np(drafts), method, gamma=gamma, inv_temperature=np.float32(inv_t),
+                        seq_id=to_np(seq), seed=17, step=5)
+    assert np.allclose(to_np(g["theta"]), ref["theta"], rtol=1e-5, atol=1e-6)
+    near = 0
+    for r in range(R):
+        if ref["near_tie"][r] or ref["last_gap"][r] < NEAR_TIE:
+            near += 1
+            continue
+        assert int(g["accepted"][r]) == int(ref["accepted"][r])
+        assert int(g["token"][r]) == int(ref["token"][r]), r
+        if method == binding.BASELINE_MULTIROUND or gamma >= K:
+            assert int(g["flags"][r]) == (1 if ref["flags"][r] else 0)
+    say(f"  accepted {ref['accepted'].tolist()}, near ties {near}")
+    assert near <= 1
+
+
+def test_baseline_verifiers_identical_models_and_bad_arguments():
+    say("baseline verify: identical models, argument errors")
+    d = dev()
+    zt, _ = workloads.make_logits("zipf", 1, 3, 4000, seed=19)
+    z = zt[0].to(d)
+    drafts = torch.tensor([[5, 5, 9], [1, 2, 3], [7, 7, 7]], dtype=torch.int32, device=d)
+    for method in (binding.BASELINE_KSEQ, binding.BASELINE_MULTIROUND):
+        g = binding.baseline_verify(z, z, drafts, method, gamma=1.0, seed=2)
+        # p = q: the first draft is accepted with certainty (gamma = 1)
+        assert to_np(g["accepted"]).tolist() == [0, 0, 0]
+        assert to_np(g["token"]).tolist() == [5, 1, 7]
+        assert np.all(to_np(g["theta"])[:, 0] == 1.0)
+    with pytest.raises(binding.RsdError) as e:
+        binding.baseline_verify(z, z, drafts, binding.BASELINE_KSEQ, gamma=5.0)      # gamma > K
+    assert e.value.code == -2
+    with pytest.raises(binding.RsdError) as e:
+        binding.baseline_verify(z, z, drafts, 7)
+    assert e.value.code == -6
