@@ -57,7 +57,7 @@ VALU_PEAK_LANE_OPS = 256 * 4 * 16 * 2.4e9
 # SQ_INSTS_VALU x 64 lanes / entries over the three level launches of the stress configuration
 # (profiles/cfg4_stress_gumbel_topk_counters.md, which also gives the measured busy fraction of the
 # vector ALUs, SQ_ACTIVE_INST_VALU against SQ_BUSY_CYCLES: the rate the pipeline really runs at)
-GUMBEL_VALU_PER_ENTRY = 31.2
+GUMBEL_VALU_PER_ENTRY = 31.0
 N_LAYERS = {"cfg1_llama2_7b": 32, "cfg2_opt_13b_sbs": 40, "cfg3_llama2_70b_gqa": 80, "cfg4_stress": 32}
 # draft size / target size of the model pairs the shapes stand for (App. C: a 115M drafter for the
 # Llama 2 targets, OPT-125M for OPT-13B): the relative draft cost r of the memory-bound speed-up
@@ -160,12 +160,8 @@ def algorithmic_figures(case):
     # every sibling group reads its draft row and its target row once; the last token reads
     # one more row pair per sequence
     rrs_bytes = (groups + B) * 2 * V * 4
-    # the residual step as the method states it: one pass over a target row and a draft row per
-    # verified sibling (all of them in ALL_GROUPS mode) plus one per last token
-    rrs_bytes_per_sibling = (sum(n - 1 for n in n_nodes) + B) * 2 * V * 4
     draft_bytes = case["draft_rows"] * V * 4
     return dict(attn_bytes=attn_bytes, attn_flops=attn_flops, rrs_bytes=rrs_bytes,
-                rrs_bytes_per_sibling=rrs_bytes_per_sibling,
                 draft_bytes=draft_bytes, nodes=sum(n_nodes), groups=groups)
 
 
@@ -226,7 +222,6 @@ def report(case, t):
         attn_frac_mfma=fig["attn_flops"] / attn_s / 1e12 / MFMA_BF16_PEAK_TFLOPS,
         attn_bound="mfma" if intensity > ridge else "hbm",
         rrs_GBps=fig["rrs_bytes"] / rrs_s / 1e9, rrs_frac_hbm=fig["rrs_bytes"] / rrs_s / 1e9 / HBM_PEAK_GBS,
-        rrs_per_sibling_GBps=fig["rrs_bytes_per_sibling"] / rrs_s / 1e9,
         draft_alu_frac=(fig["draft_bytes"] / 4 * GUMBEL_VALU_PER_ENTRY / draft_s / VALU_PEAK_LANE_OPS
                         if draft_s > 0 and cfg["sampler"] == "gumbel" else None),
         draft_GBps=fig["draft_bytes"] / draft_s / 1e9 if draft_s > 0 else None,
@@ -589,7 +584,7 @@ def main():
         value_full_step=rep["nodes_per_s_full_step"],
         phases=dict(draft_ms=rep["draft_ms"], attn_ms=rep["attn_ms"], rrs_ms=rep["rrs_ms"],
                     attn_GBps=rep["attn_GBps"], attn_TFLOPs=rep["attn_TFLOPs"],
-                    rrs_GBps=rep["rrs_GBps"], rrs_per_sibling_GBps=rep["rrs_per_sibling_GBps"],
+                    rrs_GBps=rep["rrs_GBps"],
                     rrs_frac_hbm=rep["rrs_frac_hbm"],
                     draft_GBps=rep["draft_GBps"], draft_alu_frac=rep["draft_alu_frac"], **vocab),
         roofline=roof, cpu_baseline=cpu, per_config=per_config,

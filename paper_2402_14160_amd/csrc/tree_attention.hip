@@ -553,8 +553,9 @@ __device__ __forceinline__ bool attn_w32_body(const AttnArgs &a, unsigned char *
         if (wave_active) {
             // One 64-key tile is processed as two 32-key halves so that, inside this wave's own
             // instruction stream, the exponentials of one half issue in the shadow of the matrix
-            // instructions of the other (matrix and vector work of different waves on one SIMD
-            // do not overlap; independent work inside one wave does):
+            // instructions of the other.  (Matrix and vector instructions overlap both inside a
+            // wave and across the two waves of a SIMD; the halves give this wave independent work
+            // of both kinds at every point, so it does not depend on what the other wave is at.)
             //   S0 = K0 Q^T | max(S0) | S1 = K1 Q^T || P0 = exp2(S0 - m) | max(S1) |
             //   O += V0^T P0 || P1 = exp2(S1 - m) | O += V1^T P1
             // The running maximum m is only raised when some row's new maximum exceeds it by more
