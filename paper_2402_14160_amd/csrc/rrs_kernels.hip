@@ -22,10 +22,21 @@
 //
 // ALL_GROUPS runs three kernels (plan, groups, walk + last token), PATH one persistent
 // workgroup per sequence.
+//
+// Memory.  A row pair (2 V floats) fills half a CU's vector registers, so one group is resident per
+// CU, and the CU's vector memory path needs 4096 cycles for it (64 B/clk), about a sixth of what a
+// group takes.  The group kernel of ALL_GROUPS therefore fetches the next item's rows while it
+// works on the current one, into whatever is free: the target row memory-to-LDS, spread over the
+// exponent and exponential passes; half of the draft row into registers the passes leave free,
+// spread over the exponential pass; the rest of the draft row into the registers of the current
+// rows right after their last use.  The variant that keeps draft chunks in LDS has no room to
+// stage and only does the last of the three.
 #include <hip/hip_runtime.h>
 #include <limits.h>
 #include <math.h>
 #include <stddef.h>
+
+#include <type_traits>
 
 #include "../../include/rsd.h"
 #include "rsd_device.hpp"
@@ -380,10 +391,93 @@ __device__ void process_group_stream(const RrsArgs &a, int b, int node, int n, G
 // 16..63 of every wave follow the heavy entries that the wave met (see the file header).  A
 // stage is three to four ALU operations per entry, one wave reduction and a single barrier.
 // ---------------------------------------------------------------------------
-template <int T, int CH, int CL>
+// Issues the loads of one group's row pair and nothing else: the target row into ut, the draft
+// row into edr (chunks CL..CH-1) and, for CL > 0, straight from memory into this thread's LDS
+// slots (chunks 0..CL-1; no registers, raw logits; 64 lanes x 16 bytes land contiguously,
+// which is the slot layout).  Every load is unconditional (a chunk past the end of the row
+// reads the row's last chunk instead and gets the exponent -inf), so that the loads form one
+// straight line and a wait can name exactly the loads it needs.
+// `chunk_mask` is -1, or 0 to make every load read the row's first chunk (a request nobody uses:
+// the loads stay unconditional and cost no traffic).
+// TARGET false: the draft row only (the target row comes another way).  Draft chunks below P
+// go to pf, the registers they are prefetched into in steady state; P_DONE: they are there already.
+template <int T, int CH, int CL, bool TARGET = true, int P = 0, bool P_DONE = false>
+__device__ __forceinline__ void issue_row_loads(const float *zt, const float *zd, int V, int tid,
+                                                float (&ut)[CH * 4], float (&edr)[(CH - CL) * 4],
+                                                float4 *s_ed, int chunk_mask, float (&pf)[(P > 0 ? P : 1) * 4]) {
+    const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
+    const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
+    const int last = (V >> 2) - 1;
+#pragma unroll
+    for (int j = 0; j < CH; ++j) {
+        const int c = min(j * T + tid, last) & chunk_mask;
+        if constexpr (TARGET) {
+            const float4 t = zt4[c];
+            ut[4 * j + 0] = t.x; ut[4 * j + 1] = t.y; ut[4 * j + 2] = t.z; ut[4 * j + 3] = t.w;
+        }
+        if (j >= CL && j < P) {
+            if constexpr (!P_DONE) {
+                const float4 d = zd4[c];
+                pf[4 * j] = d.x; pf[4 * j + 1] = d.y; pf[4 * j + 2] = d.z; pf[4 * j + 3] = d.w;
+            }
+        } else if (j >= CL) {
+            const float4 d = zd4[c];
+            const int r = 4 * (j - CL);
+            edr[r] = d.x; edr[r + 1] = d.y; edr[r + 2] = d.z; edr[r + 3] = d.w;
+        }
+    }
+    if constexpr (CL > 0) {
+        const int wave = tid / kWave;
+#pragma unroll
+        for (int j = 0; j < CL; ++j)
+            __builtin_amdgcn_global_load_lds((global_void *)(zd4 + (min(j * T + tid, last) & chunk_mask)),
+                                             (lds_void *)(s_ed + j * T + wave * kWave), 16, 0, 0);
+    }
+}
+
+// What the ALL_GROUPS work loop hands through a group: in, thread 0's next queue index and that
+// item's entry; out, the next item as every thread knows it, its children lookup and -- in ut,
+// edr and the LDS slots -- its rows, requested as soon as the current group has read its own
+// for the last time.
+struct NextGroup {
+    int idx;      // in (thread 0): queue index of the next item; out: the same for every thread
+    int2 ent;     // in (thread 0): that item's work entry {group, tree size}
+    int claim;    // in/out (thread 0): the queue index asked for at the start of this group; it is
+                  // waited for before the next rows are requested, not behind them
+    bool has;     // out: there is a next item
+    int b, node, n;
+    ChildCandidate cand;
+};
+
+// The next group's target row is staged in LDS while the current group is worked on, when LDS has
+// the room (no draft chunks there): one memory-to-LDS load per chunk, spread over the exponent
+// pass, so that the CU's vector memory path (64 B/clk: a row pair takes it 4096 cycles) is busy
+// under arithmetic instead of in front of it.
+template <int CL, bool PIPE>
+constexpr bool stages_next_row() { return PIPE && CL == 0; }
+
+// Workgroup barrier for threads that talk through LDS only.  __syncthreads() also waits for
+// every memory-to-LDS load in flight, which would end the staging at the first barrier.
+template <bool LDS_ONLY>
+__device__ __forceinline__ void group_barrier() {
+    if constexpr (LDS_ONLY)
+        asm volatile("s_waitcnt lgkmcnt(0)\n\ts_barrier" ::: "memory");
+    else
+        __syncthreads();
+}
+
+// ... and P chunks of its draft row are prefetched into registers that the passes leave free, one
+// load per chunk of the exponential pass.
+template <int T, int CH, int CL, bool PIPE>
+constexpr int prefetched_draft_chunks() { return !stages_next_row<CL, PIPE>() ? 0 : (T == 512 && CH == 16) ? 8 : CH / 2; }
+
+template <int T, int CH, int CL, bool PIPE>
 __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, ChildCandidate cand,
                                                   float (&ut)[CH * 4], float (&edr)[(CH - CL) * 4],
-                                                  float4 *s_ed, GroupShared &sh) {
+                                                  float (&pf)[(prefetched_draft_chunks<T, CH, CL, PIPE>() > 0 ? prefetched_draft_chunks<T, CH, CL, PIPE>() : 1) * 4],
+                                                  float4 *s_ed, float4 *s_nt, GroupShared &sh, NextGroup &nx, int count) {
+    constexpr bool STAGE = stages_next_row<CL, PIPE>();
+    constexpr int P = prefetched_draft_chunks<T, CH, CL, PIPE>();
     constexpr int NW = T / kWave;
     static_assert(NW <= kGroupWavesMax && CL >= 0 && CL < CH && T >= RSD_NODES_MAX, "");
     static_assert(CH * 4 <= 128, "the child mask holds 128 entries");
@@ -408,6 +502,11 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
         const int r = j < CL ? 0 : 4 * (j - CL);
         return make_float4(edr[r], edr[r + 1], edr[r + 2], edr[r + 3]);
     };
+    // chunk j of the raw draft row as the group finds it (the prefetched chunks are still in pf)
+    auto ed_raw = [&](int j) -> float4 {
+        if (j < P) return make_float4(pf[4 * j], pf[4 * j + 1], pf[4 * j + 2], pf[4 * j + 3]);
+        return ed_get(j);
+    };
     auto ed_put = [&](int j, float4 v) {
         if (j < CL) {
             s_ed[j * T + tid] = v;
@@ -423,7 +522,7 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
         mt = fmaxf(mt, fmaxf(fmaxf(ut[4 * j], ut[4 * j + 1]), fmaxf(ut[4 * j + 2], ut[4 * j + 3])));
-        const float4 d = ed_get(j);
+        const float4 d = ed_raw(j);
         md = fmaxf(md, fmaxf(fmaxf(d.x, d.y), fmaxf(d.z, d.w)));
         if (j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
     }
@@ -434,6 +533,12 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
     if (lane0) {
         sh.ms[wave] = MaxSum{mt, md};
         if (wave < RSD_NODES_MAX / kWave) sh.cmask[wave] = cmask;
+    }
+    if constexpr (PIPE) {
+        if (tid == 0) {
+            sh.next_idx = nx.idx;
+            sh.next_ent = nx.ent;
+        }
     }
     __syncthreads();
     if (match) {
@@ -456,7 +561,26 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
     for (int w = 0; w < NW; ++w) { mt = fmaxf(mt, sh.ms[w].m); md = fmaxf(md, sh.ms[w].s); }
     __syncthreads();
     const int K = sh.g.K;
-    if (K == 0) return;
+    if constexpr (PIPE) {
+        nx.idx = sh.next_idx;
+        nx.has = nx.idx < count;
+        const int gi = sh.next_ent.x;
+        nx.n = sh.next_ent.y;
+        nx.b = gi / a.N;
+        nx.node = gi - nx.b * a.N;
+    }
+    // (without a next item: the entry read for it is the work list's last, a valid group, and
+    // the requests all go to its rows' first chunk)
+    const int nmask = (PIPE && nx.has) ? -1 : 0;
+    const float4 *nzt4 = reinterpret_cast<const float4 *>(a.zt + ((int64_t)nx.b * a.N + nx.node) * a.V);
+    const float4 *nzd4 = reinterpret_cast<const float4 *>(a.zd + ((int64_t)nx.b * a.N + nx.node) * a.V);
+    // its children's lookup is asked for now and used at the end of this group (their own logits)
+    if constexpr (PIPE) nx.cand = fetch_candidate(a, nx.b, nx.node, nx.n, tid);
+    // (No group of the work list is empty.  If one were, the passes below would run on it to no
+    // effect -- no child lane, no stage, no threshold -- and the next item's rows are still asked for.)
+    if constexpr (!PIPE) {
+        if (K == 0) return;
+    }
     // bit (4 j + e) set: this thread's entry (j, e) is a child token
     uint64_t elmask[2] = {0, 0};
     for (int i = 0; i < K; ++i) {
@@ -470,14 +594,22 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
     // Exponents in place first.  Child tokens and heavy entries leave the fp32 arrays (exponent
     // -inf); the heavy ones go to this wave's list with their raw logits.
     int ncand = 0;  // (wave-uniform)
+    // chunk c of the next item's target row, memory to LDS (this thread's slot)
+    auto stage_chunk = [&](int c) {
+        __builtin_amdgcn_global_load_lds((global_void *)(nzt4 + (min(c * T + tid, last) & nmask)),
+                                         (lds_void *)(s_nt + c * T + wave * kWave), 16, 0, 0);
+    };
     // (chunk numbers are worked out again here rather than kept from the load loop)
     int tid_x = tid;
     asm volatile("" : "+v"(tid_x));
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
+        if constexpr (STAGE) {
+            if (j < CH / 2) stage_chunk(j);
+        }
         const bool inrow = j * T + tid_x <= last;
         const float bt = inrow ? -m_t : -INFINITY, bd = inrow ? -m_d : -INFINITY;
-        const float4 dr = ed_get(j);
+        const float4 dr = ed_raw(j);
         const float tz[4] = {ut[4 * j], ut[4 * j + 1], ut[4 * j + 2], ut[4 * j + 3]};
         const float dz[4] = {dr.x, dr.y, dr.z, dr.w};
         float at[4], ad[4];
@@ -519,6 +651,13 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
     float st = 0.f, sd = 0.f;
 #pragma unroll
     for (int j = 0; j < CH; ++j) {
+        if constexpr (STAGE) {
+            if (CH / 2 + j < CH) stage_chunk(CH / 2 + j);
+            if (j < P) {
+                const float4 nd = nzd4[min(j * T + tid, last) & nmask];
+                pf[4 * j] = nd.x; pf[4 * j + 1] = nd.y; pf[4 * j + 2] = nd.z; pf[4 * j + 3] = nd.w;
+            }
+        }
         float4 d = ed_get(j);
         d.x = __builtin_amdgcn_exp2f(d.x);
         d.y = __builtin_amdgcn_exp2f(d.y);
@@ -576,7 +715,7 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
             sh.red2[wave] = se;
         }
     }
-    __syncthreads();
+    group_barrier<STAGE>();
     double St = 0.0, Sd = 0.0;
 #pragma unroll
     for (int w = 0; w < NW; ++w) { St += sh.red[w]; Sd += sh.red2[w]; }
@@ -588,8 +727,15 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
         if (!(St > 0.0) || !isfinite(St) || !(s0 > 0.0) || !isfinite(s0)) sh.g.flags |= RSD_FLAG_NONFINITE;
     }
     double A = St;  // q^(k) = u / A
-#pragma unroll 1
-    for (int k = 0; k < K; ++k) {
+    // Stage k < K - 1 needs A_{k+1} = sum_x max(u - gamma_k e_d, 0) and, only if a stage follows it,
+    // the rows after the subtraction.  So the subtraction of stage k - 1 is applied inside the
+    // pass of stage k (one read-modify-write of u and one read of e_d per stage instead of two
+    // passes), the first stage only sums, and the last subtraction -- whose result nobody reads:
+    // the last-token pass works from the raw rows -- is never made.  A stage that is skipped
+    // (its residual has no mass) leaves a pending subtraction of zero.
+    float uh = 0.f, ul = 0.f;  // pending subtraction: gamma_{k-1} as a pair of floats
+    auto stage = [&](auto first_tag, int k) {
+        constexpr bool FIRST = decltype(first_tag)::value;
         // draft mass still available at stage k: the rest plus the children not yet removed
         double s_k = Sd;
         for (int i = K - 1; i >= k; --i) s_k += sh.ce[i];
@@ -597,33 +743,26 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
         if (tid == k) {  // what child k's threshold needs, divided once after the loop
             sh.th[k][0] = tU; sh.th[k][1] = A; sh.th[k][2] = s_k; sh.th[k][3] = tE;
         }
-        if (k == K - 1) {
-            if (tid == 0) sh.g.gam[k] = gam;
-            break;
-        }
-        const float gh = (float)gam, gl = (float)(gam - (double)(float)gam);
-        const bool fine = A < St * 0.0625;  // (uniform) small residual mass: gamma as a pair of floats
+        const float gh = (float)gam;
+        // small residual mass: gamma as a pair of floats (A_1 = St: never at the first stage)
+        const bool fine = !FIRST && A < St * 0.0625;
+        const float gl = fine ? (float)(gam - (double)gh) : 0.f;
         float part = 0.f;
-        if (!fine) {
 #pragma unroll
-            for (int j = 0; j < CH; ++j) {
-                const float4 d = ed_get(j);
-                part += fmaxf(fmaf(-gh, d.x, ut[4 * j + 0]), 0.f);
-                part += fmaxf(fmaf(-gh, d.y, ut[4 * j + 1]), 0.f);
-                part += fmaxf(fmaf(-gh, d.z, ut[4 * j + 2]), 0.f);
-                part += fmaxf(fmaf(-gh, d.w, ut[4 * j + 3]), 0.f);
-                if (CL > 0 && j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
-            }
-        } else {
+        for (int j = 0; j < CH; ++j) {
+            const float4 d = ed_get(j);
+            const float de[4] = {d.x, d.y, d.z, d.w};
 #pragma unroll
-            for (int j = 0; j < CH; ++j) {
-                const float4 d = ed_get(j);
-                part += fmaxf(fmaf(-gl, d.x, fmaf(-gh, d.x, ut[4 * j + 0])), 0.f);
-                part += fmaxf(fmaf(-gl, d.y, fmaf(-gh, d.y, ut[4 * j + 1])), 0.f);
-                part += fmaxf(fmaf(-gl, d.z, fmaf(-gh, d.z, ut[4 * j + 2])), 0.f);
-                part += fmaxf(fmaf(-gl, d.w, fmaf(-gh, d.w, ut[4 * j + 3])), 0.f);
-                if (CL > 0 && j % 3 == 2) __builtin_amdgcn_sched_barrier(0);
+            for (int e = 0; e < 4; ++e) {
+                if constexpr (FIRST) {
+                    part += fmaxf(fmaf(-gh, de[e], ut[4 * j + e]), 0.f);
+                } else {
+                    const float u = fmaxf(fmaf(-ul, de[e], fmaf(-uh, de[e], ut[4 * j + e])), 0.f);
+                    ut[4 * j + e] = u;
+                    part += fmaxf(fmaf(-gl, de[e], fmaf(-gh, de[e], u)), 0.f);
+                }
             }
+            if (CL > 0 && j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
         }
         const double cnew = fmax(tU - gam * tE, 0.0);
         part = wave_sum(part);
@@ -631,25 +770,13 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
         if (tracked) wsum += wave_sum_f64(cnew);
         double *red = sh.sred[k & 1];
         if (lane0) red[wave] = wsum;
-        __syncthreads();
+        group_barrier<STAGE>();
         double S = 0.0;
 #pragma unroll
         for (int w = 0; w < NW; ++w) S += red[w];
         const bool ok = S > 0.0 && isfinite(S);
-        {
-            // One branch-free update for all cases (a stage that is skipped subtracts zero): the
-            // rows' registers then have a single definition per stage.
-            const float uh = ok ? gh : 0.f, ul = (ok && fine) ? gl : 0.f;
-#pragma unroll
-            for (int j = 0; j < CH; ++j) {
-                const float4 d = ed_get(j);
-                ut[4 * j + 0] = fmaxf(fmaf(-ul, d.x, fmaf(-uh, d.x, ut[4 * j + 0])), 0.f);
-                ut[4 * j + 1] = fmaxf(fmaf(-ul, d.y, fmaf(-uh, d.y, ut[4 * j + 1])), 0.f);
-                ut[4 * j + 2] = fmaxf(fmaf(-ul, d.z, fmaf(-uh, d.z, ut[4 * j + 2])), 0.f);
-                ut[4 * j + 3] = fmaxf(fmaf(-ul, d.w, fmaf(-uh, d.w, ut[4 * j + 3])), 0.f);
-                if (CL > 0 && j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
-            }
-        }
+        uh = ok ? gh : 0.f;
+        ul = ok ? gl : 0.f;
         if (ok) {
             tU = cnew;
             if (tid == 0) sh.g.gam[k] = gam;
@@ -660,12 +787,33 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
         }
         // x_k leaves the draft distribution either way
         if (tid == k) tE = 0.0;
+    };
+    if (K >= 2) {
+        stage(std::true_type{}, 0);
+#pragma unroll 1
+        for (int k = 1; k < K - 1; ++k) stage(std::false_type{}, k);
+    }
+    if (K > 0) {  // the last child: its threshold's inputs and gamma_K (the last-token pass subtracts it)
+        const int k = K - 1;
+        const double s_k = Sd + sh.ce[k];
+        if (tid == k) {
+            sh.th[k][0] = tU; sh.th[k][1] = A; sh.th[k][2] = s_k; sh.th[k][3] = tE;
+        }
+        if (tid == 0) sh.g.gam[k] = A / s_k;
+    }
+    // Nothing reads this group's rows any more: the next group's are requested here, under the
+    // thresholds, the record's way to memory and the queue.
+    if constexpr (PIPE) {
+            asm volatile("" : "+v"(nx.claim));
+        const int64_t row = ((int64_t)nx.b * a.N + nx.node) * a.V;
+        fetch_child_logits(a.zt + row, a.zd + row, a.V, nx.node, nx.cand);
+        issue_row_loads<T, CH, CL, !STAGE, P, true>(a.zt + row, a.zd + row, a.V, tid, ut, edr, s_ed, nmask, pf);
     }
     if (tid < K) {  // threshold of child `tid` (Eq. (3)): (u / A) / (e_d / s); the lane's own values
         const double p = sh.th[tid][3] / sh.th[tid][2];
         sh.g.theta[tid] = (p > 0.0) ? (float)fmin(1.0, sh.th[tid][0] / (sh.th[tid][1] * p)) : 1.f;
     }
-    __syncthreads();
+    group_barrier<STAGE>();
 }
 
 // The resident variant on rows that it loads itself: one row pair per call, nothing overlapped
@@ -676,44 +824,21 @@ __device__ void process_group_res(const RrsArgs &a, int b, int node, int n, Grou
     __shared__ float4 s_ed[CL > 0 ? CL * T : 1];
     int tid = threadIdx.x;
     asm volatile("" : "+v"(tid));
-    const int wave = tid / kWave;
     const float *zt = a.zt + ((int64_t)b * a.N + node) * a.V;
     const float *zd = a.zd + ((int64_t)b * a.N + node) * a.V;
-    const float4 *zt4 = reinterpret_cast<const float4 *>(zt);
-    const float4 *zd4 = reinterpret_cast<const float4 *>(zd);
-    const int last = (a.V >> 2) - 1;
     // The children's lookup is requested first and the rows right after it, before the lookup
     // is used: its dependent steps (the children's own logits, two barriers) then run under
-    // the rows' memory latency.  Every row load is unconditional (a chunk past the end of the
-    // row reads the row's last chunk instead and gets the exponent -inf), so that the loads
-    // form one straight line and a wait can name exactly the loads it needs.
+    // the rows' memory latency.
     ChildCandidate cand = fetch_candidate(a, b, node, n, tid);
     float ut[CH * 4], edr[CR * 4];
-#pragma unroll
-    for (int j = 0; j < CH; ++j) {
-        const int c = min(j * T + tid, last);
-        const float4 t = zt4[c];
-        ut[4 * j + 0] = t.x; ut[4 * j + 1] = t.y; ut[4 * j + 2] = t.z; ut[4 * j + 3] = t.w;
-        if (j >= CL) {
-            const float4 d = zd4[c];
-            const int r = 4 * (j - CL);
-            edr[r] = d.x; edr[r + 1] = d.y; edr[r + 2] = d.z; edr[r + 3] = d.w;
-        }
-    }
+    float pf[4];  // (no prefetch here)
+    issue_row_loads<T, CH, CL>(zt, zd, a.V, tid, ut, edr, s_ed, -1, pf);
     // (the candidate is consumed from here on: its wait and the children's own logit loads come
     // after every row load has been issued)
     asm volatile("" : "+v"(cand.parent), "+v"(cand.token));
     fetch_child_logits(zt, zd, a.V, node, cand);
-    // chunks 0..CL-1 of the draft row go from memory straight into this thread's LDS slots (no
-    // registers, raw logits; 64 lanes x 16 bytes land contiguously, which is the slot layout)
-    if constexpr (CL > 0) {
-#pragma unroll
-        for (int j = 0; j < CL; ++j)
-            __builtin_amdgcn_global_load_lds((global_void *)(zd4 + min(j * T + tid, last)),
-                                             (lds_void *)(s_ed + j * T + wave * kWave), 16, 0, 0);
-        asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-    }
-    compute_group_res<T, CH, CL>(a, node, cand, ut, edr, s_ed, sh);
+    NextGroup nx{};
+    compute_group_res<T, CH, CL, false>(a, node, cand, ut, edr, pf, s_ed, nullptr, sh, nx, 0);
 }
 
 // CH == 0: streaming variant; else the resident variant with CH chunks per thread, CL of them in LDS
@@ -915,51 +1040,110 @@ __global__ __launch_bounds__(kPlanThreads) void rrs_plan_kernel(RrsArgs a) {
 
 // ---------------------------------------------------------------------------
 // ALL_GROUPS, kernel 1: persistent workgroups take items off the work list (largest groups
-// first) through one atomic counter; a workgroup asks for its next item, and reads that item's
-// entry, while it verifies the current one, so neither round trip is waited for.
+// first) through one atomic counter.  The first item of a workgroup is its own number; further
+// ones come off the counter (which starts at zero and counts the items after the first G).  A
+// workgroup asks for the number of the item after the next, and reads the next item's entry,
+// while it verifies the current one, so no round trip is waited for inside the loop.  The
+// resident variants also request the next item's rows as soon as the current group has read
+// its own for the last time (the rows live in the same registers and LDS slots).
 // ---------------------------------------------------------------------------
+__device__ __forceinline__ void write_group_record(const RrsArgs &a, int i, int b, const GroupShared &sh, int threads) {
+    GroupRec *out = a.rec + i;
+    const int words = sizeof(GroupRec) / 4;
+    const uint32_t *src = reinterpret_cast<const uint32_t *>(&sh.g);
+    uint32_t *dst = reinterpret_cast<uint32_t *>(out);
+    for (int w = threadIdx.x; w < words; w += threads) dst[w] = src[w];
+    if (a.theta && (int)threadIdx.x < sh.g.K)
+        a.theta[(int64_t)b * a.N + sh.g.kid[threadIdx.x]] = sh.g.theta[threadIdx.x];
+}
+
 template <int THREADS, int CH, int CL>
 __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
     __shared__ GroupShared sh;
     const int count = a.wq[0];
     const int G = gridDim.x;
-    // The first item of a workgroup is its own number; further ones come off the counter (which
-    // starts at zero and counts the items after the first G).  The number of the item after the
-    // next is asked for, and the entry of the next item read, while the current item is
-    // verified: no round trip is waited for inside the loop.
     int lane_zero = 0;
     asm volatile("" : "+v"(lane_zero));
     int idx = blockIdx.x;
-    int2 ent = make_int2(0, 1);
-    if (idx < count) ent = a.work[idx + lane_zero];
+    if (idx >= count) return;
+    int2 ent = a.work[idx + lane_zero];
     int idx1 = 0;  // (thread 0) the next item
     if (threadIdx.x == 0) idx1 = G + atomicAdd(&a.wq[1], 1);
-    while (idx < count) {
-        const int i = __builtin_amdgcn_readfirstlane(ent.x), n = __builtin_amdgcn_readfirstlane(ent.y);
-        int idx2 = 0;
-        int2 nent = make_int2(0, 1);
-        if (threadIdx.x == 0) {
-            nent = a.work[min(idx1, count - 1)];
-            idx2 = G + atomicAdd(&a.wq[1], 1);
+    if constexpr (CH > 0) {
+        constexpr int CR = CH - CL;  // chunks of e_d held in registers
+        constexpr bool STAGE = stages_next_row<CL, true>();
+        __shared__ float4 s_ed[CL > 0 ? CL * THREADS : 1];
+        __shared__ float4 s_nt[STAGE ? CH * THREADS : 1];  // the next item's target row (raw logits)
+        constexpr int P = prefetched_draft_chunks<THREADS, CH, CL, true>();
+        float ut[CH * 4], edr[CR * 4], pf[(P > 0 ? P : 1) * 4];
+        int i = __builtin_amdgcn_readfirstlane(ent.x), n = __builtin_amdgcn_readfirstlane(ent.y);
+        int b = i / a.N, node = i - b * a.N;
+        // first item: the children's lookup is requested first and the rows right after it
+        ChildCandidate cand = fetch_candidate(a, b, node, n, threadIdx.x);
+        {
+            const int64_t row = ((int64_t)b * a.N + node) * a.V;
+            issue_row_loads<THREADS, CH, CL, true, P, false>(a.zt + row, a.zd + row, a.V, threadIdx.x, ut, edr, s_ed, -1, pf);
         }
-        const int b = i / a.N, node = i - b * a.N;
-        verify_group<THREADS, CH, CL>(a, b, node, n, sh);
-        GroupRec *out = a.rec + i;
-        const int words = sizeof(GroupRec) / 4;
-        const uint32_t *src = reinterpret_cast<const uint32_t *>(&sh.g);
-        uint32_t *dst = reinterpret_cast<uint32_t *>(out);
-        for (int w = threadIdx.x; w < words; w += THREADS) dst[w] = src[w];
-        if (a.theta && (int)threadIdx.x < sh.g.K)
-            a.theta[(int64_t)b * a.N + sh.g.kid[threadIdx.x]] = sh.g.theta[threadIdx.x];
-        if (threadIdx.x == 0) {
-            sh.next_idx = idx1;
-            sh.next_ent = nent;
-            idx1 = idx2;
+        {
+            // (the candidate is consumed from here on: the children's own logit loads come
+            // after every row load has been issued)
+            asm volatile("" : "+v"(cand.parent), "+v"(cand.token));
+            const int64_t row = ((int64_t)b * a.N + node) * a.V;
+            fetch_child_logits(a.zt + row, a.zd + row, a.V, node, cand);
         }
-        __syncthreads();
-        idx = sh.next_idx;
-        ent = sh.next_ent;
-        __syncthreads();  // sh is reused by the next item
+        while (true) {
+            NextGroup nx{};
+            if (threadIdx.x == 0) {
+                nx.idx = idx1;
+                nx.ent = a.work[min(idx1, count - 1)];
+                nx.claim = atomicAdd(&a.wq[1], 1);  // (G is added where the value is first needed)
+            }
+            compute_group_res<THREADS, CH, CL, true>(a, node, cand, ut, edr, pf, s_ed, s_nt, sh, nx, count);
+            write_group_record(a, i, b, sh, THREADS);
+            idx1 = G + nx.claim;
+            group_barrier<STAGE>();  // sh is reused by the next item
+            if (!nx.has) break;
+            if constexpr (STAGE) {
+                // The staged row moves to the registers.  Its loads are older than the CH - P
+                // loads of the draft row that followed them, and loads complete in order.
+                asm volatile("s_waitcnt vmcnt(%0)" ::"n"(CH - P) : "memory");
+                int tid = threadIdx.x;
+                asm volatile("" : "+v"(tid));
+#pragma unroll
+                for (int j = 0; j < CH; ++j) {
+                    const float4 t = s_nt[j * THREADS + tid];
+                    ut[4 * j + 0] = t.x; ut[4 * j + 1] = t.y; ut[4 * j + 2] = t.z; ut[4 * j + 3] = t.w;
+                }
+            }
+            const int gi = nx.b * a.N + nx.node;
+            i = __builtin_amdgcn_readfirstlane(gi);
+            n = __builtin_amdgcn_readfirstlane(nx.n);
+            b = __builtin_amdgcn_readfirstlane(nx.b);
+            node = __builtin_amdgcn_readfirstlane(nx.node);
+            cand = nx.cand;
+        }
+    } else {
+        while (idx < count) {
+            const int i = __builtin_amdgcn_readfirstlane(ent.x), n = __builtin_amdgcn_readfirstlane(ent.y);
+            int idx2 = 0;
+            int2 nent = make_int2(0, 1);
+            if (threadIdx.x == 0) {
+                nent = a.work[min(idx1, count - 1)];
+                idx2 = G + atomicAdd(&a.wq[1], 1);
+            }
+            const int b = i / a.N, node = i - b * a.N;
+            verify_group<THREADS, CH, CL>(a, b, node, n, sh);
+            write_group_record(a, i, b, sh, THREADS);
+            if (threadIdx.x == 0) {
+                sh.next_idx = idx1;
+                sh.next_ent = nent;
+                idx1 = idx2;
+            }
+            __syncthreads();
+            idx = sh.next_idx;
+            ent = sh.next_ent;
+            __syncthreads();  // sh is reused by the next item
+        }
     }
 }
 

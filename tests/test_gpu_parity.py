@@ -811,6 +811,26 @@ def test_recursive_reject_many_nodes_plan_in_global_memory():
     assert near <= 2
 
 
+@pytest.mark.parametrize("V,B,inv_t", [
+    (4096, 120, 1.0),          # 256 threads, rows in registers
+    (32000, 110, 1.0 / 0.7),   # 512 threads, rows in registers
+    (50272, 100, 1.0),         # 512 threads, draft row partly in LDS
+    (65536, 100, 1.0),         # streaming variant
+])
+def test_recursive_reject_several_groups_per_workgroup(V, B, inv_t):
+    """More sibling groups than the chip has compute units, so that every persistent workgroup of
+    the ALL_GROUPS pass takes several items off the work queue and the hand-over between items
+    (rows of the next group requested while the current one is verified) is exercised, in every
+    vocabulary-size variant.  Random ragged subtrees of the (3, 2, 2) tree: about 7 groups a sequence."""
+    counts = [workloads.random_subtree_child_counts((3, 2, 2), 14, 900 + b) for b in range(B)]
+    groups = sum(1 for c in counts for level in c for k in level if k > 0)
+    say(f"rrs with {groups} groups at V = {V}")
+    assert groups > 2 * 256
+    near, _ = _rrs_case("zipf", B, V, counts, 14, 31 + V % 97, inv_t, binding.MODE_ALL_GROUPS)
+    say(f"  near ties {near}")
+    assert near <= max(3, B // 20)
+
+
 def test_tree_attention_largest_tree():
     say("attention bf16 with 256 nodes (four ancestor words, four tree tiles)")
     err = _attention_case(1, 2, 1, 256, 128, 70, "bf16", 5, n_nodes=[256], plens=[70])
