@@ -734,12 +734,16 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
     // the last-token pass works from the raw rows -- is never made.  A stage that is skipped
     // (its residual has no mass) leaves a pending subtraction of zero.
     float uh = 0.f, ul = 0.f;  // pending subtraction: gamma_{k-1} as a pair of floats
+    // Draft mass still available at stage k: the rest plus the children not yet removed.  Lane k of
+    // every wave works out s_k and its reciprocal before the stages, so that a stage starts with a
+    // lane read and a product instead of a chain of additions and a division.
+    double sk_lane = Sd;
+    for (int i = K - 1; i >= min(lane, K); --i) sk_lane += sh.ce[i];
+    const double rsk_lane = 1.0 / sk_lane;
     auto stage = [&](auto first_tag, int k) {
         constexpr bool FIRST = decltype(first_tag)::value;
-        // draft mass still available at stage k: the rest plus the children not yet removed
-        double s_k = Sd;
-        for (int i = K - 1; i >= k; --i) s_k += sh.ce[i];
-        const double gam = A / s_k;
+        const double s_k = read_lane_d(sk_lane, k);
+        const double gam = A * read_lane_d(rsk_lane, k);
         if (tid == k) {  // what child k's threshold needs, divided once after the loop
             sh.th[k][0] = tU; sh.th[k][1] = A; sh.th[k][2] = s_k; sh.th[k][3] = tE;
         }
@@ -764,10 +768,8 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
             }
             if (CL > 0 && j % 3 == 2) __builtin_amdgcn_sched_barrier(0);  // (bounds how far ahead chunks are read)
         }
-        const double cnew = fmax(tU - gam * tE, 0.0);
-        part = wave_sum(part);
-        double wsum = (double)part;
-        if (tracked) wsum += wave_sum_f64(cnew);
+        const double cnew = fmax(tU - gam * tE, 0.0);  // (zero in lanes that follow no entry)
+        const double wsum = wave_sum_f64((double)part + cnew);
         double *red = sh.sred[k & 1];
         if (lane0) red[wave] = wsum;
         group_barrier<STAGE>();
@@ -795,11 +797,11 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
     }
     if (K > 0) {  // the last child: its threshold's inputs and gamma_K (the last-token pass subtracts it)
         const int k = K - 1;
-        const double s_k = Sd + sh.ce[k];
+        const double s_k = read_lane_d(sk_lane, k);
         if (tid == k) {
             sh.th[k][0] = tU; sh.th[k][1] = A; sh.th[k][2] = s_k; sh.th[k][3] = tE;
         }
-        if (tid == 0) sh.g.gam[k] = A / s_k;
+        if (tid == 0) sh.g.gam[k] = A * read_lane_d(rsk_lane, k);
     }
     // Nothing reads this group's rows any more: the next group's are requested here, under the
     // thresholds, the record's way to memory and the queue.
@@ -1102,7 +1104,12 @@ __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
             write_group_record(a, i, b, sh, THREADS);
             idx1 = G + nx.claim;
             group_barrier<STAGE>();  // sh is reused by the next item
-            if (!nx.has) break;
+            if (!nx.has) {
+                // (the requests made for a next item that does not exist land before the
+                // workgroup gives up its LDS and registers)
+                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
+                break;
+            }
             if constexpr (STAGE) {
                 // The staged row moves to the registers.  Its loads are older than the CH - P
                 // loads of the draft row that followed them, and loads complete in order.
