@@ -569,8 +569,8 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
         nx.b = gi / a.N;
         nx.node = gi - nx.b * a.N;
     }
-    // (without a next item: the entry read for it is the work list's last, a valid group, and
-    // the requests all go to its rows' first chunk)
+    // (without a next item the entry names the current group, and the requests all go to the first
+    // chunk of its rows)
     const int nmask = (PIPE && nx.has) ? -1 : 0;
     const float4 *nzt4 = reinterpret_cast<const float4 *>(a.zt + ((int64_t)nx.b * a.N + nx.node) * a.V);
     const float4 *nzd4 = reinterpret_cast<const float4 *>(a.zd + ((int64_t)nx.b * a.N + nx.node) * a.V);
@@ -1097,19 +1097,18 @@ __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
             NextGroup nx{};
             if (threadIdx.x == 0) {
                 nx.idx = idx1;
-                nx.ent = a.work[min(idx1, count - 1)];
+                // (past the end of the list the "next item" is the current one over again: what
+                // is requested for it then goes to this group's own rows, a different place for
+                // every workgroup, and is never used)
+                nx.ent = make_int2(i, n);
+                if (idx1 < count) nx.ent = a.work[idx1];
                 nx.claim = atomicAdd(&a.wq[1], 1);  // (G is added where the value is first needed)
             }
             compute_group_res<THREADS, CH, CL, true>(a, node, cand, ut, edr, pf, s_ed, s_nt, sh, nx, count);
             write_group_record(a, i, b, sh, THREADS);
             idx1 = G + nx.claim;
             group_barrier<STAGE>();  // sh is reused by the next item
-            if (!nx.has) {
-                // (the requests made for a next item that does not exist land before the
-                // workgroup gives up its LDS and registers)
-                asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
-                break;
-            }
+            if (!nx.has) break;
             if constexpr (STAGE) {
                 // The staged row moves to the registers.  Its loads are older than the CH - P
                 // loads of the draft row that followed them, and loads complete in order.
@@ -1129,6 +1128,9 @@ __global__ __launch_bounds__(THREADS) void rrs_group_kernel(RrsArgs a) {
             node = __builtin_amdgcn_readfirstlane(nx.node);
             cand = nx.cand;
         }
+        // (the requests made for a next item that does not exist land before the workgroup gives
+        // up its LDS and registers)
+        asm volatile("s_waitcnt vmcnt(0)");
     } else {
         while (idx < count) {
             const int i = __builtin_amdgcn_readfirstlane(ent.x), n = __builtin_amdgcn_readfirstlane(ent.y);
