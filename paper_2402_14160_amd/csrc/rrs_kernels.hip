@@ -903,16 +903,28 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
     const uint32_t c3 = counter_word3(kTagLastGumbel, a.step);
     const int K = g.K;
     best_v = -INFINITY; best_i = INT_MAX; alt_v = -INFINITY; alt_i = INT_MAX;
+    // The range is walked in batches of kBatch chunks per thread whose loads are all requested
+    // before the first is used: one memory round trip per batch instead of one per chunk.
+    constexpr int kBatch = 4;
+    const int c_last = c_hi - 1;  // (callers pass c_lo < c_hi or an empty range)
     if (K == 0) {
-        for (int c = c_lo + (int)threadIdx.x; c < c_hi; c += THREADS) {
-            const float4 t = zt4[c];
-            const uint4 rnd = philox4x32_10((uint32_t)c, (uint32_t)node, seq, c3, key);
-            const uint32_t wd[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
-            const float tz[4] = {t.x, t.y, t.z, t.w};
+        for (int c0 = c_lo + (int)threadIdx.x; c0 < c_hi; c0 += kBatch * THREADS) {
+            float4 tb[kBatch];
 #pragma unroll
-            for (int i = 0; i < 4; ++i) {
-                const float s = tz[i] * a.inv_t + gumbel_from_word(wd[i]);
-                if (better(s, (c << 2) + i, best_v, best_i)) { best_v = s; best_i = (c << 2) + i; }
+            for (int r = 0; r < kBatch; ++r) tb[r] = zt4[min(c0 + r * THREADS, c_last)];
+#pragma unroll
+            for (int r = 0; r < kBatch; ++r) {
+                const int c = c0 + r * THREADS;
+                if (c >= c_hi) break;
+                const float4 t = tb[r];
+                const uint4 rnd = philox4x32_10((uint32_t)c, (uint32_t)node, seq, c3, key);
+                const uint32_t wd[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
+                const float tz[4] = {t.x, t.y, t.z, t.w};
+#pragma unroll
+                for (int i = 0; i < 4; ++i) {
+                    const float s = tz[i] * a.inv_t + gumbel_from_word(wd[i]);
+                    if (better(s, (c << 2) + i, best_v, best_i)) { best_v = s; best_i = (c << 2) + i; }
+                }
             }
         }
         return;
@@ -924,43 +936,55 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
     const float gl_last = uniform_f((float)(g.gam[K - 1] - (double)(float)g.gam[K - 1]));
     const uint64_t hits = child_chunk_mask<THREADS>(g, c_lo, c_hi);
     int it = 0;
-    for (int c = c_lo + (int)threadIdx.x; c < c_hi; c += THREADS, ++it) {
-        const float4 t = zt4[c];
-        const float4 d = zd4[c];
-        const uint4 rnd = philox4x32_10((uint32_t)c, (uint32_t)node, seq, c3, key);
-        const uint32_t wd[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
-        const float tz[4] = {t.x, t.y, t.z, t.w}, dz[4] = {d.x, d.y, d.z, d.w};
-        float u[4], e[4];
-        bool f64[4];
-        const bool hit = (hits >> it) & 1ull;
+    for (int c0 = c_lo + (int)threadIdx.x; c0 < c_hi; c0 += kBatch * THREADS) {
+        float4 tb[kBatch], db[kBatch];
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const float at = exponent_of(tz[i], a.c2h, a.c2l, -cr.mt2);
-            const float ad = exponent_of(dz[i], a.c2h, a.c2l, -cr.md2);
-            // child tokens and heavy entries get the chain in fp64, from a thread of their own
-            f64[i] = at >= -kHeavy || ad >= -kHeavy || (hit && removal_stage((c << 2) + i, g.tok, K) < K);
-            u[i] = __builtin_amdgcn_exp2f(at);
-            e[i] = __builtin_amdgcn_exp2f(ad);
+        for (int r = 0; r < kBatch; ++r) {
+            const int c = min(c0 + r * THREADS, c_last);
+            tb[r] = zt4[c];
+            db[r] = zd4[c];
         }
-        chain4(u, e, cr, K - 1);  // ~ q^(K)
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-            const int x = (c << 2) + i;
-            float s, s2;
-            if (!f64[i]) {
-                const float gum = gumbel_from_word(wd[i]);
-                s2 = fast_ln(u[i]) + gum;
-                s = fast_ln(fmaxf(fmaf(-gl_last, e[i], fmaf(-gh_last, e[i], u[i])), 0.f)) + gum;
-            } else {
-                const int slot = atomicAdd(&fs.count, 1);
-                if (slot < kFinalHeavyCap) {
-                    fs.x[slot] = x;
-                    continue;
-                }
-                final_scores_f64(a, g, zt, zd, x, (uint32_t)node, seq, s, s2);  // (list full: in place)
+        for (int r = 0; r < kBatch; ++r, ++it) {
+            const int c = c0 + r * THREADS;
+            if (c >= c_hi) break;
+            const float4 t = tb[r];
+            const float4 d = db[r];
+            const uint4 rnd = philox4x32_10((uint32_t)c, (uint32_t)node, seq, c3, key);
+            const uint32_t wd[4] = {rnd.x, rnd.y, rnd.z, rnd.w};
+            const float tz[4] = {t.x, t.y, t.z, t.w}, dz[4] = {d.x, d.y, d.z, d.w};
+            float u[4], e[4];
+            bool f64[4];
+            const bool hit = (hits >> it) & 1ull;
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const float at = exponent_of(tz[i], a.c2h, a.c2l, -cr.mt2);
+                const float ad = exponent_of(dz[i], a.c2h, a.c2l, -cr.md2);
+                // child tokens and heavy entries get the chain in fp64, from a thread of their own
+                f64[i] = at >= -kHeavy || ad >= -kHeavy || (hit && removal_stage((c << 2) + i, g.tok, K) < K);
+                u[i] = __builtin_amdgcn_exp2f(at);
+                e[i] = __builtin_amdgcn_exp2f(ad);
             }
-            if (better(s, x, best_v, best_i)) { best_v = s; best_i = x; }
-            if (better(s2, x, alt_v, alt_i)) { alt_v = s2; alt_i = x; }
+            chain4(u, e, cr, K - 1);  // ~ q^(K)
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+                const int x = (c << 2) + i;
+                float s, s2;
+                if (!f64[i]) {
+                    const float gum = gumbel_from_word(wd[i]);
+                    s2 = fast_ln(u[i]) + gum;
+                    s = fast_ln(fmaxf(fmaf(-gl_last, e[i], fmaf(-gh_last, e[i], u[i])), 0.f)) + gum;
+                } else {
+                    const int slot = atomicAdd(&fs.count, 1);
+                    if (slot < kFinalHeavyCap) {
+                        fs.x[slot] = x;
+                        continue;
+                    }
+                    final_scores_f64(a, g, zt, zd, x, (uint32_t)node, seq, s, s2);  // (list full: in place)
+                }
+                if (better(s, x, best_v, best_i)) { best_v = s; best_i = x; }
+                if (better(s2, x, alt_v, alt_i)) { alt_v = s2; alt_i = x; }
+            }
         }
     }
     __syncthreads();
