@@ -446,34 +446,42 @@ def acceptance_pass(case, torch, binding, trials=8):
     """Acceptance of one level of K drafts at the root of every sequence, method against method on the
     same synthetic logit rows (the comparison of the paper's toy example and first experiment, here on
     a recipe instead of a trained model pair): recursive rejection sampling on K drafts drawn without
-    replacement, against K-SEQ (gamma = K) and multi-round rejection sampling on K i.i.d. drafts."""
+    replacement, against K-SEQ (gamma = K) and multi-round rejection sampling on K i.i.d. drafts.  K is
+    the workload's own first-level branching, plus a sweep over the number of drafts."""
     cfg = case["cfg"]
-    K = cfg["branching"][0] if cfg["sampler"] == "gumbel" else cfg["width"]
+    K_own = cfg["branching"][0] if cfg["sampler"] == "gumbel" else cfg["width"]
     zt, zd = case["zt"][:, 0].contiguous(), case["zd"][:, 0].contiguous()
     B, V = zt.shape
     dev = zt.device
-    rows3 = lambda t: torch.stack([t] + [t] * K, dim=1).contiguous()      # [B, K + 1, V]: only row 0 is read
-    zt3, zd3 = rows3(zt), rows3(zd)
-    parent = torch.tensor([[-1] + [0] * K] * B, dtype=torch.int32, device=dev)
-    n_nodes = torch.full((B,), K + 1, dtype=torch.int32, device=dev)
     seq = torch.arange(B, dtype=torch.int32, device=dev)
-    hits = dict(rrs=0, kseq=0, multiround=0)
-    for t in range(trials):
-        top = binding.gumbel_topk(zd, K, seq_id=seq, seed=99, step=t, want_scores=False)["tokens"]
-        tokens = torch.cat([torch.full((B, 1), -1, dtype=torch.int32, device=dev), top], dim=1).contiguous()
-        r = binding.recursive_reject(zd3, zt3, tokens, parent, n_nodes, mode=binding.MODE_PATH, seed=99, step=t,
-                                     diagnostics=False)
-        hits["rrs"] += int((r["n_accepted"] > 0).sum().item())
-        iid = torch.cat([binding.gumbel_topk(zd, 1, seq_id=seq, node_id=seq * 0 + 1000 + k, seed=99, step=t,
-                                             want_scores=False)["tokens"] for k in range(K)], dim=1).contiguous()
-        for name, method, gamma in (("kseq", binding.BASELINE_KSEQ, float(K)),
-                                    ("multiround", binding.BASELINE_MULTIROUND, 1.0)):
-            g = binding.baseline_verify(zd, zt, iid, method, gamma=gamma, seq_id=seq, seed=99, step=t)
-            hits[name] += int((g["accepted"] >= 0).sum().item())
-    n = B * trials
-    return dict(level_acceptance_synthetic=dict(K=K, trials=n, rrs_without_replacement=round(hits["rrs"] / n, 4),
-                                                kseq_gamma_K=round(hits["kseq"] / n, 4),
-                                                multiround=round(hits["multiround"] / n, 4)))
+
+    def rates(K):
+        rows3 = lambda t: torch.stack([t] + [t] * K, dim=1).contiguous()      # [B, K + 1, V]: only row 0 is read
+        zt3, zd3 = rows3(zt), rows3(zd)
+        parent = torch.tensor([[-1] + [0] * K] * B, dtype=torch.int32, device=dev)
+        n_nodes = torch.full((B,), K + 1, dtype=torch.int32, device=dev)
+        hits = dict(rrs=0, kseq=0, multiround=0)
+        for t in range(trials):
+            top = binding.gumbel_topk(zd, K, seq_id=seq, seed=99, step=t, want_scores=False)["tokens"]
+            tokens = torch.cat([torch.full((B, 1), -1, dtype=torch.int32, device=dev), top], dim=1).contiguous()
+            r = binding.recursive_reject(zd3, zt3, tokens, parent, n_nodes, mode=binding.MODE_PATH, seed=99, step=t,
+                                         diagnostics=False)
+            hits["rrs"] += int((r["n_accepted"] > 0).sum().item())
+            iid = torch.cat([binding.gumbel_topk(zd, 1, seq_id=seq, node_id=seq * 0 + 1000 + k, seed=99, step=t,
+                                                 want_scores=False)["tokens"] for k in range(K)], dim=1).contiguous()
+            for name, method, gamma in (("kseq", binding.BASELINE_KSEQ, float(K)),
+                                        ("multiround", binding.BASELINE_MULTIROUND, 1.0)):
+                g = binding.baseline_verify(zd, zt, iid, method, gamma=gamma, seq_id=seq, seed=99, step=t)
+                hits[name] += int((g["accepted"] >= 0).sum().item())
+        n = B * trials
+        return dict(K=K, trials=n, rrs_without_replacement=round(hits["rrs"] / n, 4),
+                    kseq_gamma_K=round(hits["kseq"] / n, 4), multiround=round(hits["multiround"] / n, 4))
+
+    own = rates(K_own)
+    own["by_number_of_drafts"] = [own if K == K_own else rates(K) for K in (1, 2, 4, 8, 16) if K <= V]
+    own["by_number_of_drafts"] = [{k: v for k, v in r.items() if k != "by_number_of_drafts"}
+                                  for r in own["by_number_of_drafts"]]
+    return dict(level_acceptance_synthetic=own)
 
 
 def filter_logits_pass(case, torch, binding, steps=5):
