@@ -451,8 +451,8 @@ struct NextGroup {
 
 // The next group's target row is staged in LDS while the current group is worked on, when LDS has
 // the room (no draft chunks there): one memory-to-LDS load per chunk, spread over the exponent
-// pass, so that the CU's vector memory path (64 B/clk: a row pair takes it 4096 cycles) is busy
-// under arithmetic instead of in front of it.
+// pass and the exponential pass, so that the CU's vector memory path (64 B/clk: a row pair takes
+// it 4096 cycles) is busy under arithmetic instead of in front of it.
 template <int CL, bool PIPE>
 constexpr bool stages_next_row() { return PIPE && CL == 0; }
 
@@ -806,7 +806,7 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
     // Nothing reads this group's rows any more: the next group's are requested here, under the
     // thresholds, the record's way to memory and the queue.
     if constexpr (PIPE) {
-            asm volatile("" : "+v"(nx.claim));
+        asm volatile("" : "+v"(nx.claim));
         const int64_t row = ((int64_t)nx.b * a.N + nx.node) * a.V;
         fetch_child_logits(a.zt + row, a.zd + row, a.V, nx.node, nx.cand);
         issue_row_loads<T, CH, CL, !STAGE, P, true>(a.zt + row, a.zd + row, a.V, tid, ut, edr, s_ed, nmask, pf);
