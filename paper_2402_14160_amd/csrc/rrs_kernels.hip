@@ -412,16 +412,16 @@ __device__ __forceinline__ void issue_row_loads(const float *zt, const float *zd
     for (int j = 0; j < CH; ++j) {
         const int c = min(j * T + tid, last) & chunk_mask;
         if constexpr (TARGET) {
-            const float4 t = zt4[c];
+            const float4 t = load_stream(zt4 + c);
             ut[4 * j + 0] = t.x; ut[4 * j + 1] = t.y; ut[4 * j + 2] = t.z; ut[4 * j + 3] = t.w;
         }
         if (j >= CL && j < P) {
             if constexpr (!P_DONE) {
-                const float4 d = zd4[c];
+                const float4 d = load_stream(zd4 + c);
                 pf[4 * j] = d.x; pf[4 * j + 1] = d.y; pf[4 * j + 2] = d.z; pf[4 * j + 3] = d.w;
             }
         } else if (j >= CL) {
-            const float4 d = zd4[c];
+            const float4 d = load_stream(zd4 + c);
             const int r = 4 * (j - CL);
             edr[r] = d.x; edr[r + 1] = d.y; edr[r + 2] = d.z; edr[r + 3] = d.w;
         }
@@ -431,7 +431,7 @@ __device__ __forceinline__ void issue_row_loads(const float *zt, const float *zd
 #pragma unroll
         for (int j = 0; j < CL; ++j)
             __builtin_amdgcn_global_load_lds((global_void *)(zd4 + (min(j * T + tid, last) & chunk_mask)),
-                                             (lds_void *)(s_ed + j * T + wave * kWave), 16, 0, 0);
+                                             (lds_void *)(s_ed + j * T + wave * kWave), 16, 0, kStreamPolicy);
     }
 }
 
@@ -597,7 +597,7 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
     // chunk c of the next item's target row, memory to LDS (this thread's slot)
     auto stage_chunk = [&](int c) {
         __builtin_amdgcn_global_load_lds((global_void *)(nzt4 + (min(c * T + tid, last) & nmask)),
-                                         (lds_void *)(s_nt + c * T + wave * kWave), 16, 0, 0);
+                                         (lds_void *)(s_nt + c * T + wave * kWave), 16, 0, kStreamPolicy);
     };
     // (chunk numbers are worked out again here rather than kept from the load loop)
     int tid_x = tid;
@@ -654,7 +654,7 @@ __device__ __forceinline__ void compute_group_res(const RrsArgs &a, int node, Ch
         if constexpr (STAGE) {
             if (CH / 2 + j < CH) stage_chunk(CH / 2 + j);
             if (j < P) {
-                const float4 nd = nzd4[min(j * T + tid, last) & nmask];
+                const float4 nd = load_stream(nzd4 + (min(j * T + tid, last) & nmask));
                 pf[4 * j] = nd.x; pf[4 * j + 1] = nd.y; pf[4 * j + 2] = nd.z; pf[4 * j + 3] = nd.w;
             }
         }
@@ -911,7 +911,7 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
         for (int c0 = c_lo + (int)threadIdx.x; c0 < c_hi; c0 += kBatch * THREADS) {
             float4 tb[kBatch];
 #pragma unroll
-            for (int r = 0; r < kBatch; ++r) tb[r] = zt4[min(c0 + r * THREADS, c_last)];
+            for (int r = 0; r < kBatch; ++r) tb[r] = load_stream(zt4 + min(c0 + r * THREADS, c_last));
 #pragma unroll
             for (int r = 0; r < kBatch; ++r) {
                 const int c = c0 + r * THREADS;
@@ -941,8 +941,8 @@ __device__ void final_sample_range(const RrsArgs &a, int b, int node, const Grou
 #pragma unroll
         for (int r = 0; r < kBatch; ++r) {
             const int c = min(c0 + r * THREADS, c_last);
-            tb[r] = zt4[c];
-            db[r] = zd4[c];
+            tb[r] = load_stream(zt4 + c);
+            db[r] = load_stream(zd4 + c);
         }
 #pragma unroll
         for (int r = 0; r < kBatch; ++r, ++it) {

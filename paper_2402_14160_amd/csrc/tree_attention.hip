@@ -121,6 +121,8 @@ __device__ __forceinline__ int swz(int r) {
     return (r >> 1) & 7;  // 8 chunks per row: two rows span the 64 banks
 }
 
+// (The K/V tile loads carry the non-temporal cache policy, kStreamPolicy: every K/V byte is used by
+// the workgroups of one (sequence, KV head) only, at about the same time.)
 // One 64-row tile of K and of V from global memory into LDS.  Wave w, instruction it fills
 // 64 consecutive chunk positions (4 or 8 rows); a lane fetches the chunk that belongs at its
 // position.  Rows at or beyond `limit` re-read the last valid row (finite data; their scores
@@ -140,8 +142,8 @@ __device__ __forceinline__ void stage_tile(const __bf16 *ksrc, const __bf16 *vsr
         const int c = (lane % DCH) ^ swz<D>(r);
         const int rs = min(row0 + r, limit - 1);
         const int64_t off = (int64_t)rs * stride + c * 8;
-        __builtin_amdgcn_global_load_lds((global_void *)(ksrc + off), (lds_void *)(kdst + rbase * D), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((global_void *)(vsrc + off), (lds_void *)(vdst + rbase * D), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_void *)(ksrc + off), (lds_void *)(kdst + rbase * D), 16, 0, kStreamPolicy);
+        __builtin_amdgcn_global_load_lds((global_void *)(vsrc + off), (lds_void *)(vdst + rbase * D), 16, 0, kStreamPolicy);
     }
 }
 
@@ -170,8 +172,8 @@ __device__ __forceinline__ void stage_tile_full(const char *ksrc, const char *vs
         const int rbase = (it * WAVES + wave_s) * RPI;
         const char *kb = ksrc + it * pass_bytes;  // wave-uniform
         const char *vb = vsrc + it * pass_bytes;
-        __builtin_amdgcn_global_load_lds((global_void *)(kb + lane_off), (lds_void *)(kdst + rbase * D), 16, 0, 0);
-        __builtin_amdgcn_global_load_lds((global_void *)(vb + lane_off), (lds_void *)(vdst + rbase * D), 16, 0, 0);
+        __builtin_amdgcn_global_load_lds((global_void *)(kb + lane_off), (lds_void *)(kdst + rbase * D), 16, 0, kStreamPolicy);
+        __builtin_amdgcn_global_load_lds((global_void *)(vb + lane_off), (lds_void *)(vdst + rbase * D), 16, 0, kStreamPolicy);
     }
 }
 

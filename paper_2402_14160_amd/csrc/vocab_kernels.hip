@@ -30,7 +30,7 @@ __global__ __launch_bounds__(THREADS) void lse_kernel(const float *__restrict__ 
     MaxSum acc{-INFINITY, 0.f};
 #pragma unroll 4
     for (int c = threadIdx.x; c < nchunk; c += THREADS) {
-        const float4 z = z4[c];
+        const float4 z = load_stream(z4 + c);
         const float a0 = z.x * c2, a1 = z.y * c2, a2 = z.z * c2, a3 = z.w * c2;
         const float mx = fmaxf(fmaxf(a0, a1), fmaxf(a2, a3));
         if (mx > acc.m) {
@@ -150,7 +150,7 @@ __global__ __launch_bounds__(kTopkThreads, (CH <= 8 && !WANT_LSE) ? 8 : 4) void 
     for (int j = 0; j < CH; ++j) {
         const int c = c0 + j * kTopkThreads + tid;
         float4 t = make_float4(-INFINITY, -INFINITY, -INFINITY, -INFINITY);
-        if (c < c1) t = z4[c];
+        if (c < c1) t = load_stream(z4 + c);
         val[j * 4 + 0] = t.x; val[j * 4 + 1] = t.y; val[j * 4 + 2] = t.z; val[j * 4 + 3] = t.w;
     }
     // ... then one chunk at a time, so that only one Philox block is live
