@@ -194,8 +194,9 @@ int32_t rsd_sbs_step_static(const float *logits, const float *sum_logprob,
  *           is the log of the sum of the bf16-rounded weights that multiply V (the sum
  *           `out` is normalised by), within 2^-8 relative of the exact sum.
  * Limits: bf16: D in {64, 128}; f32: D <= 256; N_max <= RSD_NODES_MAX;
- *   H_q % H_kv == 0; all tensors 16-byte aligned, prefix strides multiples of 8 (bf16)
- *   or 4 (f32).  Invalid parent values are clamped on the device (no fault).
+ *   H_q % H_kv == 0; scale positive and finite (else RSD_ERR_SHAPE); all tensors 16-byte
+ *   aligned, prefix strides multiples of 8 (bf16) or 4 (f32).  Invalid parent values are
+ *   clamped on the device (no fault).
  * Workspace: rsd_tree_attention_workspace_bytes(...) with the same num_splits.
  * ------------------------------------------------------------------------- */
 size_t rsd_tree_attention_workspace_bytes(int32_t dtype, int32_t B, int32_t H_q, int32_t H_kv,

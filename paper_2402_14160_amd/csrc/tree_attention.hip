@@ -260,12 +260,29 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     const __bf16 *kt = reinterpret_cast<const __bf16 *>(a.kt) + layer * a.lt + ((int64_t)bs * a.Hkv + kvh) * a.N * D;
     const __bf16 *vt = reinterpret_cast<const __bf16 *>(a.vt) + layer * a.lt + ((int64_t)bs * a.Hkv + kvh) * a.N * D;
 
+    // (a full prefix tile is staged from wave-uniform addresses plus one per-thread offset that
+    // never changes; ragged and tree tiles take the general path)
+    const int wave_s = __builtin_amdgcn_readfirstlane(wave);
+    const bool lean_stage = a.sp < (1 << 24);  // per-thread byte offset fits 32 bits
+    const uint32_t lane_off = stage_lane_offset<D, kAttnThreads>(lean_stage ? a.sp : 0);
+    const int64_t pass_bytes = (int64_t)(kAttnThreads / 64) * (64 / (D / 8)) * a.sp * 2;
+    const int64_t tile_bytes = (int64_t)kTile * a.sp * 2;
+    int64_t pre_off = (int64_t)t0 * tile_bytes;  // byte offset of the next prefix tile (staged in order)
     auto stage = [&](int u) {  // tile u of this block's schedule into buffer u & 1
         const int buf = u & 1;
-        if (u < npre)
-            stage_tile<D, kAttnThreads>(kp, vp, a.sp, (t0 + u) * kTile, plen, Ks + buf * kTile * D, Vs + buf * kTile * D);
-        else
-            stage_tile<D, kAttnThreads>(kt, vt, D, (u - npre) * kTile, n, Ks + buf * kTile * D, Vs + buf * kTile * D);
+        __bf16 *kd = Ks + buf * kTile * D, *vd = Vs + buf * kTile * D;
+        if (u < npre) {
+            const int row0 = (t0 + u) * kTile;
+            if (lean_stage && row0 + kTile <= plen)
+                stage_tile_full<D, kAttnThreads>(reinterpret_cast<const char *>(kp) + pre_off,
+                                                 reinterpret_cast<const char *>(vp) + pre_off, pass_bytes,
+                                                 lane_off, wave_s, kd, vd);
+            else
+                stage_tile<D, kAttnThreads>(kp, vp, a.sp, row0, plen, kd, vd);
+            pre_off += tile_bytes;
+        } else {
+            stage_tile<D, kAttnThreads>(kt, vt, D, (u - npre) * kTile, n, kd, vd);
+        }
     };
 
     floatx4 o[DT];
@@ -279,7 +296,14 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
     wait_tile_loads<0>();
     __syncthreads();
 
-    for (int u = 0; u < ntiles; ++u) {
+    // Full prefix tiles (nearly all of them) run a mask-free copy of the tile body; the ragged last
+    // prefix tile and the tree tiles the masked one.  The running maximum m (of scale * score, in
+    // log2 units) is only raised when some row of the wave exceeds it by more than kSlack16, so the
+    // common tile has no rescale of the accumulators; p <= 2^kSlack16 keeps bf16's relative precision.
+    constexpr float kSlack16 = 8.f;
+    const int nfull = min(max(plen / kTile - t0, 0), npre);
+    auto iteration = [&](int u, auto masked_tag) {
+        constexpr bool MASKED = decltype(masked_tag)::value;
         const int buf = u & 1;
         if (u + 1 < ntiles) stage(u + 1);  // lands while this tile is consumed
 
@@ -298,41 +322,50 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
             }
         }
 
-        // ---- scale, mask, online softmax ------------------------------------
-        const bool is_tree = u >= npre;
-        const int row0 = is_tree ? (u - npre) * kTile : (t0 + u) * kTile;
-        const int limit = is_tree ? n : plen;
-        uint64_t vis = ~0ull;
-        if (is_tree) vis = anc[qi * kAncWords + (u - npre)];
-        if (row0 + kTile > limit) {
-            const int nv = limit - row0;  // 1..63
-            vis &= (nv >= 64) ? ~0ull : ((1ull << nv) - 1ull);
-        }
+        // ---- mask, online softmax (scores stay unscaled until the exponent) -----
         float mx = -INFINITY;
-#pragma unroll
-        for (int t = 0; t < 4; ++t) {
-#pragma unroll
-            for (int r = 0; r < 4; ++r) {
-                const int kk = t * 16 + g * 4 + r;
-                float v = s[t][r] * a.scale_log2;
-                v = ((vis >> kk) & 1ull) ? v : -INFINITY;
-                s[t][r] = v;
-                mx = fmaxf(mx, v);
+        if constexpr (MASKED) {
+            const bool is_tree = u >= npre;
+            const int row0 = is_tree ? (u - npre) * kTile : (t0 + u) * kTile;
+            const int limit = is_tree ? n : plen;
+            uint64_t vis = ~0ull;
+            if (is_tree) vis = anc[qi * kAncWords + (u - npre)];
+            if (row0 + kTile > limit) {
+                const int nv = limit - row0;  // 1..63
+                vis &= (nv >= 64) ? ~0ull : ((1ull << nv) - 1ull);
             }
+#pragma unroll
+            for (int t = 0; t < 4; ++t) {
+#pragma unroll
+                for (int r = 0; r < 4; ++r) {
+                    const int kk = t * 16 + g * 4 + r;
+                    const float v = ((vis >> kk) & 1ull) ? s[t][r] : -INFINITY;
+                    s[t][r] = v;
+                    mx = fmaxf(mx, v);
+                }
+            }
+        } else {
+#pragma unroll
+            for (int t = 0; t < 4; ++t) mx = fmaxf(mx, fmaxf(fmaxf(s[t][0], s[t][1]), fmaxf(s[t][2], s[t][3])));
         }
         mx = fmaxf(mx, __shfl_xor(mx, 16, kWave));
         mx = fmaxf(mx, __shfl_xor(mx, 32, kWave));
-        const float m_new = fmaxf(m, mx);
-        const float m_use = (m_new == -INFINITY) ? 0.f : m_new;
-        const float alpha = exp2f(m - m_use);
+        mx *= a.scale_log2;  // (the scale is positive)
+        if (__any(mx > m + kSlack16)) {  // (m = -inf at the start: any finite score raises it)
+            const float m_new = fmaxf(m, mx);
+            const float m_to = (m_new == -INFINITY) ? 0.f : m_new;
+            const float alpha = exp2f(m - m_to);
+            m = m_new;
+            l *= alpha;
+#pragma unroll
+            for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
+        }
+        const float neg_ref = (m == -INFINITY) ? 0.f : -m;
 #pragma unroll
         for (int t = 0; t < 4; ++t) {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) s[t][r] = exp2f(s[t][r] - m_use);
+            for (int r = 0; r < 4; ++r) s[t][r] = __builtin_amdgcn_exp2f(fmaf(s[t][r], a.scale_log2, neg_ref));
         }
-        m = m_new;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) o[dt] *= alpha;
 
         // ---- O^T += V^T P^T ---------------------------------------------------
         bf16x8 pf[2];
@@ -341,7 +374,7 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
 #pragma unroll
             for (int e = 0; e < 8; ++e) pf[j][e] = (__bf16)s[2 * j + (e >> 2)][e & 3];
         }
-        l = l * alpha + rounded_sum(pf[0], pf[1]);
+        l += rounded_sum(pf[0], pf[1]);
         // lane (c16, g) of the A operand needs V[key][16 dt + c16] for the keys
         // 32 j + 16 a + 4 g + r (a = 0,1; r = 0..3): two transposing reads, in which this
         // lane loads row 32 j + 16 a + 4 g + c16 / 4, columns 16 dt + 4 (c16 % 4) .. + 3.
@@ -362,6 +395,11 @@ __global__ __launch_bounds__(kAttnThreads, 2) void tree_attn_bf16_kernel(AttnArg
 
         wait_tile_loads<0>();
         __syncthreads();
+    };
+    {
+        int u = 0;
+        for (; u < nfull; ++u) iteration(u, std::false_type{});
+        for (; u < ntiles; ++u) iteration(u, std::true_type{});
     }
 
     // ---- epilogue -----------------------------------------------------------
@@ -1000,6 +1038,7 @@ static int32_t attn_launch(const void *q, const void *k_prefix, const void *v_pr
     if (B < 0 || L < 1 || H_q < 1 || H_kv < 1 || H_q % H_kv || N_max < 1 || N_max > RSD_NODES_MAX ||
         P_max < 0 || num_splits < 0 || (int64_t)L * B > 65535)
         return RSD_ERR_SHAPE;
+    if (!(scale > 0.f) || !(scale < INFINITY)) return RSD_ERR_SHAPE;  // (row maxima are taken before scaling)
     if (dtype != RSD_DTYPE_BF16 && dtype != RSD_DTYPE_F32) return RSD_ERR_UNSUPPORTED;
     const int esz = dtype == RSD_DTYPE_BF16 ? 2 : 4;
     const int vec = 16 / esz;
