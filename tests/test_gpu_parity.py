@@ -369,6 +369,10 @@ def test_tree_attention_strided_prefix_and_bad_arguments():
         binding.tree_attention(q.to(d)[..., :96].contiguous(), None, None, kt.to(d)[..., :96].contiguous(),
                                vt.to(d)[..., :96].contiguous(), *args)
     assert e.value.code == -6
+    for bad_scale in (0.0, -0.1, float("inf"), float("nan")):       # row maxima are taken before scaling
+        with pytest.raises(binding.RsdError) as e:
+            binding.tree_attention(q.to(d), kp.to(d), vp.to(d), kt.to(d), vt.to(d), *args[:3], bad_scale)
+        assert e.value.code == -2
 
 
 # ------------------------------------------------------------- probability filtering
