@@ -327,11 +327,14 @@ def test_tree_attention_one_key_prefix_wide_rows():
     assert err < 1e-2
 
 
-def test_tree_attention_rising_scores():
-    """Scores that climb far above those of the first tile (by more than 64 in log2 units): blocks of
-    the 256-row kernel leave their fixed-reference pass and repeat with the running-maximum pass."""
-    say("attention bf16, scores rising by orders of magnitude along the prefix")
-    B, Hq, Hkv, N, D, P = 2, 8, 1, 40, 128, 320
+@pytest.mark.parametrize("Hq,Hkv", [(8, 1), (2, 2)])
+def test_tree_attention_rising_scores(Hq, Hkv):
+    """Scores that climb far above those of the first tile (by more than 64 in log2 units).  With eight
+    query heads per KV head (320 stacked rows) blocks of the 256-row kernel leave their fixed-reference
+    pass and repeat with the running-maximum pass; with one (40 rows) the 16-row kernel, which raises its
+    running maximum only past a slack, has to raise it again and again."""
+    say(f"attention bf16, scores rising by orders of magnitude along the prefix, {Hq} q / {Hkv} kv heads")
+    B, N, D, P = 2, 40, 128, 320
     rng = np.random.default_rng(11)
     q, kp, vp, kt, vt = workloads.make_qkv(B, Hq, Hkv, N, D, P, "bf16", 11)
     kp = kp.to(torch.float32)
