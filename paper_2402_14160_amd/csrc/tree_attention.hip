@@ -940,19 +940,27 @@ static int plan_segments(int dtype, int B, int Hq, int Hkv, int N, int P_max, in
         int s = requested;
         if (dtype != RSD_DTYPE_BF16) s = 1;
         if (s <= 0) {
-            // The number of splits that minimises (rounds of workgroups over the chip's slots, one
-            // or two per CU) x (tiles per split + about two tiles' worth of set-up), plus about two
-            // tiles for the merge launch once there is more than one split.  A split of fewer than
-            // four tiles costs more in set-up and merging than it gains.
+            // The number of splits that minimises the time of the launch in units of one tile of one
+            // workgroup: the workgroups run in rounds over the chip's slots (one or two per CU); a
+            // round takes tiles per split + about two tiles' worth of set-up, stretched when more
+            // workgroups stream at once than HBM feeds at full speed (about 410 of the 16-row and
+            // 128-row kernels, measured: a workgroup alone takes ~2 us per 32 KB tile, the chip
+            // delivers ~205 tiles per us); the merge launch costs about five tiles once there is
+            // more than one split.  A split of fewer than four tiles costs more in set-up and
+            // merging than it gains.
             const long blocks = (long)seg[i].row_blocks * Hkv * B;
             const long slots = seg[i].variant == kV32x8 ? 256 : 512;
+            const double fed = seg[i].variant == kV32x8 ? 1e9 : 410.0;  // (the 256-row kernel is bound by its arithmetic)
             int smax = tiles / 4 < kMaxSplits ? tiles / 4 : kMaxSplits;
             if (smax < 1) smax = 1;
             double best = 0.0;
             s = 1;
             for (int c = 1; c <= smax; ++c) {
-                const long rounds = (blocks * c + slots - 1) / slots;
-                const double cost = (double)rounds * ((double)tiles / c + 2.0) + (c > 1 ? 2.0 : 0.0);
+                const double per = (double)tiles / c + 2.0;
+                const long total = blocks * c, full_rounds = total / slots, last = total % slots;
+                double cost = (double)full_rounds * per * ((double)slots > fed ? (double)slots / fed : 1.0);
+                if (last > 0) cost += per * ((double)last > fed ? (double)last / fed : 1.0);
+                if (c > 1) cost += 5.0;
                 if (c == 1 || cost < best) {
                     best = cost;
                     s = c;
