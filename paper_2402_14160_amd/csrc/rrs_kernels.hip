@@ -57,10 +57,7 @@ constexpr int kLdsThreads = 512, kLdsChunks = 25, kLdsChunksInLds = 18;
 constexpr int kGroupWavesMax = 16;
 constexpr int kFinalThreads = 512;
 constexpr int kFinalSplitsMax = 8;
-#ifndef RSD_X_HEAVY
-#define RSD_X_HEAVY 4.f
-#endif
-constexpr float kHeavy = RSD_X_HEAVY;   // entries with exponent >= -kHeavy are followed in fp64
+constexpr float kHeavy = 4.f;   // entries with exponent >= -kHeavy are followed in fp64
 constexpr int kCandCap = 48;    // such entries per wave: lanes 16..63 (lanes 0..15 of wave 0: the children)
 
 // Per (sequence, node) record produced by the group pass, kept in workspace.
